@@ -1,0 +1,178 @@
+/*
+ * logquant.h - C ABI of the MI355X (gfx950) LogQuant decode hot path.
+ *
+ * LogQuant (arXiv 2503.19950) keeps a log-sparse set of past tokens at original
+ * precision (Algorithm 1, Sec. 2.5), quantizes every token that leaves that set
+ * to 2 bits (Fig. 6 caption, Sec. 2.3; INT2 and group size G in Sec. 3.1, keys
+ * per channel in Sec. 2.5), stores both regions one after the other without
+ * regard to token positions (Sec. 2.4, Eq. 3) and attends over both with one
+ * softmax (Eq. 2, with the 1/sqrt(d) of Eq. 6).
+ *
+ * Conventions for every entry point
+ *   - All buffer pointers are caller-owned DEVICE memory unless marked HOST.
+ *     The library never allocates, frees or synchronises; work is enqueued on
+ *     the given HIP stream (passed as void*, 0 = default stream).
+ *   - lq_config and lq_cache are HOST structs.  Token counts live in the host
+ *     struct (lock-step batch: every sequence has the same length) and are
+ *     updated synchronously by the call that changes them.
+ *   - Errors are return codes.  Argument and state errors are detected before
+ *     anything is enqueued and leave the cache untouched.
+ *   - T is the cache element type (fp16 or bf16); q, out, new tokens, scales
+ *     and zero-points are all of type T.
+ *
+ * Physical layouts.  Row order inside either region carries no meaning for
+ * attention (Eq. 3), so every buffer is stored in the order the decode kernel's
+ * 64-lane matrix instructions consume it; a lane then reads its operand with
+ * one contiguous 16-byte load.  With
+ *     bh    = b * Hkv + h                     (batch row b, kv head h)
+ *     NKC   = d / 32,  NNT = d / 16,  NGC = ceil(d / G),  CAP = 3W = 3*fp_budget/2
+ *     kperm(x) = 8*((x % 16) / 4) + 4*(x / 16) + (x % 4)          for 0 <= x < 32
+ * the element (slot t, channel c) of one (b, h) slice lives at:
+ *
+ *   k_fp[buf]   T     index (((bh*(CAP/16) + t/16)*NKC + c/32)*64 + 16*((c%32)/8) + t%16)*8 + c%8
+ *   v_fp[buf]   T     index (((bh*(CAP/32) + t/32)*NNT + c/16)*64 + 16*(k/8) + c%16)*8 + k%8,
+ *                     k = kperm(t % 32)
+ *   pos_fp[buf] i32   index b*CAP + t                     absolute position of fp slot t
+ *
+ *   k_codes     u32   word  ((bh*(q_capacity/32) + t/32)*64 + 16*((c%32)/8) + t%16)*NKC + o/2,
+ *                     o = ((t%32)/16)*NKC + c/32,
+ *                     bits [p, p+2) with p = 8*(o%2) + 2*((c%8)/2) + 16*(c%2)
+ *   v_codes     u32   word  ((bh*(q_capacity/32) + t/32)*64 + 16*(k/8) + c%16)*NKC + (c/16)/2,
+ *                     k = kperm(t % 32),
+ *                     bits [p, p+2) with p = 8*((c/16)%2) + 2*((k%8)/2) + 16*(k%2)
+ *   k_scale, k_zero   T   index (bh*(q_capacity/G) + t/G)*d + c      one per channel per G slots
+ *   v_scale, v_zero   T   index ((bh*(q_capacity/32) + t/32)*NGC + c/G)*32 + kperm(t % 32)
+ *   pos_q       i32   index b*q_capacity + t              absolute position of quantized slot t
+ *
+ * Slots 0..n_fp-1 of the fp region are in the logical order of Algorithm 1's
+ * list; slots 0..n_q-1 of the quantized region are in eviction order.  Content
+ * of slots beyond the counts is unspecified and never influences a result.
+ *
+ * Quantizer (one group of values x_i of type T; a reading, the paper prints no
+ * formula): zero z = min x_i (with -0 stored as +0); scale
+ * s = T((f32(max) - f32(min)) / 3) with IEEE fp32 subtract and divide and
+ * round-to-nearest-even to T; code_i = [x_i - z >= s/2] + [x_i - z >= 3s/2] +
+ * [x_i - z >= 5s/2] with the subtraction exact (fp64), all 0 when s == 0;
+ * dequantized value z + code_i * s.  Key groups: one channel, G consecutive
+ * quantized slots (G tokens evicted together).  Value groups: one slot, G
+ * consecutive channels, the last group shorter when G does not divide d.
+ */
+#ifndef LOGQUANT_H
+#define LOGQUANT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  LQ_OK = 0,
+  LQ_ERR_NULL = 1,        /* a required pointer is null                              */
+  LQ_ERR_SHAPE = 2,       /* inconsistent B/Hq/Hkv/d/fp_budget/group/q_capacity       */
+  LQ_ERR_UNSUPPORTED = 3, /* valid in the paper but not built: bits != 2, G not in
+                             {32,64,128}, G not dividing W, d not in {64,96,128}      */
+  LQ_ERR_CAPACITY = 4,    /* fp region or quantized region would overflow             */
+  LQ_ERR_STATE = 5,       /* call not allowed in the cache's current state            */
+  LQ_ERR_HIP = 6          /* the HIP runtime reported a launch error                  */
+} lq_status;
+
+typedef enum { LQ_F16 = 0, LQ_BF16 = 1 } lq_dtype;
+
+/* Immutable problem description (HOST). */
+typedef struct {
+  int32_t B;           /* batch rows                                                   */
+  int32_t Hq;          /* query heads; query head h reads kv head h / (Hq/Hkv)         */
+  int32_t Hkv;         /* kv heads, Hq % Hkv == 0                                      */
+  int32_t d;           /* head dimension, one of 64, 96, 128                           */
+  int32_t fp_budget;   /* F = 2W: fp tokens left after a compress; fp capacity is 3W   */
+  int32_t group;       /* G: quantization group size, 32/64/128, must divide W         */
+  int32_t bits;        /* 2                                                            */
+  int32_t dtype;       /* lq_dtype                                                     */
+  int32_t q_capacity;  /* max quantized slots per sequence; multiple of W and of 64    */
+} lq_config;
+
+/* Cache state (HOST struct, DEVICE buffers; layouts above). */
+typedef struct {
+  void     *k_fp[2];     /* two copies: compress reads buffer `cur`, writes the other  */
+  void     *v_fp[2];
+  int32_t  *pos_fp[2];
+  uint32_t *k_codes, *v_codes;
+  void     *k_scale, *k_zero, *v_scale, *v_zero;
+  int32_t  *pos_q;
+  int32_t   cur;         /* which fp buffer is live (0 or 1)                           */
+  int32_t   n_fp;        /* tokens in the fp region, 0..3W                             */
+  int32_t   n_q;         /* slots in the quantized region, multiple of W               */
+} lq_cache;
+
+/* Byte sizes of every buffer of lq_cache for a given config (HOST out). */
+typedef struct {
+  size_t k_fp, v_fp, pos_fp;            /* each of the two copies                      */
+  size_t k_codes, v_codes, k_meta, v_meta, pos_q; /* k_meta: k_scale and k_zero each   */
+  size_t workspace;                     /* logquant_workspace_bytes                    */
+} lq_sizes;
+
+/* Sizes of the buffers the caller has to provide.  Pure host arithmetic.
+ * Returns LQ_ERR_NULL / LQ_ERR_SHAPE / LQ_ERR_UNSUPPORTED for a bad config. */
+lq_status logquant_sizes(const lq_config *cfg, lq_sizes *out);
+
+/* Bytes of the scratch buffer `workspace` that compress and decode_attn take
+ * (partial softmax states of the context splits); 0 for an invalid config. */
+size_t logquant_workspace_bytes(const lq_config *cfg);
+
+/* Algorithm 1, the append branch: store n_new new tokens per sequence in fp
+ * slots n_fp .. n_fp+n_new-1 and record their absolute positions
+ * n_fp+n_q .. (every token ever appended is either in the fp region or in the
+ * quantized region, so that sum is the next position).
+ *   k_new, v_new : DEVICE [B][Hkv][n_new][d] T, row-major.
+ * Requires n_fp + n_new <= 3W (else LQ_ERR_CAPACITY).  On success n_fp += n_new.
+ * The caller runs logquant_compress when n_fp reaches 3W. */
+lq_status logquant_append(const lq_config *cfg, lq_cache *cache, const void *k_new,
+                          const void *v_new, int32_t n_new, void *stream);
+
+/* Algorithm 1, the filtering branch, plus the quantization of what it removes
+ * (Fig. 6 caption; Sec. 2.3).  Requires n_fp == 3W (else LQ_ERR_STATE) and
+ * n_q + W <= q_capacity (else LQ_ERR_CAPACITY).  For every sequence and kv head:
+ *   - logical fp rows 1,3,..,2W-1 are quantized with the quantizer above and
+ *     appended, in that order, as quantized slots n_q .. n_q+W-1 (codes, scales,
+ *     zero-points, positions);
+ *   - logical rows 0,2,..,2W-2 followed by rows 2W..3W-1 become rows 0..2W-1 of
+ *     the other fp buffer, which becomes the live one (cache->cur flips).
+ * On success n_fp = 2W, n_q += W.  `workspace` is not used at present and may
+ * be null. */
+lq_status logquant_compress(const lq_config *cfg, lq_cache *cache, void *workspace,
+                            void *stream);
+
+/* Decode attention, Eq. 2 with Eq. 6's scaling, over the whole cache:
+ *   out[b][h] = softmax_t( scale * q[b][h] . k_t ) applied to v_t,
+ * t running over the n_fp original-precision rows and the n_q dequantized rows
+ * of kv head h / (Hq/Hkv); one softmax over both regions (Sec. 2.4).  The 2-bit
+ * rows are dequantized in registers, never in memory.
+ *   q   : DEVICE [B][Hq][d] T          out : DEVICE [B][Hq][d] T
+ *   softmax_scale <= 0 selects 1/sqrt(d).
+ *   workspace : DEVICE, logquant_workspace_bytes(cfg) bytes, contents ignored.
+ * Requires n_fp + n_q >= 1 (else LQ_ERR_STATE).  The cache is not modified.
+ * Finite inputs only; |q . scale| is assumed to stay below fp16 range (65504). */
+lq_status logquant_decode_attn(const lq_config *cfg, const lq_cache *cache, const void *q,
+                               float softmax_scale, void *out, void *workspace,
+                               void *stream);
+
+/* Launch shape logquant_decode_attn would use for these counts (HOST out), so a
+ * harness can report bytes per launch; pure host arithmetic. */
+typedef struct {
+  int32_t blocks;           /* workgroups of the attention kernel                    */
+  int32_t waves_per_block;
+  int32_t splits;           /* context splits per (batch row, kv head)               */
+  int32_t fp_waves;         /* of splits*waves_per_block waves, those on the fp rows */
+  int64_t bytes_read;       /* cache bytes one call must read (codes, scales,
+                               zero-points, fp rows of live slots)                   */
+} lq_plan;
+lq_status logquant_decode_plan(const lq_config *cfg, int32_t n_fp, int32_t n_q, lq_plan *out);
+
+const char *logquant_status_string(lq_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LOGQUANT_H */

@@ -1,0 +1,108 @@
+"""2-bit group quantizer of the evicted tokens.  Test infrastructure only.
+
+The paper fixes the bit width (INT2), the group size G and the axis for keys
+("Key-per-channel", Sec. 2.5; G and INT2 in Sec. 3.1) but prints no formula.
+The reading used everywhere in this repository, for one group of values x_i
+held in the cache type T (fp16 or bf16):
+
+    zero  z = min_i x_i                      (an element of T; -0.0 stored as +0.0)
+    scale s = round_to_T( (f32(max) - f32(min)) / 3 )   one fp32 subtract, one
+            correctly rounded fp32 divide, one round-to-nearest-even to T
+    code_i = [d_i >= 0.5 s] + [d_i >= 1.5 s] + [d_i >= 2.5 s],  d_i = x_i - z in fp64
+             (round-half-up of d_i / s clamped to 0..3, written without a
+             division); all codes are 0 when s == 0
+    dequantized value  z + code_i * s        (fp64)
+
+The scale is the one place evaluated in fp32 on purpose: it is a stored
+parameter that has to be reproducible bit for bit.
+
+Grouping.  Keys: statistics run along the token axis, one group per channel
+per run of G tokens in the order the tokens were evicted.  Values: statistics
+run along the channel axis, one group per token per run of G channels, the last
+run shorter when G does not divide d (a reading: the paper is silent on values).
+"""
+import numpy as np
+
+
+def round_to_T(x, dtype):
+    """Round fp32 values to the nearest value of T (ties to even); result is
+    returned as fp32 holding exactly representable values."""
+    x = np.asarray(x, dtype=np.float32)
+    if dtype == "f16":
+        return x.astype(np.float16).astype(np.float32)
+    if dtype == "bf16":
+        bits = x.view(np.uint32).astype(np.uint64)
+        lsb = (bits >> np.uint64(16)) & np.uint64(1)
+        bits = (bits + np.uint64(0x7FFF) + lsb) & np.uint64(0xFFFF0000)
+        return bits.astype(np.uint32).view(np.float32).reshape(x.shape)
+    raise ValueError("dtype must be 'f16' or 'bf16'")
+
+
+def quantize_groups(x, dtype):
+    """Quantize every group along the LAST axis of x.
+
+    x : array [..., n] of values exactly representable in T.
+    Returns (codes uint8 [..., n], scale fp32 [...], zero fp32 [...]); scale and
+    zero hold values of T.
+    """
+    x32 = np.asarray(x, dtype=np.float32)
+    mn = x32.min(axis=-1)
+    mx = x32.max(axis=-1)
+    mn = np.where(mn == 0, np.float32(0.0), mn).astype(np.float32)  # -0.0 -> +0.0
+    diff = (mx.astype(np.float32) - mn).astype(np.float32)          # fp32 subtract
+    s = round_to_T((diff / np.float32(3.0)).astype(np.float32), dtype)
+    d = x32.astype(np.float64) - mn.astype(np.float64)[..., None]   # fp64 subtract
+    s64 = s.astype(np.float64)[..., None]
+    codes = ((d >= 0.5 * s64).astype(np.uint8)
+             + (d >= 1.5 * s64).astype(np.uint8)
+             + (d >= 2.5 * s64).astype(np.uint8))
+    codes = np.where(s64 == 0, np.uint8(0), codes).astype(np.uint8)
+    return codes, s, mn
+
+
+def quantize_keys(K_ev, G, dtype):
+    """Keys of one compress event, [W][d] in eviction order, W % G == 0.
+
+    Returns codes [W][d] uint8, scale [W/G][d], zero [W/G][d]."""
+    W, d = K_ev.shape
+    if W % G:
+        raise ValueError("group size must divide the number of evicted tokens")
+    x = np.asarray(K_ev, dtype=np.float32).reshape(W // G, G, d).transpose(0, 2, 1)
+    codes, s, z = quantize_groups(x, dtype)          # [W/G][d][G]
+    return codes.transpose(0, 2, 1).reshape(W, d), s, z
+
+
+def value_group_bounds(d, G):
+    """Channel runs of a value row: [(0,G), (G,2G), ..., (kG, d)]."""
+    return [(lo, min(lo + G, d)) for lo in range(0, d, G)]
+
+
+def quantize_values(V_ev, G, dtype):
+    """Values of one compress event, [W][d].
+
+    Returns codes [W][d] uint8, scale [W][ceil(d/G)], zero [W][ceil(d/G)]."""
+    W, d = V_ev.shape
+    bounds = value_group_bounds(d, G)
+    codes = np.zeros((W, d), dtype=np.uint8)
+    s = np.zeros((W, len(bounds)), dtype=np.float32)
+    z = np.zeros((W, len(bounds)), dtype=np.float32)
+    for j, (lo, hi) in enumerate(bounds):
+        c, sj, zj = quantize_groups(np.asarray(V_ev, dtype=np.float32)[:, lo:hi], dtype)
+        codes[:, lo:hi] = c
+        s[:, j] = sj
+        z[:, j] = zj
+    return codes, s, z
+
+
+def dequantize_keys(codes, scale, zero, G):
+    """x_hat[t][c] = zero[t//G][c] + codes[t][c] * scale[t//G][c], fp64."""
+    n, d = codes.shape
+    grp = np.arange(n) // G
+    return zero.astype(np.float64)[grp] + codes.astype(np.float64) * scale.astype(np.float64)[grp]
+
+
+def dequantize_values(codes, scale, zero, G):
+    """x_hat[t][c] = zero[t][c//G] + codes[t][c] * scale[t][c//G], fp64."""
+    n, d = codes.shape
+    grp = np.arange(d) // G
+    return zero.astype(np.float64)[:, grp] + codes.astype(np.float64) * scale.astype(np.float64)[:, grp]

@@ -1,0 +1,71 @@
+"""Pins for oracle/layout.py: the documented index functions are bijections onto
+their buffers and agree with hand-evaluated positions."""
+import numpy as np
+import pytest
+
+from oracle import layout
+
+
+@pytest.mark.parametrize("d", [64, 96, 128])
+def test_fp_index_functions_are_bijections(d):
+    cap = 96
+    t = np.arange(cap)[:, None]
+    c = np.arange(d)[None, :]
+    for fn in (layout.k_fp_index, layout.v_fp_index):
+        idx = np.broadcast_to(fn(t, c, d), (cap, d)).ravel()
+        assert sorted(idx.tolist()) == list(range(cap * d))
+
+
+@pytest.mark.parametrize("d", [64, 96, 128])
+def test_code_positions_are_a_bijection_onto_bit_pairs(d):
+    n = 128
+    t = np.arange(n)[:, None]
+    c = np.arange(d)[None, :]
+    for fn in (layout.k_code_word_bit, layout.v_code_word_bit):
+        w, b = fn(t, c, d)
+        assert (b % 2 == 0).all() and b.max() == 30
+        key = (np.broadcast_to(w, (n, d)) * 16 + np.broadcast_to(b, (n, d)) // 2).ravel()
+        assert sorted(key.tolist()) == list(range(n * d))      # every 2-bit field used once
+
+
+@pytest.mark.parametrize("d,G", [(128, 32), (128, 64), (96, 64), (64, 128)])
+def test_v_meta_bijection(d, G):
+    n = 96
+    ngc = -(-d // G)
+    idx = set()
+    for t in range(n):
+        for c in range(0, d, G):
+            idx.add(int(layout.v_meta_index(t, c, d, G)))
+    assert idx == set(range(n * ngc))
+
+
+def test_hand_evaluated_positions():
+    # kperm: 32 slots -> (lane group, element): x = 21 -> 8*((21%16)//4) + 4*(21//16) + 21%4 = 8+4+1
+    assert int(layout.kperm(21)) == 13 and sorted(layout.kperm(np.arange(32)).tolist()) == list(range(32))
+    d = 128
+    # key code of slot 53 (block 1, x = 21, upper 16-row tile, row 5), channel 77 (chunk 2, octet 1, i 5)
+    w, b = layout.k_code_word_bit(53, 77, d)
+    o = 1 * 4 + 2
+    assert int(w) == (1 * 64 + 16 * 1 + 5) * 4 + o // 2 and int(b) == 8 * (o % 2) + 2 * 2 + 16 * 1
+    # value code of slot 53 (k = 13: lane group 1, element 5), channel 77 (tile 4, column 13)
+    w, b = layout.v_code_word_bit(53, 77, d)
+    assert int(w) == (1 * 64 + 16 * 1 + 13) * 4 + 2 and int(b) == 8 * 0 + 2 * 2 + 16 * 1
+    assert int(layout.k_fp_index(53, 77, d)) == (((3 * 4 + 2) * 64) + 16 * 1 + 5) * 8 + 5
+    assert int(layout.v_fp_index(53, 77, d)) == (((1 * 8 + 4) * 64) + 16 * 1 + 13) * 8 + 5
+    assert int(layout.k_meta_index(53, 77, d, 32)) == 1 * 128 + 77
+    assert int(layout.v_meta_index(53, 77, d, 32)) == ((1 * 4 + 2) * 32) + 13
+
+
+@pytest.mark.parametrize("d", [96, 128])
+def test_pack_unpack_roundtrip(d):
+    rng = np.random.default_rng(0)
+    codes = rng.integers(0, 4, (160, d)).astype(np.uint8)
+    for which in ("k", "v"):
+        words = layout.pack_codes(codes, which)
+        assert words.shape == (160 // 32 * 64 * (d // 32),)
+        assert np.array_equal(layout.unpack_codes(words, which, 160, d), codes)
+    rows = rng.standard_normal((96, d)).astype(np.float32)
+    for which in ("k", "v"):
+        assert np.array_equal(layout.gather_fp(layout.scatter_fp(rows, which, 96), which, 96, d), rows)
+    meta = rng.standard_normal((64, -(-d // 64))).astype(np.float32)
+    assert np.array_equal(layout.gather_v_meta(layout.scatter_v_meta(meta, d, 64), 64, d, 64), meta)

@@ -1,0 +1,151 @@
+"""Pins for oracle/quantizer.py: 2-bit asymmetric min/max group quantizer
+(INT2, group size G: Sec. 3.1; keys per channel: Sec. 2.5; formula is a reading)."""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import quantizer as Q
+
+
+def _f16(vals):
+    return np.array(vals, dtype=np.float16).astype(np.float32)
+
+
+def _bf16(x):
+    return Q.round_to_T(np.asarray(x, np.float32), "bf16")
+
+
+def test_round_to_T_known_values():
+    # bf16: 8 significant bits.  1 + 2^-8 is a tie -> even (1.0); 1 + 3*2^-8 ties up to 1 + 2^-6
+    x = np.array([1.0, 1.0 + 2.0 ** -8, 1.0 + 2.0 ** -7, 1.0 + 3 * 2.0 ** -8, 3.14159274], np.float32)
+    want = np.array([1.0, 1.0, 1.0 + 2.0 ** -7, 1.0 + 2.0 ** -6, 3.140625], np.float32)
+    assert np.array_equal(Q.round_to_T(x, "bf16"), want)
+    # fp16: 11 significant bits: 1 + 2^-11 ties to 1.0, 2049 -> 2048, 2051 -> 2052
+    x = np.array([1.0 + 2.0 ** -11, 2049.0, 2051.0, 0.1], np.float32)
+    want = np.array([1.0, 2048.0, 2052.0, 0.0999755859375], np.float32)
+    assert np.array_equal(Q.round_to_T(x, "f16"), want)
+
+
+def test_tie_vectors_round_half_up():
+    # s = 1.5 exactly, values on the grid z + k*s
+    c, s, z = Q.quantize_groups(_f16([0, 4.5, 3, 1.5]), "f16")
+    assert s == 1.5 and z == 0 and c.tolist() == [0, 3, 2, 1]
+    # s = 1: every interior value is an exact tie; half-up gives 1,2,3 (half-even would give 0,2,2)
+    c, s, z = Q.quantize_groups(_f16([0, 3, 0.5, 1.5, 2.5]), "f16")
+    assert s == 1.0 and c.tolist() == [0, 3, 1, 2, 3]
+
+
+def test_exact_grid_reconstructs_exactly():
+    z, s = -2.5, 0.75
+    x = _f16([z, z + s, z + 2 * s, z + 3 * s, z + s, z])
+    c, ss, zz = Q.quantize_groups(x, "f16")
+    assert ss == s and zz == z and c.tolist() == [0, 1, 2, 3, 1, 0]
+    assert np.array_equal(zz + c * np.float64(ss), x.astype(np.float64))
+
+
+def test_constant_group_and_signed_zero():
+    c, s, z = Q.quantize_groups(_f16([1.25] * 8), "f16")
+    assert s == 0 and z == 1.25 and not c.any()
+    c, s, z = Q.quantize_groups(np.array([-0.0, 0.0, -0.0], np.float32), "f16")
+    assert s == 0 and not np.signbit(z) and not c.any()
+    c, s, z = Q.quantize_groups(np.array([-0.0, 3.0], np.float32), "f16")
+    assert not np.signbit(z) and s == 1.0 and c.tolist() == [0, 3]
+
+
+def _exact_reference(xs, dtype):
+    """Brute force in exact rational arithmetic, the scale taken from the
+    definition (correctly rounded fp32 quotient, then nearest-even to T)."""
+    fx = [Fraction(float(v)) for v in xs]
+    mn, mx = min(fx), max(fx)
+    # fp32 subtract: correctly rounded value of the exact difference
+    diff = _round_fraction_to_f32(mx - mn)
+    quo = _round_fraction_to_f32(Fraction(float(diff)) / 3)
+    s = Fraction(float(Q.round_to_T(np.float32(quo), dtype)))
+    codes = []
+    for v in fx:
+        dlt = v - mn
+        codes.append(0 if s == 0 else int(dlt >= s / 2) + int(dlt >= 3 * s / 2) + int(dlt >= 5 * s / 2))
+    return codes, s, mn
+
+
+def _round_fraction_to_f32(fr):
+    """Nearest fp32 to an exact rational, ties to even, by exact comparison."""
+    x = np.float32(float(fr))
+    lo = np.nextafter(x, np.float32(-np.inf), dtype=np.float32)
+    hi = np.nextafter(x, np.float32(np.inf), dtype=np.float32)
+    cands = [(abs(Fraction(float(c)) - fr), int(np.float32(c).view(np.uint32)) & 1, c)
+             for c in (x, lo, hi)]
+    return min(cands, key=lambda t: (t[0], t[1]))[2]
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_against_exact_rational_arithmetic(dtype):
+    rng = np.random.default_rng(7)
+    for trial in range(300):
+        n = int(rng.integers(2, 9))
+        scale = 10.0 ** rng.uniform(-3, 2)
+        x = Q.round_to_T((rng.standard_normal(n) * scale).astype(np.float32), dtype)
+        if trial % 5 == 0:      # grids with many exact ties
+            x = Q.round_to_T((rng.integers(0, 7, n) * 0.5).astype(np.float32), dtype)
+        codes, s, z = Q.quantize_groups(x, dtype)
+        rc, rs, rz = _exact_reference(x, dtype)
+        assert Fraction(float(s)) == rs and Fraction(float(z)) == rz
+        assert codes.tolist() == rc
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_invariants(dtype):
+    rng = np.random.default_rng(11)
+    x = Q.round_to_T(rng.standard_normal((500, 32)).astype(np.float32) * 3, dtype)
+    x[:, 5] *= 10
+    codes, s, z = Q.quantize_groups(x, dtype)
+    assert codes.min() == 0 and codes.max() == 3
+    rows = np.arange(x.shape[0])
+    assert (codes[rows, x.argmin(1)] == 0).all() and (codes[rows, x.argmax(1)] == 3).all()
+    order = np.argsort(x, axis=1, kind="stable")
+    assert (np.diff(np.take_along_axis(codes.astype(int), order, 1), axis=1) >= 0).all()   # monotone
+    xhat = z.astype(np.float64)[:, None] + codes * s.astype(np.float64)[:, None]
+    err = np.abs(xhat - x)
+    rng_ = (x.max(1) - x.min(1)).astype(np.float64)
+    bound = np.maximum(s / 2.0, rng_ - 3.0 * s)       # top bin may exceed s/2 when s was rounded down
+    assert (err <= bound[:, None] + 1e-300).all()
+    # with a scale that was not rounded down the bound is exactly s/2
+    ok = 3.0 * s.astype(np.float64) >= rng_
+    assert (err[ok] <= (s[ok] / 2.0)[:, None]).all()
+
+
+def test_key_and_value_grouping_axes():
+    rng = np.random.default_rng(3)
+    W, d, G = 64, 96, 32
+    K = Q.round_to_T(rng.standard_normal((W, d)).astype(np.float32), "f16")
+    kc, ks, kz = Q.quantize_keys(K, G, "f16")
+    assert kc.shape == (W, d) and ks.shape == (W // G, d)
+    # keys: statistics along tokens, per channel, per run of G tokens
+    for g in range(W // G):
+        for c in (0, 17, 95):
+            col = K[g * G:(g + 1) * G, c]
+            assert kz[g, c] == col.min()
+            c1, s1, _ = Q.quantize_groups(col, "f16")
+            assert ks[g, c] == s1 and (kc[g * G:(g + 1) * G, c] == c1).all()
+    # values: statistics along channels, per token; ragged tail when G does not divide d
+    G = 64
+    vc, vs, vz = Q.quantize_values(K, G, "f16")
+    assert vs.shape == (W, 2) and Q.value_group_bounds(d, G) == [(0, 64), (64, 96)]
+    for t in (0, 13, 63):
+        assert vz[t, 0] == K[t, :64].min() and vz[t, 1] == K[t, 64:].min()
+        c1, s1, _ = Q.quantize_groups(K[t, 64:], "f16")
+        assert vs[t, 1] == s1 and (vc[t, 64:] == c1).all()
+    # dequantization addresses the same groups
+    Kh = Q.dequantize_keys(kc, ks, kz, 32)
+    assert np.abs(Kh - K).max() <= (ks.max() / 2) * 1.0001 + 1e-3
+    Vh = Q.dequantize_values(vc, vs, vz, G)
+    t, c = 5, 70
+    assert Vh[t, c] == vz[t, 1].astype(np.float64) + vc[t, c] * vs[t, 1].astype(np.float64)
+    t, c = 40, 3
+    assert Kh[t, c] == kz[1, c].astype(np.float64) + kc[t, c] * ks[1, c].astype(np.float64)
+
+
+def test_quantize_keys_needs_divisible_window():
+    with pytest.raises(ValueError):
+        Q.quantize_keys(np.zeros((42, 8), np.float32), 32, "f16")
