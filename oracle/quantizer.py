@@ -5,7 +5,8 @@ The paper fixes the bit width (INT2), the group size G and the axis for keys
 The reading used everywhere in this repository, for one group of values x_i
 held in the cache type T (fp16 or bf16):
 
-    zero  z = min_i x_i                      (an element of T; -0.0 stored as +0.0)
+    zero  z = min_i x_i                      (an element of T; a minimum or maximum
+                                              equal to zero is taken as +0.0)
     scale s = round_to_T( (f32(max) - f32(min)) / 3 )   one fp32 subtract, one
             correctly rounded fp32 divide, one round-to-nearest-even to T
     code_i = [d_i >= 0.5 s] + [d_i >= 1.5 s] + [d_i >= 2.5 s],  d_i = x_i - z in fp64
@@ -49,6 +50,7 @@ def quantize_groups(x, dtype):
     mn = x32.min(axis=-1)
     mx = x32.max(axis=-1)
     mn = np.where(mn == 0, np.float32(0.0), mn).astype(np.float32)  # -0.0 -> +0.0
+    mx = np.where(mx == 0, np.float32(0.0), mx).astype(np.float32)  # (min/max do not order signed zeros)
     diff = (mx.astype(np.float32) - mn).astype(np.float32)          # fp32 subtract
     s = round_to_T((diff / np.float32(3.0)).astype(np.float32), dtype)
     d = x32.astype(np.float64) - mn.astype(np.float64)[..., None]   # fp64 subtract

@@ -1,0 +1,205 @@
+"""ctypes binding of liblogquant.so: argument marshalling only.
+
+The functions carry the names of the C entry points declared in
+include/logquant.h.  PyTorch appears only as the owner of device memory and of
+the HIP stream; every step of the path runs in the library's kernels.  There is
+no fallback: if the shared library is missing, importing this module fails.
+"""
+import ctypes as C
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "liblogquant.so")
+
+LQ_OK, LQ_ERR_NULL, LQ_ERR_SHAPE, LQ_ERR_UNSUPPORTED, LQ_ERR_CAPACITY, LQ_ERR_STATE, LQ_ERR_HIP = range(7)
+LQ_F16, LQ_BF16 = 0, 1
+
+
+class lq_config(C.Structure):
+    _fields_ = [("B", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("d", C.c_int32),
+                ("fp_budget", C.c_int32), ("group", C.c_int32), ("bits", C.c_int32),
+                ("dtype", C.c_int32), ("q_capacity", C.c_int32)]
+
+
+class lq_cache(C.Structure):
+    _fields_ = [("k_fp", C.c_void_p * 2), ("v_fp", C.c_void_p * 2), ("pos_fp", C.c_void_p * 2),
+                ("k_codes", C.c_void_p), ("v_codes", C.c_void_p),
+                ("k_scale", C.c_void_p), ("k_zero", C.c_void_p),
+                ("v_scale", C.c_void_p), ("v_zero", C.c_void_p),
+                ("pos_q", C.c_void_p),
+                ("cur", C.c_int32), ("n_fp", C.c_int32), ("n_q", C.c_int32)]
+
+
+class lq_sizes(C.Structure):
+    _fields_ = [(n, C.c_size_t) for n in ("k_fp", "v_fp", "pos_fp", "k_codes", "v_codes", "k_meta",
+                                          "v_meta", "pos_q", "workspace")]
+
+
+class lq_plan(C.Structure):
+    _fields_ = [("blocks", C.c_int32), ("waves_per_block", C.c_int32), ("splits", C.c_int32),
+                ("fp_waves", C.c_int32), ("bytes_read", C.c_int64)]
+
+
+EXPORTS = ("logquant_sizes", "logquant_workspace_bytes", "logquant_append", "logquant_compress",
+           "logquant_decode_attn", "logquant_decode_plan", "logquant_status_string")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError("liblogquant.so is not built: run `python -m paper_2503_19950_amd.build` "
+                      "(there is no fallback path)")
+_lib = C.CDLL(LIB_PATH)
+
+_lib.logquant_sizes.argtypes = [C.POINTER(lq_config), C.POINTER(lq_sizes)]
+_lib.logquant_sizes.restype = C.c_int
+_lib.logquant_workspace_bytes.argtypes = [C.POINTER(lq_config)]
+_lib.logquant_workspace_bytes.restype = C.c_size_t
+_lib.logquant_append.argtypes = [C.POINTER(lq_config), C.POINTER(lq_cache), C.c_void_p, C.c_void_p,
+                                 C.c_int32, C.c_void_p]
+_lib.logquant_append.restype = C.c_int
+_lib.logquant_compress.argtypes = [C.POINTER(lq_config), C.POINTER(lq_cache), C.c_void_p, C.c_void_p]
+_lib.logquant_compress.restype = C.c_int
+_lib.logquant_decode_attn.argtypes = [C.POINTER(lq_config), C.POINTER(lq_cache), C.c_void_p, C.c_float,
+                                      C.c_void_p, C.c_void_p, C.c_void_p]
+_lib.logquant_decode_attn.restype = C.c_int
+_lib.logquant_decode_plan.argtypes = [C.POINTER(lq_config), C.c_int32, C.c_int32, C.POINTER(lq_plan)]
+_lib.logquant_decode_plan.restype = C.c_int
+_lib.logquant_status_string.argtypes = [C.c_int]
+_lib.logquant_status_string.restype = C.c_char_p
+
+
+class LogQuantError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s: %s" % (where, logquant_status_string(status)))
+
+
+def _ptr(x):
+    """Device (or null) pointer of a torch tensor / int / None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()
+
+
+def _p(struct):
+    return C.byref(struct) if struct is not None else None
+
+
+def logquant_status_string(status):
+    return _lib.logquant_status_string(int(status)).decode()
+
+
+def logquant_sizes(cfg):
+    out = lq_sizes()
+    st = _lib.logquant_sizes(_p(cfg), C.byref(out))
+    if st != LQ_OK:
+        raise LogQuantError(st, "logquant_sizes")
+    return out
+
+
+def logquant_workspace_bytes(cfg):
+    return int(_lib.logquant_workspace_bytes(_p(cfg)))
+
+
+def logquant_append(cfg, cache, k_new, v_new, n_new, stream=0):
+    return _lib.logquant_append(_p(cfg), _p(cache), _ptr(k_new), _ptr(v_new), int(n_new), stream)
+
+
+def logquant_compress(cfg, cache, workspace=None, stream=0):
+    return _lib.logquant_compress(_p(cfg), _p(cache), _ptr(workspace), stream)
+
+
+def logquant_decode_attn(cfg, cache, q, softmax_scale, out, workspace, stream=0):
+    return _lib.logquant_decode_attn(_p(cfg), _p(cache), _ptr(q), float(softmax_scale), _ptr(out),
+                                     _ptr(workspace), stream)
+
+
+def logquant_decode_plan(cfg, n_fp, n_q):
+    out = lq_plan()
+    st = _lib.logquant_decode_plan(_p(cfg), int(n_fp), int(n_q), C.byref(out))
+    if st != LQ_OK:
+        raise LogQuantError(st, "logquant_decode_plan")
+    return out
+
+
+def make_config(B, Hq, Hkv, d, fp_budget, group, dtype, q_capacity, bits=2):
+    return lq_config(B, Hq, Hkv, d, fp_budget, group, bits, LQ_BF16 if dtype == "bf16" else LQ_F16,
+                     q_capacity)
+
+
+class DeviceCache:
+    """Owner of the device buffers of one lq_cache (torch tensors) plus the
+    workspace.  Only allocation and pointer bookkeeping happen here."""
+
+    def __init__(self, cfg, device="cuda:0", poison=False):
+        import torch
+        self.torch = torch
+        self.cfg = cfg
+        self.device = torch.device(device)
+        sz = logquant_sizes(cfg)
+        self.sizes = sz
+
+        def buf(nbytes):
+            t = torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=self.device)
+            t.fill_(0xFF if poison else 0)   # 0xFF..: NaN patterns in fp16/bf16
+            return t
+
+        self.k_fp = [buf(sz.k_fp), buf(sz.k_fp)]
+        self.v_fp = [buf(sz.v_fp), buf(sz.v_fp)]
+        self.pos_fp = [buf(sz.pos_fp), buf(sz.pos_fp)]
+        self.k_codes, self.v_codes = buf(sz.k_codes), buf(sz.v_codes)
+        self.k_scale, self.k_zero = buf(sz.k_meta), buf(sz.k_meta)
+        self.v_scale, self.v_zero = buf(sz.v_meta), buf(sz.v_meta)
+        self.pos_q = buf(sz.pos_q)
+        self.workspace = buf(sz.workspace)
+        c = lq_cache()
+        for i in range(2):
+            c.k_fp[i] = self.k_fp[i].data_ptr()
+            c.v_fp[i] = self.v_fp[i].data_ptr()
+            c.pos_fp[i] = self.pos_fp[i].data_ptr()
+        c.k_codes, c.v_codes = self.k_codes.data_ptr(), self.v_codes.data_ptr()
+        c.k_scale, c.k_zero = self.k_scale.data_ptr(), self.k_zero.data_ptr()
+        c.v_scale, c.v_zero = self.v_scale.data_ptr(), self.v_zero.data_ptr()
+        c.pos_q = self.pos_q.data_ptr()
+        c.cur = c.n_fp = c.n_q = 0
+        self.c = c
+
+    @property
+    def W(self):
+        return self.cfg.fp_budget // 2
+
+    def _stream(self):
+        return self.torch.cuda.current_stream(self.device).cuda_stream
+
+    def _check(self, st, where):
+        if st != LQ_OK:
+            raise LogQuantError(st, where)
+
+    def append(self, k_new, v_new):
+        """k_new, v_new: [B][Hkv][n][d] tensors of the cache dtype, contiguous."""
+        n = k_new.shape[2]
+        assert k_new.is_contiguous() and v_new.is_contiguous()
+        self._check(logquant_append(self.cfg, self.c, k_new, v_new, n, self._stream()), "logquant_append")
+
+    def compress(self):
+        self._check(logquant_compress(self.cfg, self.c, self.workspace, self._stream()), "logquant_compress")
+
+    def stream_in(self, K, V):
+        """Append [B][Hkv][n][d] rows with the eager trigger: compress whenever the
+        fp region reaches 3W rows.  Returns the number of compress events."""
+        n, i, ev, cap = K.shape[2], 0, 0, 3 * self.W
+        while i < n:
+            m = min(cap - self.c.n_fp, n - i)
+            self.append(K[:, :, i:i + m].contiguous(), V[:, :, i:i + m].contiguous())
+            i += m
+            if self.c.n_fp == cap:
+                self.compress()
+                ev += 1
+        return ev
+
+    def decode_attn(self, q, out=None, softmax_scale=0.0):
+        if out is None:
+            out = self.torch.empty_like(q)
+        self._check(logquant_decode_attn(self.cfg, self.c, q, softmax_scale, out, self.workspace,
+                                         self._stream()), "logquant_decode_attn")
+        return out

@@ -1,0 +1,167 @@
+// C ABI of the library: argument checks on the host, then kernel launches.
+// Every check happens before the first HIP call, so bad arguments are reported
+// on machines without a GPU as well.
+#include "lq_internal.h"
+
+namespace lq {
+
+lq_status make_shape(const lq_config* cfg, Shape* s) {
+  if (!cfg || !s) return LQ_ERR_NULL;
+  if (cfg->B <= 0 || cfg->Hq <= 0 || cfg->Hkv <= 0 || cfg->d <= 0 || cfg->fp_budget <= 0 ||
+      cfg->group <= 0 || cfg->q_capacity <= 0)
+    return LQ_ERR_SHAPE;
+  if (cfg->Hq % cfg->Hkv) return LQ_ERR_SHAPE;
+  if (cfg->fp_budget % 2) return LQ_ERR_SHAPE;
+  if (cfg->dtype != LQ_F16 && cfg->dtype != LQ_BF16) return LQ_ERR_SHAPE;
+  if (cfg->bits != 2) return LQ_ERR_UNSUPPORTED;
+  if (cfg->d != 64 && cfg->d != 96 && cfg->d != 128) return LQ_ERR_UNSUPPORTED;
+  if (cfg->group != 32 && cfg->group != 64 && cfg->group != 128) return LQ_ERR_UNSUPPORTED;
+  const int W = cfg->fp_budget / 2;
+  if (W % cfg->group) return LQ_ERR_UNSUPPORTED;  // ragged key groups are not built
+  if (cfg->q_capacity % W || cfg->q_capacity % 64) return LQ_ERR_SHAPE;
+  if ((int64_t)cfg->B * cfg->Hkv * (int64_t)cfg->q_capacity * cfg->d > ((int64_t)1 << 40))
+    return LQ_ERR_SHAPE;
+  s->B = cfg->B; s->Hq = cfg->Hq; s->Hkv = cfg->Hkv; s->d = cfg->d;
+  s->W = W; s->G = cfg->group; s->cap = 3 * W; s->qcap = cfg->q_capacity;
+  s->gh = cfg->Hq / cfg->Hkv;
+  s->nkc = cfg->d / 32; s->nnt = cfg->d / 16; s->ngc = (cfg->d + cfg->group - 1) / cfg->group;
+  s->bf16 = cfg->dtype == LQ_BF16;
+  return LQ_OK;
+}
+
+int max_splits(const Shape& s) {
+  const int bh = s.B * s.Hkv;
+  int m = (1024 + bh - 1) / bh;
+  if (m < 1) m = 1;
+  if (m > 256) m = 256;
+  return m;
+}
+
+int64_t cache_bytes_read(const Shape& s, int n_fp, int n_q) {
+  // per quantized slot: K codes d/4 + V codes d/4 bytes; key scale+zero 4d bytes
+  // per G slots; value scale+zero 4 bytes per channel group.
+  const int64_t q_bytes = (int64_t)n_q * (s.d / 2 + 4 * s.ngc) + (int64_t)(n_q / s.G) * 4 * s.d;
+  const int64_t fp_bytes = (int64_t)n_fp * 4 * s.d;
+  return (int64_t)s.B * s.Hkv * (q_bytes + fp_bytes);
+}
+
+static bool cache_ptrs_ok(const lq_cache* c) {
+  return c && c->k_fp[0] && c->k_fp[1] && c->v_fp[0] && c->v_fp[1] && c->pos_fp[0] &&
+         c->pos_fp[1] && c->k_codes && c->v_codes && c->k_scale && c->k_zero && c->v_scale &&
+         c->v_zero && c->pos_q;
+}
+
+static lq_status cache_state_ok(const Shape& s, const lq_cache* c) {
+  if (c->cur != 0 && c->cur != 1) return LQ_ERR_STATE;
+  if (c->n_fp < 0 || c->n_fp > s.cap) return LQ_ERR_STATE;
+  if (c->n_q < 0 || c->n_q > s.qcap || c->n_q % s.W) return LQ_ERR_STATE;
+  return LQ_OK;
+}
+
+}  // namespace lq
+
+using namespace lq;
+
+extern "C" {
+
+lq_status logquant_sizes(const lq_config* cfg, lq_sizes* out) {
+  if (!cfg || !out) return LQ_ERR_NULL;
+  Shape s;
+  lq_status st = make_shape(cfg, &s);
+  if (st != LQ_OK) return st;
+  const size_t bh = (size_t)s.B * s.Hkv;
+  out->k_fp = bh * s.cap * s.d * 2;
+  out->v_fp = out->k_fp;
+  out->pos_fp = (size_t)s.B * s.cap * 4;
+  out->k_codes = bh * s.qcap * s.d / 4;
+  out->v_codes = out->k_codes;
+  out->k_meta = bh * (s.qcap / s.G) * s.d * 2;
+  out->v_meta = bh * s.qcap * s.ngc * 2;
+  out->pos_q = (size_t)s.B * s.qcap * 4;
+  out->workspace = logquant_workspace_bytes(cfg);
+  return LQ_OK;
+}
+
+size_t logquant_workspace_bytes(const lq_config* cfg) {
+  Shape s;
+  if (make_shape(cfg, &s) != LQ_OK) return 0;
+  // per (b, kv head, split): gh * (d + 2) floats (o, m, l)
+  return (size_t)s.B * s.Hkv * max_splits(s) * s.gh * (s.d + 2) * sizeof(float);
+}
+
+lq_status logquant_append(const lq_config* cfg, lq_cache* cache, const void* k_new,
+                          const void* v_new, int32_t n_new, void* stream) {
+  if (!cfg || !cache || !k_new || !v_new) return LQ_ERR_NULL;
+  Shape s;
+  lq_status st = make_shape(cfg, &s);
+  if (st != LQ_OK) return st;
+  if (!cache_ptrs_ok(cache)) return LQ_ERR_NULL;
+  if ((st = cache_state_ok(s, cache)) != LQ_OK) return st;
+  if (n_new <= 0) return LQ_ERR_SHAPE;
+  if (cache->n_fp + n_new > s.cap) return LQ_ERR_CAPACITY;
+  if (launch_append(s, *cache, k_new, v_new, n_new, (hipStream_t)stream) != hipSuccess)
+    return LQ_ERR_HIP;
+  cache->n_fp += n_new;
+  return LQ_OK;
+}
+
+lq_status logquant_compress(const lq_config* cfg, lq_cache* cache, void* workspace, void* stream) {
+  (void)workspace;
+  if (!cfg || !cache) return LQ_ERR_NULL;
+  Shape s;
+  lq_status st = make_shape(cfg, &s);
+  if (st != LQ_OK) return st;
+  if (!cache_ptrs_ok(cache)) return LQ_ERR_NULL;
+  if ((st = cache_state_ok(s, cache)) != LQ_OK) return st;
+  if (cache->n_fp != s.cap) return LQ_ERR_STATE;
+  if (cache->n_q + s.W > s.qcap) return LQ_ERR_CAPACITY;
+  if (launch_compress(s, *cache, (hipStream_t)stream) != hipSuccess) return LQ_ERR_HIP;
+  cache->cur ^= 1;
+  cache->n_fp = 2 * s.W;
+  cache->n_q += s.W;
+  return LQ_OK;
+}
+
+lq_status logquant_decode_plan(const lq_config* cfg, int32_t n_fp, int32_t n_q, lq_plan* out) {
+  if (!cfg || !out) return LQ_ERR_NULL;
+  Shape s;
+  lq_status st = make_shape(cfg, &s);
+  if (st != LQ_OK) return st;
+  if (n_fp < 0 || n_fp > s.cap || n_q < 0 || n_q > s.qcap || n_q % s.W || n_fp + n_q < 1)
+    return LQ_ERR_STATE;
+  plan_decode(s, n_fp, n_q, out);
+  return LQ_OK;
+}
+
+lq_status logquant_decode_attn(const lq_config* cfg, const lq_cache* cache, const void* q,
+                               float softmax_scale, void* out, void* workspace, void* stream) {
+  if (!cfg || !cache || !q || !out || !workspace) return LQ_ERR_NULL;
+  Shape s;
+  lq_status st = make_shape(cfg, &s);
+  if (st != LQ_OK) return st;
+  if (!cache_ptrs_ok(cache)) return LQ_ERR_NULL;
+  if ((st = cache_state_ok(s, cache)) != LQ_OK) return st;
+  if (cache->n_fp + cache->n_q < 1) return LQ_ERR_STATE;
+  lq_plan plan;
+  plan_decode(s, cache->n_fp, cache->n_q, &plan);
+  if (!(softmax_scale > 0.f)) softmax_scale = 1.0f / sqrtf((float)s.d);
+  if (launch_decode_attn(s, *cache, q, softmax_scale, out, workspace, plan, (hipStream_t)stream) !=
+      hipSuccess)
+    return LQ_ERR_HIP;
+  return LQ_OK;
+}
+
+const char* logquant_status_string(lq_status s) {
+  switch (s) {
+    case LQ_OK: return "ok";
+    case LQ_ERR_NULL: return "null pointer";
+    case LQ_ERR_SHAPE: return "inconsistent shape";
+    case LQ_ERR_UNSUPPORTED: return "unsupported configuration";
+    case LQ_ERR_CAPACITY: return "capacity exceeded";
+    case LQ_ERR_STATE: return "call not allowed in this cache state";
+    case LQ_ERR_HIP: return "HIP launch error";
+  }
+  return "unknown status";
+}
+
+}  // extern "C"

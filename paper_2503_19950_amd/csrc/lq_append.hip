@@ -1,0 +1,35 @@
+// Append branch of Algorithm 1 (Sec. 2.5): new tokens go to the end of the
+// original-precision list.  The rows arrive row-major and are scattered into the
+// operand-ordered fp buffers (keys: 16-byte octets of channels; values: one
+// 2-byte element per channel into the token-interleaved tiles).
+#include "lq_device.h"
+#include "lq_internal.h"
+
+namespace lq {
+
+// grid (n_new, B*Hkv), block d/8 * 8 = d threads.
+__global__ void append_kernel(const uint16_t* __restrict__ k_new, const uint16_t* __restrict__ v_new,
+                              uint16_t* __restrict__ k_fp, uint16_t* __restrict__ v_fp,
+                              int32_t* __restrict__ pos_fp, int n_new, int n_fp, int pos0, int d,
+                              int cap, int Hkv) {
+  const int j = blockIdx.x;        // which new token
+  const int bh = blockIdx.y;
+  const int c = threadIdx.x;       // channel
+  const int t = n_fp + j;          // destination slot
+  const int64_t src = ((int64_t)bh * n_new + j) * d + c;
+  const int64_t slice = (int64_t)bh * cap * d;
+  k_fp[slice + k_fp_index(t, c, d >> 5)] = k_new[src];
+  v_fp[slice + v_fp_index(t, c, d >> 4)] = v_new[src];
+  if (c == 0 && bh % Hkv == 0) pos_fp[(bh / Hkv) * cap + t] = pos0 + j;
+}
+
+hipError_t launch_append(const Shape& s, const lq_cache& c, const void* k_new, const void* v_new,
+                         int n_new, hipStream_t st) {
+  dim3 grid(n_new, s.B * s.Hkv);
+  hipLaunchKernelGGL(append_kernel, grid, dim3(s.d), 0, st, (const uint16_t*)k_new,
+                     (const uint16_t*)v_new, (uint16_t*)c.k_fp[c.cur], (uint16_t*)c.v_fp[c.cur],
+                     c.pos_fp[c.cur], n_new, c.n_fp, c.n_fp + c.n_q, s.d, s.cap, s.Hkv);
+  return hipGetLastError();
+}
+
+}  // namespace lq

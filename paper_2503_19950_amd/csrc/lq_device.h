@@ -1,0 +1,53 @@
+// Device-side helpers shared by the gfx950 kernels: element type conversion and
+// the physical index functions documented in include/logquant.h.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+namespace lq {
+
+// ---- cache element type T, handled as raw 16-bit patterns --------------------
+template <bool BF16>
+__device__ __forceinline__ float t2f(uint16_t u) {
+  if constexpr (BF16) {
+    return __uint_as_float(static_cast<uint32_t>(u) << 16);
+  } else {
+    return __half2float(__ushort_as_half(u));
+  }
+}
+
+// fp32 -> T, round to nearest even (finite inputs).
+template <bool BF16>
+__device__ __forceinline__ uint16_t f2t(float x) {
+  if constexpr (BF16) {
+    uint32_t u = __float_as_uint(x);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return static_cast<uint16_t>(u >> 16);
+  } else {
+    return __half_as_ushort(__float2half_rn(x));
+  }
+}
+
+// ---- layouts (one (b,h) slice; offsets relative to the slice) ----------------
+__host__ __device__ __forceinline__ int kperm(int x) {
+  return 8 * ((x & 15) >> 2) + 4 * (x >> 4) + (x & 3);
+}
+__host__ __device__ __forceinline__ int kperm_inv(int k) {   // k = 8a + 4b + c -> 16b + 4a + c
+  return 16 * ((k >> 2) & 1) + 4 * (k >> 3) + (k & 3);
+}
+// element index of fp key (slot t, channel c); NKC = d/32
+__host__ __device__ __forceinline__ int64_t k_fp_index(int t, int c, int nkc) {
+  return ((((int64_t)(t >> 4) * nkc + (c >> 5)) * 64 + 16 * ((c & 31) >> 3) + (t & 15)) << 3) + (c & 7);
+}
+// element index of fp value (slot t, channel c); NNT = d/16
+__host__ __device__ __forceinline__ int64_t v_fp_index(int t, int c, int nnt) {
+  const int k = kperm(t & 31);
+  return ((((int64_t)(t >> 5) * nnt + (c >> 4)) * 64 + 16 * (k >> 3) + (c & 15)) << 3) + (k & 7);
+}
+// index of the v_scale / v_zero entry of (slot t, channel group gc)
+__host__ __device__ __forceinline__ int64_t v_meta_index(int t, int gc, int ngc) {
+  return ((int64_t)(t >> 5) * ngc + gc) * 32 + kperm(t & 31);
+}
+
+}  // namespace lq

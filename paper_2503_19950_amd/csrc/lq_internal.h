@@ -1,0 +1,33 @@
+// Host-side internals: validated shape bundle and kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/logquant.h"
+
+namespace lq {
+
+struct Shape {
+  int B, Hq, Hkv, d, W, G, cap, qcap, gh;  // gh = Hq/Hkv, cap = 3W
+  int nkc, nnt, ngc;                       // d/32, d/16, ceil(d/G)
+  bool bf16;
+};
+
+// Fills `s`; returns LQ_OK or the config error.  Pure host arithmetic.
+lq_status make_shape(const lq_config* cfg, Shape* s);
+
+// Upper bound on context splits per (b, kv head) that decode_attn may use.
+int max_splits(const Shape& s);
+
+// Bytes one decode step reads from the cache (live slots only).
+int64_t cache_bytes_read(const Shape& s, int n_fp, int n_q);
+
+// --- launchers (enqueue only) -------------------------------------------------
+hipError_t launch_append(const Shape& s, const lq_cache& c, const void* k_new, const void* v_new,
+                         int n_new, hipStream_t st);
+hipError_t launch_compress(const Shape& s, const lq_cache& c, hipStream_t st);
+hipError_t launch_decode_attn(const Shape& s, const lq_cache& c, const void* q, float scale,
+                              void* out, void* ws, const lq_plan& plan, hipStream_t st);
+void plan_decode(const Shape& s, int n_fp, int n_q, lq_plan* plan);
+
+}  // namespace lq

@@ -1,0 +1,112 @@
+"""Helpers of the GPU parity tests: build the same cache state through the C ABI
+(on the GPU) and through the oracle (on the CPU) and compare them."""
+import numpy as np
+
+from oracle import attention, layout
+from oracle.cache import SliceCache
+from paper_2503_19950_amd import inputs
+
+TOL = {"f16": 2e-3, "bf16": 1e-2}      # max-abs tolerance on attention outputs
+
+
+def torch_dtype(dtype):
+    import torch
+    return torch.bfloat16 if dtype == "bf16" else torch.float16
+
+
+def to_dev(x, dtype, device="cuda:0"):
+    """float32 numpy array of exact T values -> device tensor of type T."""
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(x)).to(device).to(torch_dtype(dtype))
+
+
+def make_wl(**kw):
+    wl = dict(B=1, Hq=4, Hkv=1, d=128, dtype="f16", G=32, F=64, dist="normal", v_outliers=False,
+              sinks=0, L=0)
+    wl.update(kw)
+    return wl
+
+
+def build_gpu(wl, seed_id, L, q_capacity=None, poison=False, b_list=None):
+    """Stream L tokens of workload `wl` through logquant_append / logquant_compress."""
+    from paper_2503_19950_amd import binding
+    W = wl["F"] // 2
+    if q_capacity is None:
+        q_capacity = max(64, -(-L // (2 * W)) * 2 * W)
+        while q_capacity % 64 or q_capacity % W:
+            q_capacity += W
+    cfg = binding.make_config(wl["B"], wl["Hq"], wl["Hkv"], wl["d"], wl["F"], wl["G"], wl["dtype"],
+                              q_capacity)
+    dc = binding.DeviceCache(cfg, poison=poison)
+    step = 3 * W * 8
+    for t0 in range(0, L, step):
+        t1 = min(L, t0 + step)
+        K, V = inputs.batch_kv(seed_id, t0, t1, wl)
+        dc.stream_in(to_dev(K, wl["dtype"]), to_dev(V, wl["dtype"]))
+    return dc
+
+
+def build_oracle(wl, seed_id, L, b, h):
+    c = SliceCache(wl["F"] // 2, wl["G"], wl["d"], wl["dtype"])
+    step = 1 << 15
+    for t0 in range(0, L, step):
+        K, V = inputs.slice_kv(seed_id, b, h, t0, min(L, t0 + step), wl)
+        c.append_block(K, V)
+    return c
+
+
+def _np(t, np_dtype):
+    return t.cpu().numpy().view(np_dtype)
+
+
+def check_state(dc, oc, wl, b, h):
+    """Bit-exact comparison of one (b, h) slice of the GPU cache with the oracle."""
+    d, G, dt = wl["d"], wl["G"], wl["dtype"]
+    W = wl["F"] // 2
+    cap, qcap = 3 * W, dc.cfg.q_capacity
+    nkc, ngc = d // 32, -(-d // G)
+    bh = b * wl["Hkv"] + h
+    cur = dc.c.cur
+    assert (dc.c.n_fp, dc.c.n_q) == (oc.n_fp, oc.n_q)
+    n_fp, n_q = oc.n_fp, oc.n_q
+    pos_fp = _np(dc.pos_fp[cur], np.int32)[b * cap:b * cap + n_fp]
+    assert pos_fp.tolist() == oc.pos_fp, "fp positions"
+    pos_q = _np(dc.pos_q, np.int32)[b * qcap:b * qcap + n_q]
+    assert pos_q.tolist() == oc.pos_q, "quantized positions"
+    for which, buf, rows in (("k", dc.k_fp[cur], oc.K_fp), ("v", dc.v_fp[cur], oc.V_fp)):
+        flat = _np(buf, np.uint16)[bh * cap * d:(bh + 1) * cap * d]
+        got = layout.gather_fp(flat, which, n_fp, d)
+        assert np.array_equal(got, inputs.to_bits16(rows, dt)), "fp rows " + which
+    if n_q == 0:
+        return
+    nw = n_q // 32 * 64 * nkc
+    for which, buf, codes in (("k", dc.k_codes, oc.K_codes), ("v", dc.v_codes, oc.V_codes)):
+        words = _np(buf, np.uint32)[bh * (qcap // 32) * 64 * nkc:][:nw]
+        want = layout.pack_codes(codes, which)
+        assert np.array_equal(words, want), "packed codes " + which
+    for buf, meta, name in ((dc.k_scale, oc.K_scale, "k_scale"), (dc.k_zero, oc.K_zero, "k_zero")):
+        got = _np(buf, np.uint16)[bh * (qcap // G) * d:][:n_q // G * d]
+        assert np.array_equal(got, inputs.to_bits16(meta, dt).ravel()), name
+    for buf, meta, name in ((dc.v_scale, oc.V_scale, "v_scale"), (dc.v_zero, oc.V_zero, "v_zero")):
+        got = _np(buf, np.uint16)[bh * (qcap // 32) * ngc * 32:][:n_q // 32 * ngc * 32]
+        want = layout.scatter_v_meta(inputs.to_bits16(meta, dt), d, G)
+        assert np.array_equal(got, want), name
+
+
+def check_attention(dc, oc_by_slice, wl, q_np, scale=0.0):
+    """Run logquant_decode_attn for the whole batch; compare the heads of the given
+    (b, h) slices with the oracle.  Returns the largest abs error seen."""
+    dt = wl["dtype"]
+    gh = wl["Hq"] // wl["Hkv"]
+    out = dc.decode_attn(to_dev(q_np, dt), softmax_scale=scale)
+    import torch
+    torch.cuda.synchronize()
+    out = out.float().cpu().numpy()
+    assert np.isfinite(out).all()
+    worst = 0.0
+    for (b, h), oc in oc_by_slice.items():
+        want = attention.decode_attention(oc, q_np[b, h * gh:(h + 1) * gh], scale if scale > 0 else None)
+        err = np.abs(out[b, h * gh:(h + 1) * gh] - want).max()
+        worst = max(worst, float(err))
+        assert err <= TOL[dt], "attention (b=%d,h=%d): max abs err %.3e > %.1e" % (b, h, err, TOL[dt])
+    return worst

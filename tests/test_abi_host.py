@@ -1,0 +1,107 @@
+"""CPU-side checks of the C ABI: the library loads, exports every declared symbol,
+and rejects bad arguments before touching the GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2503_19950_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "logquant.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(logquant_\w+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    syms = _declared_symbols()
+    assert set(syms) == set(B.EXPORTS)
+    lib = C.CDLL(B.LIB_PATH)
+    for s in syms:
+        assert getattr(lib, s) is not None
+
+
+def _cfg(**kw):
+    a = dict(B=1, Hq=32, Hkv=8, d=128, fp_budget=128, group=32, dtype="f16", q_capacity=1024)
+    a.update(kw)
+    return B.make_config(**a)
+
+
+def test_sizes_match_the_documented_layouts():
+    s = B.logquant_sizes(_cfg())
+    bh, cap, d, qc = 8, 192, 128, 1024
+    assert s.k_fp == s.v_fp == bh * cap * d * 2
+    assert s.k_codes == s.v_codes == bh * qc * d // 4
+    assert s.k_meta == bh * (qc // 32) * d * 2 and s.v_meta == bh * qc * 4 * 2
+    assert s.pos_fp == cap * 4 and s.pos_q == qc * 4
+    assert s.workspace == B.logquant_workspace_bytes(_cfg()) > 0
+    s = B.logquant_sizes(_cfg(d=96, group=64, Hq=8, Hkv=8, fp_budget=384, q_capacity=384 * 2))
+    assert s.v_meta == 8 * 768 * 2 * 2        # ceil(96/64) = 2 channel groups
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(bits=4), B.LQ_ERR_UNSUPPORTED),
+    (dict(d=80), B.LQ_ERR_UNSUPPORTED),
+    (dict(group=16), B.LQ_ERR_UNSUPPORTED),
+    (dict(fp_budget=84, q_capacity=42 * 64), B.LQ_ERR_UNSUPPORTED),   # the paper's W = 42: G does not divide W
+    (dict(Hq=30), B.LQ_ERR_SHAPE),
+    (dict(B=0), B.LQ_ERR_SHAPE),
+    (dict(q_capacity=1000), B.LQ_ERR_SHAPE),
+    (dict(fp_budget=127), B.LQ_ERR_SHAPE),
+])
+def test_bad_configs_are_rejected(kw, status):
+    cfg = _cfg(**kw)
+    out = B.lq_sizes()
+    assert B._lib.logquant_sizes(C.byref(cfg), C.byref(out)) == status
+    assert B.logquant_workspace_bytes(cfg) == 0
+    cache = B.lq_cache()
+    assert B.logquant_compress(cfg, cache) == status
+    plan = B.lq_plan()
+    assert B._lib.logquant_decode_plan(C.byref(cfg), 1, 0, C.byref(plan)) == status
+
+
+def test_null_and_state_errors_without_a_gpu():
+    cfg = _cfg()
+    cache = B.lq_cache()                       # all pointers null
+    assert B.logquant_compress(None, cache) == B.LQ_ERR_NULL
+    assert B.logquant_compress(cfg, None) == B.LQ_ERR_NULL
+    assert B.logquant_compress(cfg, cache) == B.LQ_ERR_NULL
+    assert B.logquant_append(cfg, cache, None, None, 1) == B.LQ_ERR_NULL
+    assert B.logquant_decode_attn(cfg, cache, None, 0.0, None, None) == B.LQ_ERR_NULL
+    # fake non-null pointers: the state checks run before anything is enqueued
+    for name, _ in B.lq_cache._fields_[3:10]:
+        setattr(cache, name, 4096)
+    for i in range(2):
+        cache.k_fp[i] = cache.v_fp[i] = cache.pos_fp[i] = 4096
+    cache.n_fp, cache.n_q = 10, 0
+    assert B.logquant_compress(cfg, cache) == B.LQ_ERR_STATE            # window not full
+    assert B.logquant_append(cfg, cache, 4096, 4096, 183) == B.LQ_ERR_CAPACITY
+    assert B.logquant_append(cfg, cache, 4096, 4096, 0) == B.LQ_ERR_SHAPE
+    cache.n_fp, cache.n_q = 192, 1024
+    assert B.logquant_compress(cfg, cache) == B.LQ_ERR_CAPACITY         # quantized region full
+    cache.n_fp, cache.n_q = 0, 0
+    assert B.logquant_decode_attn(cfg, cache, 4096, 0.0, 4096, 4096) == B.LQ_ERR_STATE   # empty cache
+    cache.n_q = 10
+    assert B.logquant_compress(cfg, cache) == B.LQ_ERR_STATE            # n_q not a multiple of W
+    assert cache.n_fp == 0 and cache.cur == 0                           # nothing was modified
+
+
+def test_plan_reports_the_algorithmic_bytes():
+    # cfg 1: 128 fp rows and 384 quantized rows per slice, 8 slices:
+    # 128*512 + 384*96 bytes each
+    p = B.logquant_decode_plan(_cfg(), 128, 384)
+    assert p.bytes_read == 8 * (128 * 512 + 384 * 96) == 819200
+    cfg3 = _cfg(fp_budget=512, group=64, dtype="bf16", q_capacity=131072)
+    assert B.logquant_decode_plan(cfg3, 512, 130560).bytes_read == 85655552
+    cfg5 = _cfg(B=16, Hq=32, Hkv=32, d=96, fp_budget=384, group=64, dtype="bf16", q_capacity=32256 + 192 * 2)
+    assert B.logquant_decode_plan(cfg5, 512, 32256).bytes_read == 1124597760
+    assert p.blocks >= 1 and p.splits >= 1
+
+
+def test_status_strings():
+    assert B.logquant_status_string(0) == "ok"
+    assert "capacity" in B.logquant_status_string(B.LQ_ERR_CAPACITY)

@@ -1,0 +1,94 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the
+same seeded inputs.  Integer results (positions, packed codes, scales, zero-points,
+fp rows) must match bit for bit; attention outputs within 2e-3 (fp16) / 1e-2 (bf16)
+max-abs of the oracle's fp64 result."""
+import numpy as np
+import pytest
+
+from paper_2503_19950_amd import inputs
+from tests import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+SMALL = [
+    # name, workload overrides, L
+    ("cfg1", dict(inputs.WORKLOADS[1]), 512),
+    ("mha_d96_g64_bf16_midwindow", U.make_wl(B=2, Hq=4, Hkv=4, d=96, G=64, F=128, dtype="bf16",
+                                             dist="laplace"), 700),
+    ("d64_gqa2_ragged", U.make_wl(B=2, Hq=4, Hkv=2, d=64, G=32, F=64), 333),
+    ("d128_g64_bf16_sinks", U.make_wl(B=1, Hq=8, Hkv=2, d=128, G=64, F=128, dtype="bf16",
+                                      v_outliers=True, sinks=4), 1000),
+    ("d128_g128_gqa8", U.make_wl(B=1, Hq=8, Hkv=1, d=128, G=128, F=256), 900),
+    ("gqa3_odd_ratio", U.make_wl(B=1, Hq=6, Hkv=2, d=128, G=32, F=64), 200),
+    ("all_fp_no_quantized_rows", U.make_wl(B=2, Hq=8, Hkv=2, d=128, G=32, F=128), 50),
+    ("single_token", U.make_wl(B=1, Hq=4, Hkv=1, d=128, G=32, F=64), 1),
+    ("exactly_at_event", U.make_wl(B=1, Hq=4, Hkv=1, d=128, G=32, F=64), 96),
+    ("one_before_event", U.make_wl(B=1, Hq=4, Hkv=1, d=128, G=32, F=64), 95),
+]
+
+
+@pytest.mark.parametrize("name,wl,L", SMALL, ids=[s[0] for s in SMALL])
+def test_small_cases_every_slice(name, wl, L):
+    seed_id = 100 + [s[0] for s in SMALL].index(name)
+    print("case", name, "L", L, flush=True)
+    dc = U.build_gpu(wl, seed_id, L)
+    ocs = {}
+    for b in range(wl["B"]):
+        for h in range(wl["Hkv"]):
+            oc = U.build_oracle(wl, seed_id, L, b, h)
+            U.check_state(dc, oc, wl, b, h)
+            ocs[(b, h)] = oc
+    q = inputs.queries(seed_id, 0, wl)
+    U.check_attention(dc, ocs, wl, q)
+    U.check_attention(dc, ocs, wl, q, scale=0.2)
+
+
+def test_single_token_output_is_its_value_row():
+    wl = U.make_wl(B=1, Hq=4, Hkv=1, d=128, G=32, F=64)
+    dc = U.build_gpu(wl, 150, 1)
+    _, V = inputs.slice_kv(150, 0, 0, 0, 1, wl)
+    q = inputs.queries(150, 0, wl)
+    out = dc.decode_attn(U.to_dev(q, "f16")).float().cpu().numpy()
+    assert np.array_equal(out[0], np.broadcast_to(V[0], (4, 128)))
+
+
+def test_slots_beyond_the_counts_do_not_matter():
+    """Unused capacity filled with NaN bit patterns must not change any output."""
+    wl = U.make_wl(B=1, Hq=8, Hkv=2, d=128, G=32, F=64)
+    q = U.to_dev(inputs.queries(160, 0, wl), "f16")
+    outs = []
+    for poison in (False, True):
+        dc = U.build_gpu(wl, 160, 237, q_capacity=1024, poison=poison)
+        outs.append(dc.decode_attn(q).cpu().view(dtype=__import__("torch").int16).numpy())
+    assert np.array_equal(outs[0], outs[1])
+
+
+def test_decode_does_not_modify_the_cache_and_is_repeatable():
+    import torch
+    wl = U.make_wl(B=2, Hq=8, Hkv=2, d=128, G=32, F=64)
+    dc = U.build_gpu(wl, 170, 400)
+    before = [t.clone() for t in (dc.k_fp[dc.c.cur], dc.v_fp[dc.c.cur], dc.k_codes, dc.v_codes,
+                                  dc.k_scale, dc.v_scale)]
+    q = U.to_dev(inputs.queries(170, 0, wl), "f16")
+    a = dc.decode_attn(q).clone()
+    b = dc.decode_attn(q)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+    after = (dc.k_fp[dc.c.cur], dc.v_fp[dc.c.cur], dc.k_codes, dc.v_codes, dc.k_scale, dc.v_scale)
+    assert all(torch.equal(x, y) for x, y in zip(before, after))
+
+
+def test_error_codes_with_live_device_buffers():
+    from paper_2503_19950_amd import binding as B
+    wl = U.make_wl(B=1, Hq=4, Hkv=1, d=128, G=32, F=64)
+    dc = U.build_gpu(wl, 180, 40, q_capacity=64)
+    assert B.logquant_compress(dc.cfg, dc.c) == B.LQ_ERR_STATE          # window not full
+    K, V = inputs.batch_kv(180, 40, 200, wl)
+    k, v = U.to_dev(K, "f16"), U.to_dev(V, "f16")
+    assert B.logquant_append(dc.cfg, dc.c, k, v, 160) == B.LQ_ERR_CAPACITY   # 40 + 160 > 96
+    assert dc.c.n_fp == 40
+    dc.stream_in(k[:, :, :88], v[:, :, :88])          # two events fill q_capacity = 64
+    assert (dc.c.n_fp, dc.c.n_q) == (64, 64)
+    dc.append(k[:, :, 88:120].contiguous(), v[:, :, 88:120].contiguous())
+    assert dc.c.n_fp == 96
+    assert B.logquant_compress(dc.cfg, dc.c) == B.LQ_ERR_CAPACITY       # quantized region is full
