@@ -8,6 +8,11 @@ no fallback: if the shared library is missing, importing this module fails.
 import ctypes as C
 import os
 
+# PyTorch ships its own HIP runtime.  It has to be in the process before the library
+# is loaded so that the library binds to that same runtime (matched by soname); two
+# HIP runtimes in one process cannot both open the GPU.
+import torch  # noqa: F401  (device memory and streams come from here as well)
+
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "liblogquant.so")
 

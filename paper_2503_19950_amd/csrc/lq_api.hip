@@ -1,6 +1,8 @@
 // C ABI of the library: argument checks on the host, then kernel launches.
 // Every check happens before the first HIP call, so bad arguments are reported
 // on machines without a GPU as well.
+#include <stdio.h>
+
 #include "lq_internal.h"
 
 namespace lq {
@@ -43,6 +45,12 @@ int64_t cache_bytes_read(const Shape& s, int n_fp, int n_q) {
   const int64_t q_bytes = (int64_t)n_q * (s.d / 2 + 4 * s.ngc) + (int64_t)(n_q / s.G) * 4 * s.d;
   const int64_t fp_bytes = (int64_t)n_fp * 4 * s.d;
   return (int64_t)s.B * s.Hkv * (q_bytes + fp_bytes);
+}
+
+hipError_t launch_status(const char* what) {
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) fprintf(stderr, "logquant: %s: %s\n", what, hipGetErrorString(e));
+  return e;
 }
 
 static bool cache_ptrs_ok(const lq_cache* c) {
@@ -99,6 +107,7 @@ lq_status logquant_append(const lq_config* cfg, lq_cache* cache, const void* k_n
   if ((st = cache_state_ok(s, cache)) != LQ_OK) return st;
   if (n_new <= 0) return LQ_ERR_SHAPE;
   if (cache->n_fp + n_new > s.cap) return LQ_ERR_CAPACITY;
+  clear_stale_error();
   if (launch_append(s, *cache, k_new, v_new, n_new, (hipStream_t)stream) != hipSuccess)
     return LQ_ERR_HIP;
   cache->n_fp += n_new;
@@ -115,6 +124,7 @@ lq_status logquant_compress(const lq_config* cfg, lq_cache* cache, void* workspa
   if ((st = cache_state_ok(s, cache)) != LQ_OK) return st;
   if (cache->n_fp != s.cap) return LQ_ERR_STATE;
   if (cache->n_q + s.W > s.qcap) return LQ_ERR_CAPACITY;
+  clear_stale_error();
   if (launch_compress(s, *cache, (hipStream_t)stream) != hipSuccess) return LQ_ERR_HIP;
   cache->cur ^= 1;
   cache->n_fp = 2 * s.W;
@@ -145,6 +155,7 @@ lq_status logquant_decode_attn(const lq_config* cfg, const lq_cache* cache, cons
   lq_plan plan;
   plan_decode(s, cache->n_fp, cache->n_q, &plan);
   if (!(softmax_scale > 0.f)) softmax_scale = 1.0f / sqrtf((float)s.d);
+  clear_stale_error();
   if (launch_decode_attn(s, *cache, q, softmax_scale, out, workspace, plan, (hipStream_t)stream) !=
       hipSuccess)
     return LQ_ERR_HIP;

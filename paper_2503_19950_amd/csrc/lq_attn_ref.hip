@@ -140,7 +140,7 @@ __global__ void combine_kernel(const float* __restrict__ ws, uint16_t* __restric
 hipError_t launch_combine(const Shape& s, const float* ws, void* out, int splits, hipStream_t st) {
   auto kern = s.bf16 ? combine_kernel<true> : combine_kernel<false>;
   hipLaunchKernelGGL(kern, dim3(s.B * s.Hq), dim3(s.d), 0, st, ws, (uint16_t*)out, s.d, s.gh, splits);
-  return hipGetLastError();
+  return launch_status(__func__);
 }
 
 template <bool BF16, int HB>
@@ -152,7 +152,7 @@ static hipError_t launch_ref_t(const Shape& s, const lq_cache& c, const void* q,
                      c.v_codes, (const uint16_t*)c.k_scale, (const uint16_t*)c.k_zero,
                      (const uint16_t*)c.v_scale, (const uint16_t*)c.v_zero, (float*)ws, s.d, s.G,
                      s.cap, s.qcap, c.n_fp, c.n_q, s.gh, splits, scale * 1.4426950408889634f);
-  return hipGetLastError();
+  return launch_status(__func__);
 }
 
 hipError_t launch_decode_attn_ref(const Shape& s, const lq_cache& c, const void* q, float scale,

@@ -198,13 +198,13 @@ hipError_t launch_compress(const Shape& s, const lq_cache& c, hipStream_t st) {
                      (const uint16_t*)c.v_fp[cur], c.pos_fp[cur], c.k_codes, c.v_codes,
                      (uint16_t*)c.k_scale, (uint16_t*)c.k_zero, (uint16_t*)c.v_scale,
                      (uint16_t*)c.v_zero, c.pos_q, s.d, s.G, s.cap, s.qcap, c.n_q, s.Hkv);
-  hipError_t e = hipGetLastError();
+  hipError_t e = launch_status(__func__);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(compact_kernel, dim3(2 * s.W / 32, s.B * s.Hkv), dim3(256), 0, st,
                      (const uint16_t*)c.k_fp[cur], (const uint16_t*)c.v_fp[cur], c.pos_fp[cur],
                      (uint16_t*)c.k_fp[alt], (uint16_t*)c.v_fp[alt], c.pos_fp[alt], s.d, s.W, s.cap,
                      s.Hkv);
-  return hipGetLastError();
+  return launch_status(__func__);
 }
 
 }  // namespace lq

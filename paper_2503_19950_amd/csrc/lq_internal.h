@@ -22,6 +22,12 @@ int max_splits(const Shape& s);
 // Bytes one decode step reads from the cache (live slots only).
 int64_t cache_bytes_read(const Shape& s, int n_fp, int n_q);
 
+// hipGetLastError() also reports failures of earlier, unrelated runtime calls made
+// by other code in the process (an expected hipErrorNotReady, say).  Launchers
+// clear that state first and report only what their own launch produced.
+inline void clear_stale_error() { (void)hipGetLastError(); }
+hipError_t launch_status(const char* what);
+
 // --- launchers (enqueue only) -------------------------------------------------
 hipError_t launch_append(const Shape& s, const lq_cache& c, const void* k_new, const void* v_new,
                          int n_new, hipStream_t st);

@@ -7,6 +7,7 @@ from oracle.cache import SliceCache
 from paper_2503_19950_amd import inputs
 
 TOL = {"f16": 2e-3, "bf16": 1e-2}      # max-abs tolerance on attention outputs
+HALF_ULP = {"f16": 2.0 ** -11, "bf16": 2.0 ** -8}   # worst relative half-ulp of the output type
 
 
 def torch_dtype(dtype):
@@ -93,9 +94,13 @@ def check_state(dc, oc, wl, b, h):
         assert np.array_equal(got, want), name
 
 
-def check_attention(dc, oc_by_slice, wl, q_np, scale=0.0):
+def check_attention(dc, oc_by_slice, wl, q_np, scale=0.0, large_outputs=False):
     """Run logquant_decode_attn for the whole batch; compare the heads of the given
-    (b, h) slices with the oracle.  Returns the largest abs error seen."""
+    (b, h) slices with the oracle.  Returns the largest abs error seen.
+
+    large_outputs: for inputs built to give outputs far above 1 the rounding of the
+    output to T alone exceeds the absolute tolerance; the bound then adds half an ulp
+    of the expected value."""
     dt = wl["dtype"]
     gh = wl["Hq"] // wl["Hkv"]
     out = dc.decode_attn(to_dev(q_np, dt), softmax_scale=scale)
@@ -106,7 +111,11 @@ def check_attention(dc, oc_by_slice, wl, q_np, scale=0.0):
     worst = 0.0
     for (b, h), oc in oc_by_slice.items():
         want = attention.decode_attention(oc, q_np[b, h * gh:(h + 1) * gh], scale if scale > 0 else None)
-        err = np.abs(out[b, h * gh:(h + 1) * gh] - want).max()
+        diff = np.abs(out[b, h * gh:(h + 1) * gh] - want)
+        err = diff.max()
         worst = max(worst, float(err))
-        assert err <= TOL[dt], "attention (b=%d,h=%d): max abs err %.3e > %.1e" % (b, h, err, TOL[dt])
+        if large_outputs:
+            assert (diff <= TOL[dt] + HALF_ULP[dt] * np.abs(want)).all(), "attention (b=%d,h=%d)" % (b, h)
+        else:
+            assert err <= TOL[dt], "attention (b=%d,h=%d): max abs err %.3e > %.1e" % (b, h, err, TOL[dt])
     return worst

@@ -17,7 +17,9 @@ SMALL = [
                                              dist="laplace"), 700),
     ("d64_gqa2_ragged", U.make_wl(B=2, Hq=4, Hkv=2, d=64, G=32, F=64), 333),
     ("d128_g64_bf16_sinks", U.make_wl(B=1, Hq=8, Hkv=2, d=128, G=64, F=128, dtype="bf16",
-                                      v_outliers=True, sinks=4), 1000),
+                                      sinks=4), 1000),
+    ("d128_g64_bf16_large_values", U.make_wl(B=1, Hq=8, Hkv=2, d=128, G=64, F=128, dtype="bf16",
+                                             v_outliers=True, sinks=4, sink_v=True), 1000),
     ("d128_g128_gqa8", U.make_wl(B=1, Hq=8, Hkv=1, d=128, G=128, F=256), 900),
     ("gqa3_odd_ratio", U.make_wl(B=1, Hq=6, Hkv=2, d=128, G=32, F=64), 200),
     ("all_fp_no_quantized_rows", U.make_wl(B=2, Hq=8, Hkv=2, d=128, G=32, F=128), 50),
@@ -39,8 +41,9 @@ def test_small_cases_every_slice(name, wl, L):
             U.check_state(dc, oc, wl, b, h)
             ocs[(b, h)] = oc
     q = inputs.queries(seed_id, 0, wl)
-    U.check_attention(dc, ocs, wl, q)
-    U.check_attention(dc, ocs, wl, q, scale=0.2)
+    big = bool(wl.get("v_outliers"))
+    U.check_attention(dc, ocs, wl, q, large_outputs=big)
+    U.check_attention(dc, ocs, wl, q, scale=0.2, large_outputs=big)
 
 
 def test_single_token_output_is_its_value_row():
