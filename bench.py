@@ -1,0 +1,239 @@
+#!/usr/bin/env python3
+"""Benchmark of the LogQuant decode hot path on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch: append the new token's
+K/V rows, run the filtering + 2-bit quantization + compaction when the
+original-precision window is full, then decode attention over both regions.
+Consecutive steps rotate over several independent copies of the cache (as the layers
+of a model would), so every step reads its cache from HBM rather than from the
+256 MB last-level cache.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=0, help="timed steps (default: one window W)")
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", type=int, default=3, help="1..5, see BASELINE.json configs")
+    ap.add_argument("--copies", type=int, default=0, help="cache copies to rotate over (0 = auto)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def build_states(wl, cfg_id, copies):
+    """Cache copy 0 is 5 tokens short of a full window (it fires one compress during
+    the timed region), the others have just been compressed: L tokens."""
+    import torch
+    from paper_2503_19950_amd import binding, inputs
+    from tests.gpu_util import to_dev
+    W, L, dt = wl["F"] // 2, wl["L"], wl["dtype"]
+    qcap = (L // W + 4) * W
+    while qcap % 64:
+        qcap += W
+    cfg = binding.make_config(wl["B"], wl["Hq"], wl["Hkv"], wl["d"], wl["F"], wl["G"], dt, qcap)
+    dc = binding.DeviceCache(cfg)
+    near = L - 5
+    step = 8 * 3 * W
+    t0 = 0
+    while t0 < near:
+        t1 = min(near, t0 + step)
+        K, V = inputs.batch_kv(cfg_id, t0, t1, wl)
+        dc.stream_in(to_dev(K, dt), to_dev(V, dt))
+        t0 = t1
+    first = dc.clone()
+    K, V = inputs.batch_kv(cfg_id, near, L, wl)
+    dc.stream_in(to_dev(K, dt), to_dev(V, dt))
+    caches = [first, dc] + [dc.clone() for _ in range(copies - 2)]
+    torch.cuda.synchronize()
+    return cfg, caches
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (the path shards by "
+              "kv head / batch row, see DESIGN.md)" % a.gpus, file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2503_19950_amd import binding, inputs
+    from tests.gpu_util import to_dev
+
+    wl = dict(inputs.WORKLOADS[a.workload])
+    W, L, dt = wl["F"] // 2, wl["L"], wl["dtype"]
+    steps = a.steps or W
+    plan0 = None
+    # enough copies that the rotation's footprint is >= 1 GiB (4x the 256 MB last-level cache)
+    cfg_probe = binding.make_config(wl["B"], wl["Hq"], wl["Hkv"], wl["d"], wl["F"], wl["G"], dt,
+                                    (L // W + 4) * W if ((L // W + 4) * W) % 64 == 0 else (L // W + 5) * W)
+    plan0 = binding.logquant_decode_plan(cfg_probe, 2 * W, (L - 2 * W) // W * W)
+    copies = a.copies or max(2, min(16, -(-(1 << 30) // max(1, plan0.bytes_read))))
+    t_build = time.time()
+    cfg, caches = build_states(wl, a.workload, copies)
+    t_build = time.time() - t_build
+
+    # per-step inputs: one new token per sequence and one query, seeded
+    n_in = steps + a.warmup
+    newK, newV = inputs.batch_kv(a.workload, L, L + n_in, wl)          # [B][Hkv][n_in][d]
+    # [n_in][B][Hkv][1][d]: step j's rows are one contiguous block
+    newK = to_dev(newK, dt).permute(2, 0, 1, 3).unsqueeze(3).contiguous()
+    newV = to_dev(newV, dt).permute(2, 0, 1, 3).unsqueeze(3).contiguous()
+    qs = to_dev(np.stack([inputs.queries(a.workload, s, wl) for s in range(n_in)]), dt)
+    out = torch.empty_like(qs[0])
+    stream = torch.cuda.current_stream()
+    sh = stream.cuda_stream
+
+    def run(n, record):
+        """n steps; returns per-kernel event pairs when record is True."""
+        ev = []
+        n_compress = 0
+        visits = [0] * len(caches)
+        for s in range(n):
+            i = s % len(caches)
+            dc = caches[i]
+            j = visits[i]
+            visits[i] += 1
+            st = binding.logquant_append(cfg, dc.c, newK[j], newV[j], 1, sh)
+            assert st == 0, binding.logquant_status_string(st)
+            if dc.c.n_fp == 3 * W:
+                if record:
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(stream)
+                st = binding.logquant_compress(cfg, dc.c, dc.workspace, sh)
+                assert st == 0, binding.logquant_status_string(st)
+                n_compress += 1
+                if record:
+                    e1.record(stream)
+                    ev.append(("compress", e0, e1, 0))
+            if record:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                nbytes = binding.logquant_decode_plan(cfg, dc.c.n_fp, dc.c.n_q).bytes_read
+                e0.record(stream)
+            st = binding.logquant_decode_attn(cfg, dc.c, qs[s], 0.0, out, dc.workspace, sh)
+            assert st == 0, binding.logquant_status_string(st)
+            if record:
+                e1.record(stream)
+                ev.append(("attn", e0, e1, nbytes))
+        return ev, n_compress
+
+    saved = [dc.counts() for dc in caches]
+    run(a.warmup, False)
+    torch.cuda.synchronize()
+    for dc, c in zip(caches, saved):
+        dc.set_counts(c)
+
+    # timed region 1: the whole hot path, K steps, wall clock
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    _, n_compress = run(steps, False)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / steps
+    for dc, c in zip(caches, saved):
+        dc.set_counts(c)
+
+    # timed region 2: the same K steps with HIP events around every attention / compress
+    # launch (same stream), for the per-kernel durations the roofline is computed from
+    ev, _ = run(steps, True)
+    torch.cuda.synchronize()
+    attn = [(e0.elapsed_time(e1) * 1e3, nb) for k, e0, e1, nb in ev if k == "attn"]
+    comp = [e0.elapsed_time(e1) * 1e3 for k, e0, e1, nb in ev if k == "compress"]
+    attn_us = float(np.mean([t for t, _ in attn]))
+    attn_bytes = float(np.mean([nb for _, nb in attn]))
+    achieved = attn_bytes / (attn_us * 1e-6) / 1e9
+
+    # back-to-back attention launches only (no appends in between), rotating copies
+    for dc, c in zip(caches, saved):
+        dc.set_counts(c)
+    nb2b = 200
+    for s in range(20):
+        binding.logquant_decode_attn(cfg, caches[s % len(caches)].c, qs[0], 0.0, out,
+                                     caches[s % len(caches)].workspace, sh)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for s in range(nb2b):
+        dc = caches[s % len(caches)]
+        binding.logquant_decode_attn(cfg, dc.c, qs[0], 0.0, out, dc.workspace, sh)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    b2b_us = e0.elapsed_time(e1) * 1e3 / nb2b
+    b2b_bytes = float(np.mean([binding.logquant_decode_plan(cfg, dc.c.n_fp, dc.c.n_q).bytes_read
+                               for dc in caches]))
+
+    plan = binding.logquant_decode_plan(cfg, caches[1].c.n_fp, caches[1].c.n_q)
+    result = {
+        "metric": "decode-attn effective KV tokens/sec",
+        "value": wl["B"] * L / (ms_per_step * 1e-3),
+        "unit": "KV tokens/s",
+        "n_gpus": 1, "steps": steps, "warmup": a.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": dt, "data": "synthetic",
+        "config": {"workload": wl["name"], "B": wl["B"], "Hq": wl["Hq"], "Hkv": wl["Hkv"],
+                   "d": wl["d"], "L": L, "group": wl["G"], "fp_budget": wl["F"], "bits": 2,
+                   "cache_copies_rotated": len(caches), "compress_events_in_timed_region": n_compress,
+                   "attn_blocks": plan.blocks, "attn_splits": plan.splits},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "decode attention", "us_per_launch": attn_us,
+                     "algorithmic_bytes_per_launch": attn_bytes,
+                     "back_to_back_us_per_launch": b2b_us,
+                     "back_to_back_GBs": b2b_bytes / (b2b_us * 1e-6) / 1e9},
+        "compress_us_per_call": float(np.mean(comp)) if comp else None,
+        "token_heads_per_s": wl["B"] * wl["Hkv"] * L / (ms_per_step * 1e-3),
+        "state_build_s": t_build,
+    }
+    if not a.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(wl, a.workload)
+    print(json.dumps(result), flush=True)
+
+
+def cpu_baseline(wl, cfg_id):
+    """The oracle's decode attention, as it stands, on a bounded sample of the same
+    workload: a few (batch row, kv head) slices at the full context length."""
+    import numpy as np
+    from oracle import attention
+    from tests.gpu_util import build_oracle
+    from paper_2503_19950_amd import inputs
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count()
+    gh = wl["Hq"] // wl["Hkv"]
+    q = inputs.queries(cfg_id, 0, wl)
+    t_total, n_slices = 0.0, 0
+    budget_s = 12.0
+    t_begin = time.perf_counter()
+    for h in range(wl["Hkv"]):
+        oc = build_oracle(wl, cfg_id, wl["L"], 0, h)          # state building is not timed
+        best = None
+        for _ in range(2):
+            t0 = time.perf_counter()
+            attention.decode_attention(oc, q[0, h * gh:(h + 1) * gh])
+            dt_ = time.perf_counter() - t0
+            best = dt_ if best is None else min(best, dt_)
+        t_total += best
+        n_slices += 1
+        if time.perf_counter() - t_begin > budget_s:
+            break
+    per_slice = t_total / n_slices
+    whole = per_slice * wl["B"] * wl["Hkv"]
+    return {"value": wl["B"] * wl["L"] / whole, "unit": "KV tokens/s", "cores": int(cores),
+            "kind": "oracle",
+            "sample": "%d of %d (batch row, kv head) slices at L=%d, decode attention only, best of 2 "
+                      "each, extrapolated to the whole batch" % (n_slices, wl["B"] * wl["Hkv"], wl["L"])}
+
+
+if __name__ == "__main__":
+    main()

@@ -169,6 +169,27 @@ class DeviceCache:
         c.cur = c.n_fp = c.n_q = 0
         self.c = c
 
+    BUFFERS = ("k_codes", "v_codes", "k_scale", "k_zero", "v_scale", "v_zero", "pos_q")
+
+    def clone(self):
+        """A second cache with its own device buffers and the same contents/counts."""
+        other = DeviceCache(self.cfg, device=self.device)
+        for i in range(2):
+            other.k_fp[i].copy_(self.k_fp[i])
+            other.v_fp[i].copy_(self.v_fp[i])
+            other.pos_fp[i].copy_(self.pos_fp[i])
+        for name in self.BUFFERS:
+            getattr(other, name).copy_(getattr(self, name))
+        other.c.cur, other.c.n_fp, other.c.n_q = self.c.cur, self.c.n_fp, self.c.n_q
+        return other
+
+    def counts(self):
+        return (self.c.cur, self.c.n_fp, self.c.n_q)
+
+    def set_counts(self, counts):
+        """Rewind the host-side counts (the device buffers are left as they are)."""
+        self.c.cur, self.c.n_fp, self.c.n_q = counts
+
     @property
     def W(self):
         return self.cfg.fp_budget // 2
