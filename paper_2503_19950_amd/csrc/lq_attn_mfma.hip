@@ -13,10 +13,16 @@
 //            -> p_t vs_t (one per token and channel group) is the A operand, the
 //               code tile the B operand; sum_t p_t vz_t is kept per channel group.
 //
-// A 2-bit code sits in the low mantissa bits of an fp16 lane of the operand, i.e.
-// it is the subnormal number code * 2^-24; gfx950's matrix cores take subnormal
-// operands exactly, so unpacking is a shift and a mask for two codes at a time and
-// needs no integer-to-float conversion.
+// Codes as operands.  An fp16 lane whose only set bits are mantissa bits 2v, 2v+1 is
+// the subnormal number code * 2^(2v-24); gfx950's matrix cores take subnormal
+// operands exactly.  The packed layout puts the eight codes a lane feeds to one
+// matrix instruction into one byte of the low and one byte of the high half of a
+// 32-bit word, so four ANDs (plus one shift by 8 for the odd operand of a word)
+// produce the four operand registers: 9 VALU instructions per 16 codes, no
+// integer-to-float conversion.  The factor 2^(2v) that depends on the position v
+// of a code inside its byte is cancelled in the other operand: q is pre-multiplied
+// by 2^(3-2v) per channel, and the probabilities by the same factor per token slot
+// (folded into the exponent of exp2, so it costs nothing).
 //
 // The up to four query heads that share a kv head occupy four of the 16 columns of
 // the logits tile; the other twelve columns repeat them for three more 16-token
@@ -38,6 +44,7 @@ typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
 struct AttnParams {
   const uint16_t* q;
@@ -54,6 +61,8 @@ struct AttnParams {
   float c;  // softmax scale * log2(e)
 };
 
+constexpr int PSHIFT = 5;   // probabilities are kept relative to 2^(max - PSHIFT)
+
 __device__ __forceinline__ floatx4 mfma_f16(uint4 a, uint4 b, floatx4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a),
                                                 __builtin_bit_cast(half8_t, b), c, 0, 0, 0);
@@ -67,15 +76,15 @@ __device__ __forceinline__ floatx4 mfma_T(uint4 a, uint4 b, floatx4 c) {
   if constexpr (BF16) return mfma_bf16(a, b, c); else return mfma_f16(a, b, c);
 }
 
-// Eight codes of one operand: register v gets the codes at bits 2(j0+v) and
-// 2(j0+v)+16 of `w` in the low two bits of its two fp16 lanes (value code * 2^-24).
-__device__ __forceinline__ uint4 unpack4(uint32_t w, int j0) {
-  uint4 r;
-  r.x = (w >> (2 * j0)) & 0x00030003u;
-  r.y = (w >> (2 * j0 + 2)) & 0x00030003u;
-  r.z = (w >> (2 * j0 + 4)) & 0x00030003u;
-  r.w = (w >> (2 * j0 + 6)) & 0x00030003u;
-  return r;
+// The eight codes of one operand live in byte 0 and byte 2 of `w` (even operand of
+// the word) or in byte 1 and byte 3 (odd operand).  Register v keeps the code at
+// bits 2v, 2v+1 of each fp16 lane: value code * 2^(2v-24).
+__device__ __forceinline__ uint4 codes_even(uint32_t w) {
+  return make_uint4(w & 0x00030003u, w & 0x000C000Cu, w & 0x00300030u, w & 0x00C000C0u);
+}
+__device__ __forceinline__ uint4 codes_odd(uint32_t w) { return codes_even(w >> 8); }
+__device__ __forceinline__ uint4 codes_of(uint32_t w, int odd) {
+  return odd ? codes_odd(w) : codes_even(w);
 }
 
 __device__ __forceinline__ uint32_t pack_f16(float a, float b) {
@@ -102,18 +111,37 @@ __device__ __forceinline__ void unpack8_T(uint4 v, float* f) {
   f[0] = lo_T<BF16>(v.x); f[1] = hi_T<BF16>(v.x); f[2] = lo_T<BF16>(v.y); f[3] = hi_T<BF16>(v.y);
   f[4] = lo_T<BF16>(v.z); f[5] = hi_T<BF16>(v.z); f[6] = lo_T<BF16>(v.w); f[7] = hi_T<BF16>(v.w);
 }
+// a pair of T values -> a pair of fp16 values (exact for normal-range bf16 inputs)
+template <bool BF16>
+__device__ __forceinline__ half2_t pair_to_f16(uint32_t w) {
+  if constexpr (BF16) return half2_t{(_Float16)lo_T<true>(w), (_Float16)hi_T<true>(w)};
+  else return __builtin_bit_cast(half2_t, w);
+}
+// fp32 accumulate of a two-element dot product of T pairs (exact products)
+template <bool BF16>
+__device__ __forceinline__ float dot2_T(uint32_t a, uint32_t b, float c) {
+  if constexpr (BF16)
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c, false);
+  else
+    return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, a), __builtin_bit_cast(half2_t, b), c, false);
+}
 
-// all-reduce over the 16 lanes that share lane & 3 (one query head)
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
+// all-reduce over the 16 lanes that share lane & 3 (one query head): two rotations
+// inside the row of 16 lanes, two exchanges across rows
 __device__ __forceinline__ float head_max(float v) {
-  v = fmaxf(v, __shfl_xor(v, 4));
-  v = fmaxf(v, __shfl_xor(v, 8));
+  v = fmaxf(v, dpp_f<0x124>(v));   // row_ror:4
+  v = fmaxf(v, dpp_f<0x128>(v));   // row_ror:8
   v = fmaxf(v, __shfl_xor(v, 16));
   v = fmaxf(v, __shfl_xor(v, 32));
   return v;
 }
 __device__ __forceinline__ float head_sum(float v) {
-  v += __shfl_xor(v, 4);
-  v += __shfl_xor(v, 8);
+  v += dpp_f<0x124>(v);
+  v += dpp_f<0x128>(v);
   v += __shfl_xor(v, 16);
   v += __shfl_xor(v, 32);
   return v;
@@ -130,24 +158,33 @@ __device__ __forceinline__ void wave_lds_sync() {
 template <int N>
 struct Words { uint32_t w[N]; };
 
-// Running softmax state of one wavefront.  m, l, zacc belong to head (lane & 3);
+// Running softmax state of one wavefront.  m and l belong to head (lane & 3);
 // acc[nt][j] is output row 4*(lane>>4)+j, column lane&15 of channel tile nt.
+// Everything is relative to 2^(m - PSHIFT); l[j] additionally carries the factor
+// 2^offs[j] of its token slot.
 template <int NNT>
 struct State {
   floatx4 acc[NNT];
-  float m, l, zacc;
+  float m;
+  float l[4];
+  float zacc[8];
 };
 
-// s[0..3]: log2-domain logits of this lane's four tokens -> p[0..3]; updates state.
-template <int NNT>
+// s[0..3]: log2-domain logits (slot offsets included) of this lane's four tokens
+// -> p[0..3] = 2^(s - m + PSHIFT); updates the state.
+template <int NNT, bool ZACC>
 __device__ __forceinline__ void online_softmax(State<NNT>& st, const float* s, float* p) {
   float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
   mx = head_max(mx);
   const float m_new = fmaxf(st.m, mx);
   if (__any(m_new > st.m)) {
-    const float alpha = exp2f(st.m - m_new);   // 0 on the first tile (m = -inf)
-    st.l *= alpha;
-    st.zacc *= alpha;
+    const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);   // 0 on the first tile (m = -inf)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) st.l[j] *= alpha;
+    if constexpr (ZACC) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) st.zacc[i] *= alpha;
+    }
     float a4[4];
 #pragma unroll
     for (int gg = 0; gg < 4; ++gg) a4[gg] = __shfl(alpha, (threadIdx.x & 60) | gg);
@@ -158,22 +195,27 @@ __device__ __forceinline__ void online_softmax(State<NNT>& st, const float* s, f
     }
     st.m = m_new;
   }
+  const float mref = st.m - (float)PSHIFT;
 #pragma unroll
-  for (int j = 0; j < 4; ++j) p[j] = exp2f(s[j] - st.m);
-  st.l += (p[0] + p[1]) + (p[2] + p[3]);
+  for (int j = 0; j < 4; ++j) {
+    p[j] = __builtin_amdgcn_exp2f(s[j] - mref);
+    st.l[j] += p[j];
+  }
 }
 
 template <bool BF16, int D, int G>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256, 2)
 attn_mfma_kernel(const AttnParams P) {
   constexpr int NKC = D / 32, NNT = D / 16, NGC = (D + G - 1) / G;
   constexpr int NGRP = G < 64 ? 64 / G : 1;     // key groups per 64-token tile
   __shared__ __attribute__((aligned(16))) uint16_t qs_lds[4][NGRP][2][4][D];   // fp16 head/tail of q*s per wave
+  __shared__ __attribute__((aligned(16))) float p_lds[4][4][4][4][4];         // [wave][q4][g][up][j]
   __shared__ float o_lds[4][4][D];
   __shared__ float ml_lds[4][4][2];
   __shared__ float zs_lds[4][4][4];
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nhg = P.gh / P.hb;
   const int split = blockIdx.x, hsub = blockIdx.y % nhg, bh = blockIdx.y / nhg;
   const int q4 = lane >> 4, n16 = lane & 15, up = n16 >> 2, g = lane & 3;
@@ -187,34 +229,47 @@ attn_mfma_kernel(const AttnParams P) {
   State<NNT> st;
 #pragma unroll
   for (int nt = 0; nt < NNT; ++nt) st.acc[nt] = floatx4{0.f, 0.f, 0.f, 0.f};
-  st.m = -INFINITY; st.l = 0.f; st.zacc = 0.f;
+  st.m = -INFINITY;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) st.l[j] = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) st.zacc[i] = 0.f;
 
   if (gw >= NWF) {
     // ------------------------- quantized rows -------------------------
     const int wq = gw - NWF;
-    const int64_t code_slice = (int64_t)bh * (P.qcap >> 5) * 64 * NKC;
-    const uint32_t* kcb = P.k_codes + code_slice + lane * NKC;
-    const uint32_t* vcb = P.v_codes + code_slice + lane * NKC;
-    const uint16_t* ksb = P.k_scale + (int64_t)bh * (P.qcap / G) * D;
-    const uint16_t* kzb = P.k_zero + (int64_t)bh * (P.qcap / G) * D;
-    const int64_t vm_slice = (int64_t)bh * (P.qcap >> 5) * NGC * 32;
+    const char* kcb = (const char*)(P.k_codes + (int64_t)bh * (P.qcap >> 5) * 64 * NKC);
+    const char* vcb = (const char*)(P.v_codes + (int64_t)bh * (P.qcap >> 5) * 64 * NKC);
+    const char* ksb = (const char*)(P.k_scale + (int64_t)bh * (P.qcap / G) * D);
+    const char* kzb = (const char*)(P.k_zero + (int64_t)bh * (P.qcap / G) * D);
+    const char* vsb = (const char*)(P.v_scale + (int64_t)bh * (P.qcap >> 5) * NGC * 32);
+    const char* vzb = (const char*)(P.v_zero + (int64_t)bh * (P.qcap >> 5) * NGC * 32);
     const int upc = up < NGC ? up : 0;
-    const uint16_t* vsb = P.v_scale + vm_slice + upc * 32 + 8 * q4;
-    const uint16_t* vzb = P.v_zero + vm_slice + upc * 32 + 8 * q4;
-    const int c8 = lane >> 2;                 // channel octet this lane prepares q*s for
+    const uint32_t code_off = lane * NKC * 4;                 // byte offsets of this lane
+    const uint32_t vm_off = (upc * 32 + 8 * q4) * 2;
+    const int c8 = lane >> 2;                                  // channel octet this lane prepares q*s for
     const bool prep = 8 * c8 < D;
-    const int c8c = prep ? c8 : 0;
+    const uint32_t km_off = (prep ? 8 * c8 : 0) * 2;
 
-    float qv[8];
+    // q of (head g, channels 8*c8..+7): raw pairs for the bias dot products, and
+    // fp16 pairs pre-multiplied by 2^(3-2v) (v = pair index) for the q*s operands
+    uint32_t qraw[4];
+    half2_t qh[4];
     {
-      const uint4 raw = *reinterpret_cast<const uint4*>(P.q + qrow + 8 * c8c);
-      unpack8_T<BF16>(raw, qv);
-      if (!prep || !head_ok) {
+      uint4 raw = *reinterpret_cast<const uint4*>(P.q + qrow + (prep ? 8 * c8 : 0));
+      if (!prep || !head_ok) raw = make_uint4(0, 0, 0, 0);
+      qraw[0] = raw.x; qraw[1] = raw.y; qraw[2] = raw.z; qraw[3] = raw.w;
+      const float f[4] = {8.f, 2.f, 0.5f, 0.125f};
 #pragma unroll
-        for (int i = 0; i < 8; ++i) qv[i] = 0.f;
-      }
+      for (int v = 0; v < 4; ++v)
+        qh[v] = half2_t{(_Float16)(lo_T<BF16>(qraw[v]) * f[v]), (_Float16)(hi_T<BF16>(qraw[v]) * f[v])};
     }
-    const float c24 = P.c * 16777216.f;       // codes enter as code * 2^-24
+    const float c21 = P.c * 2097152.f;        // codes enter as code * 2^-24, q*s as 2^3 q s
+    // slot offsets: token slot j of this lane is element i = 4*(up&1) + j of its
+    // lane group in the output step, whose codes sit at position v = i >> 1
+    float offs[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) offs[j] = (float)(3 - 2 * (2 * (up & 1) + (j >> 1)));
 
     struct Tile {
       Words<NKC> kc[2], vc[2];
@@ -223,132 +278,169 @@ attn_mfma_kernel(const AttnParams P) {
     };
     auto load_tile = [&](int t) {
       Tile T;
+      const char* kcp = kcb + (int64_t)t * (2 * 64 * NKC * 4);
+      const char* vcp = vcb + (int64_t)t * (2 * 64 * NKC * 4);
+      const char* vsp = vsb + (int64_t)t * (2 * NGC * 32 * 2);
+      const char* vzp = vzb + (int64_t)t * (2 * NGC * 32 * 2);
 #pragma unroll
       for (int b2 = 0; b2 < 2; ++b2) {
-        T.kc[b2] = *reinterpret_cast<const Words<NKC>*>(kcb + (int64_t)(2 * t + b2) * 64 * NKC);
-        T.vc[b2] = *reinterpret_cast<const Words<NKC>*>(vcb + (int64_t)(2 * t + b2) * 64 * NKC);
-        T.vs[b2] = *reinterpret_cast<const uint4*>(vsb + (int64_t)(2 * t + b2) * NGC * 32);
-        T.vz[b2] = *reinterpret_cast<const uint4*>(vzb + (int64_t)(2 * t + b2) * NGC * 32);
+        T.kc[b2] = *reinterpret_cast<const Words<NKC>*>(kcp + b2 * (64 * NKC * 4) + code_off);
+        T.vc[b2] = *reinterpret_cast<const Words<NKC>*>(vcp + b2 * (64 * NKC * 4) + code_off);
+        T.vs[b2] = *reinterpret_cast<const uint4*>(vsp + b2 * (NGC * 32 * 2) + vm_off);
+        T.vz[b2] = *reinterpret_cast<const uint4*>(vzp + b2 * (NGC * 32 * 2) + vm_off);
       }
 #pragma unroll
       for (int e = 0; e < NGRP; ++e) {
         const int grp = G <= 64 ? t * NGRP + e : t / (G / 64);
-        T.ks8[e] = *reinterpret_cast<const uint4*>(ksb + (int64_t)grp * D + 8 * c8c);
-        T.kz8[e] = *reinterpret_cast<const uint4*>(kzb + (int64_t)grp * D + 8 * c8c);
+        T.ks8[e] = *reinterpret_cast<const uint4*>(ksb + (int64_t)grp * (D * 2) + km_off);
+        T.kz8[e] = *reinterpret_cast<const uint4*>(kzb + (int64_t)grp * (D * 2) + km_off);
       }
       return T;
     };
 
-    if (wq < TQ) {
-      Tile cur = load_tile(wq);
-      for (int t = wq; t < TQ; t += NWQ) {
-        const int tn = t + NWQ < TQ ? t + NWQ : t;
-        Tile nxt = load_tile(tn);
-
-        // ---- q*s (fp16) and bias = sum_c q_c z_c for each key group of the tile
+    auto process = [&](const Tile& cur, int t) {
+      // ---- q*s (fp16 head and tail) and bias = sum_c q_c z_c for each key group
+      float bo[4];
+      {
         float bias[NGRP];
 #pragma unroll
         for (int e = 0; e < NGRP; ++e) {
-          float s8[8], z8[8];
-          unpack8_T<BF16>(cur.ks8[e], s8);
-          unpack8_T<BF16>(cur.kz8[e], z8);
+          const uint32_t sw[4] = {cur.ks8[e].x, cur.ks8[e].y, cur.ks8[e].z, cur.ks8[e].w};
+          const uint32_t zw[4] = {cur.kz8[e].x, cur.kz8[e].y, cur.kz8[e].z, cur.kz8[e].w};
           float bp = 0.f;
+          uint32_t h[4], l[4];
 #pragma unroll
-          for (int i = 0; i < 8; ++i) bp = fmaf(qv[i], z8[i], bp);
+          for (int v = 0; v < 4; ++v) {
+            bp = dot2_T<BF16>(qraw[v], zw[v], bp);
+            const half2_t sh = pair_to_f16<BF16>(sw[v]);
+            const half2_t hi = qh[v] * sh;
+            const half2_t lo = __builtin_elementwise_fma(qh[v], sh, -hi);
+            h[v] = __builtin_bit_cast(uint32_t, hi);
+            l[v] = __builtin_bit_cast(uint32_t, lo);
+          }
           if (prep) {
-            float x[8], r[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-              x[i] = qv[i] * s8[i];
-              r[i] = x[i] - (float)(_Float16)x[i];
-            }
-            uint4 h, l;
-            h.x = pack_f16(x[0], x[1]); h.y = pack_f16(x[2], x[3]);
-            h.z = pack_f16(x[4], x[5]); h.w = pack_f16(x[6], x[7]);
-            l.x = pack_f16(r[0], r[1]); l.y = pack_f16(r[2], r[3]);
-            l.z = pack_f16(r[4], r[5]); l.w = pack_f16(r[6], r[7]);
-            *reinterpret_cast<uint4*>(&qs_lds[wave][e][0][g][8 * c8]) = h;
-            *reinterpret_cast<uint4*>(&qs_lds[wave][e][1][g][8 * c8]) = l;
+            *reinterpret_cast<uint4*>(&qs_lds[wave][e][0][g][8 * c8]) = make_uint4(h[0], h[1], h[2], h[3]);
+            *reinterpret_cast<uint4*>(&qs_lds[wave][e][1][g][8 * c8]) = make_uint4(l[0], l[1], l[2], l[3]);
           }
           bias[e] = head_sum(bp) * P.c;
         }
-        wave_lds_sync();
+        const float b = bias[NGRP == 1 ? 0 : (up * NGRP) >> 2];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) bo[j] = b + offs[j];
+      }
+      wave_lds_sync();
 
-        // ---- logits: four 16-token tiles x NKC channel chunks
-        floatx4 Du[4];
+      // ---- logits: four 16-token tiles x NKC channel chunks, head and tail of q*s
+      floatx4 Du[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) Du[u] = floatx4{0.f, 0.f, 0.f, 0.f};
+      for (int u = 0; u < 4; ++u) Du[u] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int e = 0; e < NGRP; ++e) {
+      for (int e = 0; e < NGRP; ++e) {
 #pragma unroll
-          for (int kc = 0; kc < NKC; ++kc) {
-            const uint4 bh_ = *reinterpret_cast<const uint4*>(&qs_lds[wave][e][0][g][32 * kc + 8 * q4]);
-            const uint4 bl_ = *reinterpret_cast<const uint4*>(&qs_lds[wave][e][1][g][32 * kc + 8 * q4]);
+        for (int kc = 0; kc < NKC; ++kc) {
+          const uint4 bh_ = *reinterpret_cast<const uint4*>(&qs_lds[wave][e][0][g][32 * kc + 8 * q4]);
+          const uint4 bl_ = *reinterpret_cast<const uint4*>(&qs_lds[wave][e][1][g][32 * kc + 8 * q4]);
 #pragma unroll
-            for (int u = e * (4 / NGRP); u < (e + 1) * (4 / NGRP); ++u) {
-              const int o = (u & 1) * NKC + kc;
-              const uint4 a = unpack4(cur.kc[u >> 1].w[o >> 1], 4 * (o & 1));
-              Du[u] = mfma_f16(a, bh_, Du[u]);
-              Du[u] = mfma_f16(a, bl_, Du[u]);
-            }
+          for (int u = e * (4 / NGRP); u < (e + 1) * (4 / NGRP); ++u) {
+            const int o = (u & 1) * NKC + kc;
+            const uint4 a = codes_of(cur.kc[u >> 1].w[o >> 1], o & 1);
+            Du[u] = mfma_f16(a, bh_, Du[u]);
+            Du[u] = mfma_f16(a, bl_, Du[u]);
           }
         }
-        wave_lds_sync();   // qs_lds is rewritten by the next tile
+      }
 
-        float s[4], p[4];
+      float s[4], p[4];
+      {
+        const floatx4 d = up == 0 ? Du[0] : up == 1 ? Du[1] : up == 2 ? Du[2] : Du[3];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) s[j] = fmaf(d[j], c21, bo[j]);
+      }
+      const bool partial = 64 * t + 64 > P.n_q;
+      if (partial) {
+        const int tok0 = 64 * t + 16 * up + 4 * q4;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          if (tok0 + j >= P.n_q) s[j] = -INFINITY;
+      }
+      online_softmax<NNT, true>(st, s, p);
+
+      // ---- hand the probabilities to the lanes that feed the output step
+      *reinterpret_cast<float4*>(&p_lds[wave][q4][g][up][0]) = make_float4(p[0], p[1], p[2], p[3]);
+      wave_lds_sync();
+
+      // ---- output: two 32-token steps x NNT channel tiles
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        float pv[8];
         {
-          const floatx4 d = up == 0 ? Du[0] : up == 1 ? Du[1] : up == 2 ? Du[2] : Du[3];
-          const float b = bias[NGRP == 1 ? 0 : (up * NGRP) >> 2];
-          const int tok0 = 64 * t + 16 * up + 4 * q4;
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            s[j] = fmaf(d[j], c24, b);
-            if (tok0 + j >= P.n_q) s[j] = -INFINITY;
-          }
+          const float4 p0 = *reinterpret_cast<const float4*>(&p_lds[wave][q4][g][2 * ks][0]);
+          const float4 p1 = *reinterpret_cast<const float4*>(&p_lds[wave][q4][g][2 * ks + 1][0]);
+          pv[0] = p0.x; pv[1] = p0.y; pv[2] = p0.z; pv[3] = p0.w;
+          pv[4] = p1.x; pv[5] = p1.y; pv[6] = p1.z; pv[7] = p1.w;
         }
-        online_softmax<NNT>(st, s, p);
+        uint4 vsr = cur.vs[ks], vzr = cur.vz[ks];
+        if (partial) {   // slots beyond n_q hold unspecified bits: keep them out of the sums
+          uint32_t keep[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int i0 = 2 * r, i1 = 2 * r + 1;
+            const int x0 = 16 * ((i0 >> 2) & 1) + 4 * q4 + (i0 & 3), x1 = 16 * ((i1 >> 2) & 1) + 4 * q4 + (i1 & 3);
+            keep[r] = (64 * t + 32 * ks + x0 < P.n_q ? 0x0000FFFFu : 0u) |
+                      (64 * t + 32 * ks + x1 < P.n_q ? 0xFFFF0000u : 0u);
+          }
+          vsr.x &= keep[0]; vsr.y &= keep[1]; vsr.z &= keep[2]; vsr.w &= keep[3];
+          vzr.x &= keep[0]; vzr.y &= keep[1]; vzr.z &= keep[2]; vzr.w &= keep[3];
+        }
+        float vs8[8], vz8[8];
+        unpack8_T<BF16>(vsr, vs8);
+        unpack8_T<BF16>(vzr, vz8);
+        uint4 a;
+        a.x = pack_f16(pv[0] * vs8[0], pv[1] * vs8[1]);
+        a.y = pack_f16(pv[2] * vs8[2], pv[3] * vs8[3]);
+        a.z = pack_f16(pv[4] * vs8[4], pv[5] * vs8[5]);
+        a.w = pack_f16(pv[6] * vs8[6], pv[7] * vs8[7]);
+        if constexpr (NGC < 4) {
+          const uint32_t live = up < NGC ? 0xFFFFFFFFu : 0u;   // rows of absent channel groups
+          a.x &= live; a.y &= live; a.z &= live; a.w &= live;
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) st.zacc[i] = fmaf(pv[i], vz8[i], st.zacc[i]);
+#pragma unroll
+        for (int nt = 0; nt < NNT; ++nt) {
+          const uint4 b = codes_of(cur.vc[ks].w[nt >> 1], nt & 1);
+          st.acc[nt] = mfma_f16(a, b, st.acc[nt]);
+        }
+      }
+      wave_lds_sync();   // p_lds and qs_lds are rewritten by the next tile
+    };
 
-        // ---- output: two 32-token steps x NNT channel tiles
-        const bool partial = 64 * t + 64 > P.n_q;
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-          float pv[8], vs8[8], vz8[8];
-          const int src0 = (lane & 0x33) | ((2 * ks) << 2), src1 = (lane & 0x33) | ((2 * ks + 1) << 2);
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            pv[j] = __shfl(p[j], src0);
-            pv[4 + j] = __shfl(p[j], src1);
-          }
-          unpack8_T<BF16>(cur.vs[ks], vs8);
-          unpack8_T<BF16>(cur.vz[ks], vz8);
-          if (partial) {   // slots beyond n_q hold unspecified bits: keep them out of the sums
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-              const int x = 16 * ((i >> 2) & 1) + 4 * q4 + (i & 3);   // slot of k = 8*q4 + i in its 32-block
-              if (64 * t + 32 * ks + x >= P.n_q) { vs8[i] = 0.f; vz8[i] = 0.f; }
-            }
-          }
-          float ps[8];
-#pragma unroll
-          for (int i = 0; i < 8; ++i) {
-            ps[i] = up < NGC ? pv[i] * vs8[i] * 256.f : 0.f;
-            st.zacc = up < NGC ? fmaf(pv[i], vz8[i], st.zacc) : st.zacc;
-          }
-          uint4 a;
-          a.x = pack_f16(ps[0], ps[1]); a.y = pack_f16(ps[2], ps[3]);
-          a.z = pack_f16(ps[4], ps[5]); a.w = pack_f16(ps[6], ps[7]);
-#pragma unroll
-          for (int nt = 0; nt < NNT; ++nt) {
-            const uint4 b = unpack4(cur.vc[ks].w[nt >> 1], 4 * (nt & 1));
-            st.acc[nt] = mfma_f16(a, b, st.acc[nt]);
-          }
-        }
-        cur = nxt;
+    if (wq < TQ) {
+      int t = wq;
+      Tile A = load_tile(t);
+      while (true) {
+        const int t1 = t + NWQ;
+        Tile B = load_tile(t1 < TQ ? t1 : t);
+        process(A, t);
+        if (t1 >= TQ) break;
+        const int t2 = t1 + NWQ;
+        A = load_tile(t2 < TQ ? t2 : t1);
+        process(B, t1);
+        if (t2 >= TQ) break;
+        t = t2;
       }
     }
     // canonical partial of this wavefront: o[g][c], m[g], l[g]
-    const float l_tot = head_sum(st.l);
-    float zs = st.zacc;
+    float lsum = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) lsum += st.l[j] * __builtin_amdgcn_exp2f(-offs[j]);
+    const float l_tot = head_sum(lsum);
+    float zs = 0.f;
+    {
+      const float f[4] = {0.125f, 0.5f, 2.f, 8.f};   // 2^-(3-2v)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) zs += st.zacc[i] * f[i >> 1];
+    }
     zs += __shfl_xor(zs, 16);
     zs += __shfl_xor(zs, 32);
     if (q4 == 0) zs_lds[wave][up][g] = zs;
@@ -360,7 +452,7 @@ attn_mfma_kernel(const AttnParams P) {
       if (q4 == gc) {
 #pragma unroll
         for (int gg = 0; gg < 4; ++gg)
-          o_lds[wave][gg][16 * nt + n16] = st.acc[nt][gg] * 65536.f + zs_lds[wave][gc][gg];
+          o_lds[wave][gg][16 * nt + n16] = st.acc[nt][gg] * 2097152.f + zs_lds[wave][gc][gg];
       }
     }
   } else {
@@ -399,7 +491,7 @@ attn_mfma_kernel(const AttnParams P) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) s[j] = (up < 2 && tok0 + j < P.n_fp) ? d[j] * P.c : -INFINITY;
       }
-      online_softmax<NNT>(st, s, p);
+      online_softmax<NNT, false>(st, s, p);
 
       float pv[8];
       const int src0 = (lane & 0x33), src1 = (lane & 0x33) | 4;
@@ -434,7 +526,7 @@ attn_mfma_kernel(const AttnParams P) {
 #pragma unroll
       for (int nt = 0; nt < NNT; ++nt) st.acc[nt] = mfma_T<BF16>(a, va[nt], st.acc[nt]);
     }
-    const float l_tot = head_sum(st.l);
+    const float l_tot = head_sum((st.l[0] + st.l[1]) + (st.l[2] + st.l[3]));
     if (lane < 4) { ml_lds[wave][g][0] = st.m; ml_lds[wave][g][1] = l_tot; }
 #pragma unroll
     for (int nt = 0; nt < NNT; ++nt) {
@@ -466,7 +558,63 @@ attn_mfma_kernel(const AttnParams P) {
   }
 }
 
-hipError_t launch_combine(const Shape& s, const float* ws, void* out, int splits, hipStream_t st);
+// Log-sum-exp merge of the splits' partials (softmax normalisation of Eq. 2).
+// One workgroup per (batch row, query head); threads = channels x PARTS, each part
+// takes every PARTS-th split.
+template <bool BF16>
+__global__ void __launch_bounds__(512)
+combine_kernel(const float* __restrict__ ws, uint16_t* __restrict__ out, int d, int gh, int splits) {
+  __shared__ float w_s[256];        // weight of each split (splits <= 256)
+  __shared__ float red[512];
+  __shared__ float stat[2];
+  const int bhq = blockIdx.x, tid = threadIdx.x;
+  const int bh = bhq / gh, g = bhq % gh;
+  const int64_t stride = (int64_t)gh * (d + 2);
+  const float* base = ws + ((int64_t)bh * splits * gh + g) * (d + 2);
+  // weights: w_s = 2^(m_s - M); L = sum_s w_s l_s
+  float m = -INFINITY, l = 0.f;
+  if (tid < splits) { m = base[tid * stride + d]; l = base[tid * stride + d + 1]; }
+  red[tid] = m;
+  __syncthreads();
+  for (int k = 256; k >= 1; k >>= 1) {
+    if (tid < k) red[tid] = fmaxf(red[tid], red[tid + k]);
+    __syncthreads();
+  }
+  const float M = red[0];
+  __syncthreads();
+  const float w = (tid < splits && m != -INFINITY) ? exp2f(m - M) : 0.f;
+  if (tid < 256) w_s[tid] = w;
+  red[tid] = w * l;
+  __syncthreads();
+  for (int k = 256; k >= 1; k >>= 1) {
+    if (tid < k) red[tid] += red[tid + k];
+    __syncthreads();
+  }
+  if (tid == 0) stat[0] = red[0];
+  __syncthreads();
+  const float L = stat[0];
+  __syncthreads();
+  const int parts = 512 / d;
+  const int c = tid % d, part = tid / d;
+  float acc = 0.f;
+  if (part < parts) {
+#pragma unroll 8
+    for (int s = part; s < splits; s += parts) acc = fmaf(w_s[s], base[s * stride + c], acc);
+  }
+  red[tid] = acc;
+  __syncthreads();
+  if (tid < d) {
+    float o = 0.f;
+    for (int pth = 0; pth < parts; ++pth) o += red[pth * d + tid];
+    out[(int64_t)bhq * d + tid] = f2t<BF16>(o / L);
+  }
+}
+
+hipError_t launch_combine(const Shape& s, const float* ws, void* out, int splits, hipStream_t st) {
+  auto kern = s.bf16 ? combine_kernel<true> : combine_kernel<false>;
+  hipLaunchKernelGGL(kern, dim3(s.B * s.Hq), dim3(512), 0, st, ws, (uint16_t*)out, s.d, s.gh, splits);
+  return launch_status(__func__);
+}
 
 template <bool BF16, int D>
 static hipError_t launch_mfma_dg(const Shape& s, const AttnParams& P, dim3 grid, hipStream_t st) {

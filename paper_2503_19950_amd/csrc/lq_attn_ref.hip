@@ -116,32 +116,7 @@ attn_ref_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_f
   }
 }
 
-// Log-sum-exp merge of the splits' partials (softmax normalisation of Eq. 2).
-// grid (B*Hq), block d.
-template <bool BF16>
-__global__ void combine_kernel(const float* __restrict__ ws, uint16_t* __restrict__ out, int d,
-                               int gh, int splits) {
-  const int bhq = blockIdx.x, c = threadIdx.x;
-  const int bh = bhq / gh, g = bhq % gh;
-  float M = -INFINITY;
-  for (int s = 0; s < splits; ++s)
-    M = fmaxf(M, ws[(((int64_t)bh * splits + s) * gh + g) * (d + 2) + d]);
-  float acc = 0.f, L = 0.f;
-  for (int s = 0; s < splits; ++s) {
-    const int64_t base = (((int64_t)bh * splits + s) * gh + g) * (d + 2);
-    const float ms = ws[base + d];
-    const float a = ms == -INFINITY ? 0.f : exp2f(ms - M);
-    acc += a * ws[base + c];
-    L += a * ws[base + d + 1];
-  }
-  out[(int64_t)bhq * d + c] = f2t<BF16>(acc / L);
-}
-
-hipError_t launch_combine(const Shape& s, const float* ws, void* out, int splits, hipStream_t st) {
-  auto kern = s.bf16 ? combine_kernel<true> : combine_kernel<false>;
-  hipLaunchKernelGGL(kern, dim3(s.B * s.Hq), dim3(s.d), 0, st, ws, (uint16_t*)out, s.d, s.gh, splits);
-  return launch_status(__func__);
-}
+hipError_t launch_combine(const Shape& s, const float* ws, void* out, int splits, hipStream_t st);
 
 template <bool BF16, int HB>
 static hipError_t launch_ref_t(const Shape& s, const lq_cache& c, const void* q, float scale,
