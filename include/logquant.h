@@ -118,8 +118,15 @@ typedef struct {
 lq_status logquant_sizes(const lq_config *cfg, lq_sizes *out);
 
 /* Bytes of the scratch buffer `workspace` that compress and decode_attn take
- * (partial softmax states of the context splits); 0 for an invalid config. */
+ * (ticket counters and partial softmax states of the context splits); 0 for an
+ * invalid config. */
 size_t logquant_workspace_bytes(const lq_config *cfg);
+
+/* Prepare a freshly allocated workspace: zero the ticket counters at its head.
+ * Call once per workspace before its first use by logquant_decode_attn (and again
+ * only if a launch that used it was torn down mid-flight); decode_attn leaves the
+ * counters at zero.  A workspace serves one stream at a time. */
+lq_status logquant_workspace_init(const lq_config *cfg, void *workspace, void *stream);
 
 /* Algorithm 1, the append branch: store n_new new tokens per sequence in fp
  * slots n_fp .. n_fp+n_new-1 and record their absolute positions
@@ -151,7 +158,8 @@ lq_status logquant_compress(const lq_config *cfg, lq_cache *cache, void *workspa
  * rows are dequantized in registers, never in memory.
  *   q   : DEVICE [B][Hq][d] T          out : DEVICE [B][Hq][d] T
  *   softmax_scale <= 0 selects 1/sqrt(d).
- *   workspace : DEVICE, logquant_workspace_bytes(cfg) bytes, contents ignored.
+ *   workspace : DEVICE, logquant_workspace_bytes(cfg) bytes, prepared once with
+ *               logquant_workspace_init; not shared between concurrent calls.
  * Requires n_fp + n_q >= 1 (else LQ_ERR_STATE).  The cache is not modified.
  * Finite inputs only; |q . scale| is assumed to stay below fp16 range (65504). */
 lq_status logquant_decode_attn(const lq_config *cfg, const lq_cache *cache, const void *q,

@@ -45,7 +45,7 @@ class lq_plan(C.Structure):
                 ("fp_waves", C.c_int32), ("bytes_read", C.c_int64)]
 
 
-EXPORTS = ("logquant_sizes", "logquant_workspace_bytes", "logquant_append", "logquant_compress",
+EXPORTS = ("logquant_sizes", "logquant_workspace_bytes", "logquant_workspace_init", "logquant_append", "logquant_compress",
            "logquant_decode_attn", "logquant_decode_plan", "logquant_status_string")
 
 if not os.path.exists(LIB_PATH):
@@ -57,6 +57,8 @@ _lib.logquant_sizes.argtypes = [C.POINTER(lq_config), C.POINTER(lq_sizes)]
 _lib.logquant_sizes.restype = C.c_int
 _lib.logquant_workspace_bytes.argtypes = [C.POINTER(lq_config)]
 _lib.logquant_workspace_bytes.restype = C.c_size_t
+_lib.logquant_workspace_init.argtypes = [C.POINTER(lq_config), C.c_void_p, C.c_void_p]
+_lib.logquant_workspace_init.restype = C.c_int
 _lib.logquant_append.argtypes = [C.POINTER(lq_config), C.POINTER(lq_cache), C.c_void_p, C.c_void_p,
                                  C.c_int32, C.c_void_p]
 _lib.logquant_append.restype = C.c_int
@@ -104,6 +106,10 @@ def logquant_sizes(cfg):
 
 def logquant_workspace_bytes(cfg):
     return int(_lib.logquant_workspace_bytes(_p(cfg)))
+
+
+def logquant_workspace_init(cfg, workspace, stream=0):
+    return _lib.logquant_workspace_init(_p(cfg), _ptr(workspace), stream)
 
 
 def logquant_append(cfg, cache, k_new, v_new, n_new, stream=0):
@@ -168,6 +174,7 @@ class DeviceCache:
         c.pos_q = self.pos_q.data_ptr()
         c.cur = c.n_fp = c.n_q = 0
         self.c = c
+        self._check(logquant_workspace_init(cfg, self.workspace, self._stream()), "logquant_workspace_init")
 
     BUFFERS = ("k_codes", "v_codes", "k_scale", "k_zero", "v_scale", "v_zero", "pos_q")
 

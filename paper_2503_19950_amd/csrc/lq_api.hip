@@ -93,8 +93,18 @@ lq_status logquant_sizes(const lq_config* cfg, lq_sizes* out) {
 size_t logquant_workspace_bytes(const lq_config* cfg) {
   Shape s;
   if (make_shape(cfg, &s) != LQ_OK) return 0;
-  // per (b, kv head, split): gh * (d + 2) floats (o, m, l)
-  return (size_t)s.B * s.Hkv * max_splits(s) * s.gh * (s.d + 2) * sizeof(float);
+  // ticket counters, then per (b, kv head, split): gh * (d + 2) floats (o, m, l)
+  return counter_bytes(s) + (size_t)s.B * s.Hkv * max_splits(s) * s.gh * (s.d + 2) * sizeof(float);
+}
+
+lq_status logquant_workspace_init(const lq_config* cfg, void* workspace, void* stream) {
+  if (!cfg || !workspace) return LQ_ERR_NULL;
+  Shape s;
+  lq_status st = make_shape(cfg, &s);
+  if (st != LQ_OK) return st;
+  clear_stale_error();
+  if (launch_workspace_init(s, workspace, (hipStream_t)stream) != hipSuccess) return LQ_ERR_HIP;
+  return LQ_OK;
 }
 
 lq_status logquant_append(const lq_config* cfg, lq_cache* cache, const void* k_new,

@@ -23,6 +23,19 @@ __global__ void append_kernel(const uint16_t* __restrict__ k_new, const uint16_t
   if (c == 0 && bh % Hkv == 0) pos_fp[(bh / Hkv) * cap + t] = pos0 + j;
 }
 
+// Zero the ticket counters at the head of the workspace (a fill kernel rather than
+// a memset node, so the call can be recorded into a HIP graph).
+__global__ void zero_kernel(int* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+
+hipError_t launch_workspace_init(const Shape& s, void* ws, hipStream_t st) {
+  const int n = (int)(counter_bytes(s) / sizeof(int));
+  hipLaunchKernelGGL(zero_kernel, dim3((n + 255) / 256), dim3(256), 0, st, (int*)ws, n);
+  return launch_status(__func__);
+}
+
 hipError_t launch_append(const Shape& s, const lq_cache& c, const void* k_new, const void* v_new,
                          int n_new, hipStream_t st) {
   dim3 grid(n_new, s.B * s.Hkv);

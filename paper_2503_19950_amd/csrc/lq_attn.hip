@@ -27,7 +27,7 @@ void plan_decode(const Shape& s, int n_fp, int n_q, lq_plan* plan) {
   const double units = TQ + r * TF;
   const int hb = s.gh % 4 == 0 ? 4 : (s.gh % 2 == 0 ? 2 : 1);
   const int groups = s.B * s.Hkv * (s.gh / hb);
-  static const int target_blocks = env_int("LOGQUANT_ATTN_BLOCKS", 1024);
+  static const int target_blocks = env_int("LOGQUANT_ATTN_BLOCKS", 512);
   static const int min_tiles = env_int("LOGQUANT_ATTN_MIN_TILES", 2);
   int splits = (target_blocks + groups - 1) / groups;
   const int by_work = (int)ceil(units / (4.0 * min_tiles));

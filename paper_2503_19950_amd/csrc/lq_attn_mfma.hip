@@ -34,7 +34,15 @@
 // the fp rows in units of 32, the others walk the quantized rows in tiles of 64,
 // each taking every NWQ-th tile so that all wavefronts sweep memory side by side.
 // Partial (max, sum, output) triples are merged in LDS per workgroup and written
-// to the workspace; a second small kernel merges the splits.
+// to the workspace.  Every workgroup then takes a ticket from a counter of its
+// (batch row, kv head, head group); the one that draws the last ticket merges all
+// splits of that group and writes the output, so no second launch is needed and
+// the merge of one group overlaps the tail of the others.  Nobody waits on anybody.
+// The partials and the counter are accessed with device-scope relaxed atomics
+// (write-through stores, cache-bypassing loads): a device-scope fence would write
+// back and invalidate a whole L2 per workgroup, which costs more than the kernel.
+#include <stdlib.h>
+
 #include "lq_device.h"
 #include "lq_internal.h"
 
@@ -56,14 +64,19 @@ struct AttnParams {
   const uint16_t* k_zero;
   const uint16_t* v_scale;
   const uint16_t* v_zero;
-  float* ws;
-  int cap, qcap, n_fp, n_q, gh, hb, splits, nwf;
+  float* ws;          // partials
+  int* counters;      // one ticket counter per grid.y index, zero between launches
+  uint16_t* out;
+  int cap, qcap, n_fp, n_q, gh, hb, splits, nwf, dbg;
   float c;  // softmax scale * log2(e)
 };
 
 constexpr int PSHIFT = 5;   // probabilities are kept relative to 2^(max - PSHIFT)
 
 __device__ __forceinline__ floatx4 mfma_f16(uint4 a, uint4 b, floatx4 c) {
+#ifdef LQ_EXP_NOMFMA
+  c[0] += __uint_as_float(a.x ^ b.x ^ a.y ^ b.y ^ a.z ^ b.z ^ a.w ^ b.w); return c;
+#endif
   return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a),
                                                 __builtin_bit_cast(half8_t, b), c, 0, 0, 0);
 }
@@ -84,6 +97,9 @@ __device__ __forceinline__ uint4 codes_even(uint32_t w) {
 }
 __device__ __forceinline__ uint4 codes_odd(uint32_t w) { return codes_even(w >> 8); }
 __device__ __forceinline__ uint4 codes_of(uint32_t w, int odd) {
+#ifdef LQ_EXP_NOUNPACK
+  return make_uint4(w, w, w, w);
+#endif
   return odd ? codes_odd(w) : codes_even(w);
 }
 
@@ -130,20 +146,43 @@ template <int CTRL>
 __device__ __forceinline__ float dpp_f(float v) {
   return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
 }
+// lane i <-> lane i^16 and lane i <-> lane i^32 exchanges without the LDS crossbar:
+// the swap instructions trade rows (halves) between two registers, so swapping a
+// register with a copy of itself leaves one holding the even rows (low half) twice
+// and the other the odd rows (high half) twice.
+__device__ __forceinline__ void xor16_pair(float v, float* a, float* b) {
+  const unsigned u = __float_as_uint(v);
+  const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  *a = __uint_as_float(r[0]); *b = __uint_as_float(r[1]);
+}
+__device__ __forceinline__ void xor32_pair(float v, float* a, float* b) {
+  const unsigned u = __float_as_uint(v);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  *a = __uint_as_float(r[0]); *b = __uint_as_float(r[1]);
+}
 // all-reduce over the 16 lanes that share lane & 3 (one query head): two rotations
 // inside the row of 16 lanes, two exchanges across rows
 __device__ __forceinline__ float head_max(float v) {
+  float a, b;
   v = fmaxf(v, dpp_f<0x124>(v));   // row_ror:4
   v = fmaxf(v, dpp_f<0x128>(v));   // row_ror:8
-  v = fmaxf(v, __shfl_xor(v, 16));
-  v = fmaxf(v, __shfl_xor(v, 32));
+  xor16_pair(v, &a, &b); v = fmaxf(a, b);
+  xor32_pair(v, &a, &b); v = fmaxf(a, b);
   return v;
 }
 __device__ __forceinline__ float head_sum(float v) {
+  float a, b;
   v += dpp_f<0x124>(v);
   v += dpp_f<0x128>(v);
-  v += __shfl_xor(v, 16);
-  v += __shfl_xor(v, 32);
+  xor16_pair(v, &a, &b); v = a + b;
+  xor32_pair(v, &a, &b); v = a + b;
+  return v;
+}
+// sum over the four lanes that differ in lane >> 4
+__device__ __forceinline__ float rows_sum(float v) {
+  float a, b;
+  xor16_pair(v, &a, &b); v = a + b;
+  xor32_pair(v, &a, &b); v = a + b;
   return v;
 }
 
@@ -153,6 +192,14 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// device-coherent accesses to the partial results (see the ticket merge below)
+__device__ __forceinline__ void st_dev(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_dev(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 template <int N>
@@ -167,23 +214,25 @@ struct State {
   floatx4 acc[NNT];
   float m;
   float l[4];
-  float zacc[8];
+  float zacc[4];   // per code position v (token slots 2v, 2v+1 of a lane)
 };
 
 // s[0..3]: log2-domain logits (slot offsets included) of this lane's four tokens
 // -> p[0..3] = 2^(s - m + PSHIFT); updates the state.
 template <int NNT, bool ZACC>
 __device__ __forceinline__ void online_softmax(State<NNT>& st, const float* s, float* p) {
+  // the running maximum only has to bound every logit seen so far: the cross-lane
+  // reduction runs only when some lane's tile maximum exceeds it
   float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
-  mx = head_max(mx);
-  const float m_new = fmaxf(st.m, mx);
-  if (__any(m_new > st.m)) {
+  if (__any(mx > st.m)) {
+    mx = head_max(mx);
+    const float m_new = fmaxf(st.m, mx);
     const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);   // 0 on the first tile (m = -inf)
 #pragma unroll
     for (int j = 0; j < 4; ++j) st.l[j] *= alpha;
     if constexpr (ZACC) {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) st.zacc[i] *= alpha;
+      for (int i = 0; i < 4; ++i) st.zacc[i] *= alpha;
     }
     float a4[4];
 #pragma unroll
@@ -208,8 +257,10 @@ __global__ void __launch_bounds__(256, 2)
 attn_mfma_kernel(const AttnParams P) {
   constexpr int NKC = D / 32, NNT = D / 16, NGC = (D + G - 1) / G;
   constexpr int NGRP = G < 64 ? 64 / G : 1;     // key groups per 64-token tile
-  __shared__ __attribute__((aligned(16))) uint16_t qs_lds[4][NGRP][2][4][D];   // fp16 head/tail of q*s per wave
-  __shared__ __attribute__((aligned(16))) float p_lds[4][4][4][4][4];         // [wave][q4][g][up][j]
+  // fp16 head/tail of q*s per wave; rows padded by 16 bytes so that the four heads'
+  // rows start in different banks
+  __shared__ __attribute__((aligned(16))) uint16_t qs_lds[4][NGRP][2][4][D + 8];
+  __shared__ __attribute__((aligned(16))) uint2 p_lds[4][4][4][4];            // [wave][q4][g][up]: 4 fp16 probabilities
   __shared__ float o_lds[4][4][D];
   __shared__ float ml_lds[4][4][2];
   __shared__ float zs_lds[4][4][4];
@@ -233,7 +284,7 @@ attn_mfma_kernel(const AttnParams P) {
 #pragma unroll
   for (int j = 0; j < 4; ++j) st.l[j] = 0.f;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) st.zacc[i] = 0.f;
+  for (int i = 0; i < 4; ++i) st.zacc[i] = 0.f;
 
   if (gw >= NWF) {
     // ------------------------- quantized rows -------------------------
@@ -351,10 +402,11 @@ attn_mfma_kernel(const AttnParams P) {
       }
 
       float s[4], p[4];
-      {
-        const floatx4 d = up == 0 ? Du[0] : up == 1 ? Du[1] : up == 2 ? Du[2] : Du[3];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) s[j] = fmaf(d[j], c21, bo[j]);
+      for (int j = 0; j < 4; ++j) {
+        const float x = (up & 1) ? Du[1][j] : Du[0][j];
+        const float y = (up & 1) ? Du[3][j] : Du[2][j];
+        s[j] = fmaf((up & 2) ? y : x, c21, bo[j]);
       }
       const bool partial = 64 * t + 64 > P.n_q;
       if (partial) {
@@ -365,20 +417,15 @@ attn_mfma_kernel(const AttnParams P) {
       }
       online_softmax<NNT, true>(st, s, p);
 
-      // ---- hand the probabilities to the lanes that feed the output step
-      *reinterpret_cast<float4*>(&p_lds[wave][q4][g][up][0]) = make_float4(p[0], p[1], p[2], p[3]);
+      // ---- hand the probabilities (fp16) to the lanes that feed the output step
+      p_lds[wave][q4][g][up] = make_uint2(pack_f16(p[0], p[1]), pack_f16(p[2], p[3]));
       wave_lds_sync();
 
       // ---- output: two 32-token steps x NNT channel tiles
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks) {
-        float pv[8];
-        {
-          const float4 p0 = *reinterpret_cast<const float4*>(&p_lds[wave][q4][g][2 * ks][0]);
-          const float4 p1 = *reinterpret_cast<const float4*>(&p_lds[wave][q4][g][2 * ks + 1][0]);
-          pv[0] = p0.x; pv[1] = p0.y; pv[2] = p0.z; pv[3] = p0.w;
-          pv[4] = p1.x; pv[5] = p1.y; pv[6] = p1.z; pv[7] = p1.w;
-        }
+        const uint4 pw = *reinterpret_cast<const uint4*>(&p_lds[wave][q4][g][2 * ks]);
+        const uint32_t ph[4] = {pw.x, pw.y, pw.z, pw.w};      // slots (0,1) (2,3) (4,5) (6,7)
         uint4 vsr = cur.vs[ks], vzr = cur.vz[ks];
         if (partial) {   // slots beyond n_q hold unspecified bits: keep them out of the sums
           uint32_t keep[4];
@@ -392,20 +439,20 @@ attn_mfma_kernel(const AttnParams P) {
           vsr.x &= keep[0]; vsr.y &= keep[1]; vsr.z &= keep[2]; vsr.w &= keep[3];
           vzr.x &= keep[0]; vzr.y &= keep[1]; vzr.z &= keep[2]; vzr.w &= keep[3];
         }
-        float vs8[8], vz8[8];
-        unpack8_T<BF16>(vsr, vs8);
-        unpack8_T<BF16>(vzr, vz8);
-        uint4 a;
-        a.x = pack_f16(pv[0] * vs8[0], pv[1] * vs8[1]);
-        a.y = pack_f16(pv[2] * vs8[2], pv[3] * vs8[3]);
-        a.z = pack_f16(pv[4] * vs8[4], pv[5] * vs8[5]);
-        a.w = pack_f16(pv[6] * vs8[6], pv[7] * vs8[7]);
+        const uint32_t vsw[4] = {vsr.x, vsr.y, vsr.z, vsr.w}, vzw[4] = {vzr.x, vzr.y, vzr.z, vzr.w};
+        uint32_t aw[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const half2_t pp = __builtin_bit_cast(half2_t, ph[v]);
+          aw[v] = __builtin_bit_cast(uint32_t, pp * pair_to_f16<BF16>(vsw[v]));
+          st.zacc[v] = __builtin_amdgcn_fdot2(pp, pair_to_f16<BF16>(vzw[v]), st.zacc[v], false);
+        }
         if constexpr (NGC < 4) {
           const uint32_t live = up < NGC ? 0xFFFFFFFFu : 0u;   // rows of absent channel groups
-          a.x &= live; a.y &= live; a.z &= live; a.w &= live;
-        }
 #pragma unroll
-        for (int i = 0; i < 8; ++i) st.zacc[i] = fmaf(pv[i], vz8[i], st.zacc[i]);
+          for (int v = 0; v < 4; ++v) aw[v] &= live;
+        }
+        const uint4 a = make_uint4(aw[0], aw[1], aw[2], aw[3]);
 #pragma unroll
         for (int nt = 0; nt < NNT; ++nt) {
           const uint4 b = codes_of(cur.vc[ks].w[nt >> 1], nt & 1);
@@ -420,11 +467,17 @@ attn_mfma_kernel(const AttnParams P) {
       Tile A = load_tile(t);
       while (true) {
         const int t1 = t + NWQ;
+#ifdef LQ_EXP_NOLOAD
+        Tile B = A;
+#else
         Tile B = load_tile(t1 < TQ ? t1 : t);
+#endif
         process(A, t);
         if (t1 >= TQ) break;
         const int t2 = t1 + NWQ;
+#ifndef LQ_EXP_NOLOAD
         A = load_tile(t2 < TQ ? t2 : t1);
+#endif
         process(B, t1);
         if (t2 >= TQ) break;
         t = t2;
@@ -439,10 +492,9 @@ attn_mfma_kernel(const AttnParams P) {
     {
       const float f[4] = {0.125f, 0.5f, 2.f, 8.f};   // 2^-(3-2v)
 #pragma unroll
-      for (int i = 0; i < 8; ++i) zs += st.zacc[i] * f[i >> 1];
+      for (int v = 0; v < 4; ++v) zs += st.zacc[v] * f[v];
     }
-    zs += __shfl_xor(zs, 16);
-    zs += __shfl_xor(zs, 32);
+    zs = rows_sum(zs);
     if (q4 == 0) zs_lds[wave][up][g] = zs;
     if (lane < 4) { ml_lds[wave][g][0] = st.m; ml_lds[wave][g][1] = l_tot; }
     wave_lds_sync();
@@ -553,8 +605,73 @@ attn_mfma_kernel(const AttnParams P) {
       L += a * ml_lds[w][gg][1];
     }
     const int64_t base = (((int64_t)bh * P.splits + split) * P.gh + hsub * P.hb + gg) * (D + 2);
-    P.ws[base + c] = acc;
-    if (c == 0) { P.ws[base + D] = M; P.ws[base + D + 1] = L; }
+    st_dev(P.ws + base + c, acc);
+    if (c == 0) { st_dev(P.ws + base + D, M); st_dev(P.ws + base + D + 1, L); }
+  }
+
+  // ---- ticket: the last workgroup of this (b, kv head, head group) merges the splits.
+  // The barrier waits for this workgroup's stores to be acknowledged before thread 0
+  // draws; a workgroup that draws the last ticket therefore finds every partial.
+  __shared__ int is_last;
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_s_waitcnt(0);   // vmcnt(0): the write-through stores above have been acknowledged
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int old = __hip_atomic_fetch_add(P.counters + blockIdx.y, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    is_last = old == P.splits - 1 && !P.dbg;
+    if (is_last)   // every other workgroup has drawn already: re-arm for the next launch
+      __hip_atomic_store(P.counters + blockIdx.y, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  __syncthreads();
+  if (!is_last) return;
+  float* w_lds = &o_lds[0][0][0];              // [4][256] weights, o_lds is free again
+  const int64_t gstride = (int64_t)P.gh * (D + 2);
+  const float* gbase = P.ws + ((int64_t)bh * P.splits * P.gh + hsub * P.hb) * (D + 2);
+  if (wave < P.hb) {                            // wavefront w: weights of head w
+    const float* hb_ = gbase + wave * (D + 2);
+    float m[4], l[4], mx = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int sidx = lane + 64 * k;
+      m[k] = -INFINITY; l[k] = 0.f;
+      if (sidx < P.splits) { m[k] = ld_dev(hb_ + sidx * gstride + D); l[k] = ld_dev(hb_ + sidx * gstride + D + 1); }
+      mx = fmaxf(mx, m[k]);
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    float ls = 0.f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const float w = m[k] == -INFINITY ? 0.f : exp2f(m[k] - mx);
+      w_lds[wave * 256 + lane + 64 * k] = w;
+      ls += w * l[k];
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) ls += __shfl_xor(ls, o);
+    if (lane == 0) ml_lds[wave][0][0] = ls;
+  }
+  __syncthreads();
+  if (wave < P.hb) {                            // wavefront w: output channels of head w
+    constexpr int NCH = (D + 63) / 64;
+    const float* hb_ = gbase + wave * (D + 2);
+    float acc[NCH];
+#pragma unroll
+    for (int k = 0; k < NCH; ++k) acc[k] = 0.f;
+#pragma unroll 8
+    for (int sidx = 0; sidx < P.splits; ++sidx) {
+      const float w = w_lds[wave * 256 + sidx];
+#pragma unroll
+      for (int k = 0; k < NCH; ++k) {
+        const int c = lane + 64 * k;
+        if (c < D) acc[k] = fmaf(w, ld_dev(hb_ + sidx * gstride + c), acc[k]);
+      }
+    }
+    const float inv = 1.0f / ml_lds[wave][0][0];
+#pragma unroll
+    for (int k = 0; k < NCH; ++k) {
+      const int c = lane + 64 * k;
+      if (c < D) P.out[((int64_t)bh * P.gh + hsub * P.hb + wave) * D + c] = f2t<BF16>(acc[k] * inv);
+    }
   }
 }
 
@@ -644,15 +761,16 @@ hipError_t launch_decode_attn_mfma(const Shape& s, const lq_cache& c, const void
   P.k_codes = c.k_codes; P.v_codes = c.v_codes;
   P.k_scale = (const uint16_t*)c.k_scale; P.k_zero = (const uint16_t*)c.k_zero;
   P.v_scale = (const uint16_t*)c.v_scale; P.v_zero = (const uint16_t*)c.v_zero;
-  P.ws = (float*)ws;
+  P.counters = (int*)ws;
+  P.ws = (float*)((char*)ws + counter_bytes(s));
+  P.out = (uint16_t*)out;
   P.cap = s.cap; P.qcap = s.qcap; P.n_fp = c.n_fp; P.n_q = c.n_q; P.gh = s.gh;
   P.hb = s.gh % 4 == 0 ? 4 : (s.gh % 2 == 0 ? 2 : 1);
   P.splits = plan.splits; P.nwf = plan.fp_waves;
+  { const char* e = getenv("LQ_DBG"); P.dbg = e ? atoi(e) : 0; }
   P.c = scale * 1.4426950408889634f;
   dim3 grid(plan.splits, s.B * s.Hkv * (s.gh / P.hb));
-  hipError_t e = s.bf16 ? launch_mfma_d<true>(s, P, grid, st) : launch_mfma_d<false>(s, P, grid, st);
-  if (e != hipSuccess) return e;
-  return launch_combine(s, (const float*)ws, out, plan.splits, st);
+  return s.bf16 ? launch_mfma_d<true>(s, P, grid, st) : launch_mfma_d<false>(s, P, grid, st);
 }
 
 }  // namespace lq

@@ -131,7 +131,8 @@ static hipError_t launch_ref_t(const Shape& s, const lq_cache& c, const void* q,
 }
 
 hipError_t launch_decode_attn_ref(const Shape& s, const lq_cache& c, const void* q, float scale,
-                                  void* out, void* ws, int splits, hipStream_t st) {
+                                  void* out, void* ws_all, int splits, hipStream_t st) {
+  void* ws = (char*)ws_all + counter_bytes(s);
   const int hb = s.gh % 4 == 0 ? 4 : (s.gh % 2 == 0 ? 2 : 1);
   hipError_t e;
   if (s.bf16) {

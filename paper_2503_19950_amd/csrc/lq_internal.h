@@ -19,6 +19,13 @@ lq_status make_shape(const lq_config* cfg, Shape* s);
 // Upper bound on context splits per (b, kv head) that decode_attn may use.
 int max_splits(const Shape& s);
 
+// The workspace starts with one ticket counter per (b, kv head, head group), padded
+// to 256 bytes; the splits' partial results follow.
+inline size_t counter_bytes(const Shape& s) {
+  return (((size_t)s.B * s.Hkv * s.gh * sizeof(int)) + 255) / 256 * 256;
+}
+hipError_t launch_workspace_init(const Shape& s, void* ws, hipStream_t st);
+
 // Bytes one decode step reads from the cache (live slots only).
 int64_t cache_bytes_read(const Shape& s, int n_fp, int n_q);
 
