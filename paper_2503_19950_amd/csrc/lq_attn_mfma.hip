@@ -41,8 +41,6 @@
 // The partials and the counter are accessed with device-scope relaxed atomics
 // (write-through stores, cache-bypassing loads): a device-scope fence would write
 // back and invalidate a whole L2 per workgroup, which costs more than the kernel.
-#include <stdlib.h>
-
 #include "lq_device.h"
 #include "lq_internal.h"
 
@@ -67,16 +65,14 @@ struct AttnParams {
   float* ws;          // partials
   int* counters;      // one ticket counter per grid.y index, zero between launches
   uint16_t* out;
-  int cap, qcap, n_fp, n_q, gh, hb, splits, nwf, dbg;
+  int cap, qcap, n_fp, n_q, gh, hb, splits, nwf;
   float c;  // softmax scale * log2(e)
 };
 
 constexpr int PSHIFT = 5;   // probabilities are kept relative to 2^(max - PSHIFT)
+constexpr float MAX_SLACK = 4.f;
 
 __device__ __forceinline__ floatx4 mfma_f16(uint4 a, uint4 b, floatx4 c) {
-#ifdef LQ_EXP_NOMFMA
-  c[0] += __uint_as_float(a.x ^ b.x ^ a.y ^ b.y ^ a.z ^ b.z ^ a.w ^ b.w); return c;
-#endif
   return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a),
                                                 __builtin_bit_cast(half8_t, b), c, 0, 0, 0);
 }
@@ -97,9 +93,6 @@ __device__ __forceinline__ uint4 codes_even(uint32_t w) {
 }
 __device__ __forceinline__ uint4 codes_odd(uint32_t w) { return codes_even(w >> 8); }
 __device__ __forceinline__ uint4 codes_of(uint32_t w, int odd) {
-#ifdef LQ_EXP_NOUNPACK
-  return make_uint4(w, w, w, w);
-#endif
   return odd ? codes_odd(w) : codes_even(w);
 }
 
@@ -223,8 +216,10 @@ template <int NNT, bool ZACC>
 __device__ __forceinline__ void online_softmax(State<NNT>& st, const float* s, float* p) {
   // the running maximum only has to bound every logit seen so far: the cross-lane
   // reduction runs only when some lane's tile maximum exceeds it
+  // (a logit may exceed the reference by up to MAX_SLACK before that happens:
+  // probabilities then reach 2^(PSHIFT + MAX_SLACK), still far inside fp16 range)
   float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
-  if (__any(mx > st.m)) {
+  if (__any(mx > st.m + MAX_SLACK)) {
     mx = head_max(mx);
     const float m_new = fmaxf(st.m, mx);
     const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);   // 0 on the first tile (m = -inf)
@@ -257,9 +252,13 @@ __global__ void __launch_bounds__(256, 2)
 attn_mfma_kernel(const AttnParams P) {
   constexpr int NKC = D / 32, NNT = D / 16, NGC = (D + G - 1) / G;
   constexpr int NGRP = G < 64 ? 64 / G : 1;     // key groups per 64-token tile
-  // fp16 head/tail of q*s per wave; rows padded by 16 bytes so that the four heads'
-  // rows start in different banks
-  __shared__ __attribute__((aligned(16))) uint16_t qs_lds[4][NGRP][2][4][D + 8];
+  // fp16 head/tail of q*s per wave.  A 16-byte read per lane touches 16 distinct
+  // chunks (4 heads x 4 lane groups); rows are padded so that the row pitch is 64 or
+  // 192 bytes modulo the 256 bytes of the 64 banks, which spreads the 16 chunks over
+  // all banks.
+  constexpr int QS_ROW = (D * 2) % 256 == 64 || (D * 2) % 256 == 192 ? D : D + 32;
+  static_assert((QS_ROW * 2) % 256 == 64 || (QS_ROW * 2) % 256 == 192, "q*s row pitch");
+  __shared__ __attribute__((aligned(16))) uint16_t qs_lds[4][NGRP][2][4][QS_ROW];
   __shared__ __attribute__((aligned(16))) uint2 p_lds[4][4][4][4];            // [wave][q4][g][up]: 4 fp16 probabilities
   __shared__ float o_lds[4][4][D];
   __shared__ float ml_lds[4][4][2];
@@ -467,17 +466,11 @@ attn_mfma_kernel(const AttnParams P) {
       Tile A = load_tile(t);
       while (true) {
         const int t1 = t + NWQ;
-#ifdef LQ_EXP_NOLOAD
-        Tile B = A;
-#else
         Tile B = load_tile(t1 < TQ ? t1 : t);
-#endif
         process(A, t);
         if (t1 >= TQ) break;
         const int t2 = t1 + NWQ;
-#ifndef LQ_EXP_NOLOAD
         A = load_tile(t2 < TQ ? t2 : t1);
-#endif
         process(B, t1);
         if (t2 >= TQ) break;
         t = t2;
@@ -618,7 +611,7 @@ attn_mfma_kernel(const AttnParams P) {
   __syncthreads();
   if (threadIdx.x == 0) {
     const int old = __hip_atomic_fetch_add(P.counters + blockIdx.y, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    is_last = old == P.splits - 1 && !P.dbg;
+    is_last = old == P.splits - 1;
     if (is_last)   // every other workgroup has drawn already: re-arm for the next launch
       __hip_atomic_store(P.counters + blockIdx.y, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
@@ -767,7 +760,6 @@ hipError_t launch_decode_attn_mfma(const Shape& s, const lq_cache& c, const void
   P.cap = s.cap; P.qcap = s.qcap; P.n_fp = c.n_fp; P.n_q = c.n_q; P.gh = s.gh;
   P.hb = s.gh % 4 == 0 ? 4 : (s.gh % 2 == 0 ? 2 : 1);
   P.splits = plan.splits; P.nwf = plan.fp_waves;
-  { const char* e = getenv("LQ_DBG"); P.dbg = e ? atoi(e) : 0; }
   P.c = scale * 1.4426950408889634f;
   dim3 grid(plan.splits, s.B * s.Hkv * (s.gh / P.hb));
   return s.bf16 ? launch_mfma_d<true>(s, P, grid, st) : launch_mfma_d<false>(s, P, grid, st);
