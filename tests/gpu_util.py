@@ -119,3 +119,40 @@ def check_attention(dc, oc_by_slice, wl, q_np, scale=0.0, large_outputs=False):
         else:
             assert err <= TOL[dt], "attention (b=%d,h=%d): max abs err %.3e > %.1e" % (b, h, err, TOL[dt])
     return worst
+
+
+def batch_kv_sampled(seed_id, t0, t1, wl, distinct):
+    """[B][Hkv][n][d] K and V in which only the slices listed in `distinct` (and the
+    eight filler slices (0, 0..7)) carry their own seeded data; every other slice
+    repeats one of the fillers.  Used at sizes where drawing every slice would take
+    minutes; the launch shape is that of the full workload."""
+    B, H, d = wl["B"], wl["Hkv"], wl["d"]
+    n = t1 - t0
+    K = np.empty((B, H, n, d), np.float32)
+    V = np.empty((B, H, n, d), np.float32)
+    fill = [inputs.slice_kv(seed_id, 0, h % H, t0, t1, wl) for h in range(min(8, H))]
+    own = {bh: inputs.slice_kv(seed_id, bh[0], bh[1], t0, t1, wl) for bh in distinct}
+    for b in range(B):
+        for h in range(H):
+            k, v = own.get((b, h)) or fill[(b * H + h) % len(fill)]
+            K[b, h], V[b, h] = k, v
+    return K, V
+
+
+def build_gpu_sampled(wl, seed_id, L, distinct, q_capacity=None):
+    from paper_2503_19950_amd import binding
+    W = wl["F"] // 2
+    if q_capacity is None:
+        q_capacity = (L // W + 2) * W
+        while q_capacity % 64:
+            q_capacity += W
+    cfg = binding.make_config(wl["B"], wl["Hq"], wl["Hkv"], wl["d"], wl["F"], wl["G"], wl["dtype"],
+                              q_capacity)
+    dc = binding.DeviceCache(cfg)
+    step = 3 * W * 8
+    for t0 in range(0, L, step):
+        t1 = min(L, t0 + step)
+        K, V = batch_kv_sampled(seed_id, t0, t1, wl, distinct)
+        dc.stream_in(to_dev(K, wl["dtype"]), to_dev(V, wl["dtype"]))
+        print("  streamed", t1, "of", L, flush=True)
+    return dc
