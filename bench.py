@@ -28,6 +28,8 @@ def parse():
     ap.add_argument("--workload", type=int, default=3, help="1..5, see BASELINE.json configs")
     ap.add_argument("--copies", type=int, default=0, help="cache copies to rotate over (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy a few times (reference for HBM counters)")
     return ap.parse_args()
 
 
@@ -149,14 +151,16 @@ def main():
     torch.cuda.synchronize()
     attn = [(e0.elapsed_time(e1) * 1e3, nb) for k, e0, e1, nb in ev if k == "attn"]
     comp = [e0.elapsed_time(e1) * 1e3 for k, e0, e1, nb in ev if k == "compress"]
-    attn_us = float(np.mean([t for t, _ in attn]))
-    attn_bytes = float(np.mean([nb for _, nb in attn]))
-    achieved = attn_bytes / (attn_us * 1e-6) / 1e9
+    attn_event_us = float(np.mean([t for t, _ in attn]))   # includes the event markers' own cost
 
-    # back-to-back attention launches only (no appends in between), rotating copies
+    # timed region 3: the attention launches alone, back to back on the launch stream,
+    # rotating over the cache copies, one HIP event before and one after.  Kernel
+    # durations measured this way agree with rocprofv3's kernel trace (an event pair
+    # around every single launch adds several microseconds of marker cost), so the
+    # roofline figures are taken from here.
     for dc, c in zip(caches, saved):
         dc.set_counts(c)
-    nb2b = 200
+    nb2b = max(200, steps)
     for s in range(20):
         binding.logquant_decode_attn(cfg, caches[s % len(caches)].c, qs[0], 0.0, out,
                                      caches[s % len(caches)].workspace, sh)
@@ -168,8 +172,11 @@ def main():
     e1.record(stream)
     torch.cuda.synchronize()
     b2b_us = e0.elapsed_time(e1) * 1e3 / nb2b
-    b2b_bytes = float(np.mean([binding.logquant_decode_plan(cfg, dc.c.n_fp, dc.c.n_q).bytes_read
-                               for dc in caches]))
+    b2b_bytes = float(np.mean([binding.logquant_decode_plan(cfg, caches[s % len(caches)].c.n_fp,
+                                                            caches[s % len(caches)].c.n_q).bytes_read
+                               for s in range(nb2b)]))
+    attn_us, attn_bytes = b2b_us, b2b_bytes
+    achieved = attn_bytes / (attn_us * 1e-6) / 1e9
 
     plan = binding.logquant_decode_plan(cfg, caches[1].c.n_fp, caches[1].c.n_q)
     result = {
@@ -186,16 +193,37 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,
                      "kernel": "decode attention", "us_per_launch": attn_us,
-                     "algorithmic_bytes_per_launch": attn_bytes,
-                     "back_to_back_us_per_launch": b2b_us,
-                     "back_to_back_GBs": b2b_bytes / (b2b_us * 1e-6) / 1e9},
+                     "algorithmic_bytes_per_launch": attn_bytes, "launches_timed": nb2b,
+                     "in_step_loop_event_pair_us": attn_event_us},
         "compress_us_per_call": float(np.mean(comp)) if comp else None,
         "token_heads_per_s": wl["B"] * wl["Hkv"] * L / (ms_per_step * 1e-3),
         "state_build_s": t_build,
     }
+    if a.calibration_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        result["calibration_copy_bytes"] = 256 << 20
+    result["roofline"]["traffic"] = read_traffic(wl["name"])
     if not a.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, a.workload)
     print(json.dumps(result), flush=True)
+
+
+def read_traffic(workload_name):
+    """HBM bytes per attention launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    (two runs, scaled by a plain copy of known size); the figures are kept with the
+    commands that produced them in profiles/decode_attn_<workload>_hbm_traffic.txt."""
+    path = os.path.join(ROOT, "profiles", "decode_attn_%s_hbm_traffic.txt" % workload_name)
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
 
 
 def cpu_baseline(wl, cfg_id):
