@@ -93,8 +93,8 @@ lq_status logquant_sizes(const lq_config* cfg, lq_sizes* out) {
 size_t logquant_workspace_bytes(const lq_config* cfg) {
   Shape s;
   if (make_shape(cfg, &s) != LQ_OK) return 0;
-  // ticket counters, then per (b, kv head, split): gh * (d + 2) floats (o, m, l)
-  return counter_bytes(s) + (size_t)s.B * s.Hkv * max_splits(s) * s.gh * (s.d + 2) * sizeof(float);
+  // ticket counters, then per (b, kv head, split): gh * (d + 4) floats (o, m, l, padding to 16 bytes)
+  return counter_bytes(s) + (size_t)s.B * s.Hkv * max_splits(s) * s.gh * (s.d + 4) * sizeof(float);
 }
 
 lq_status logquant_workspace_init(const lq_config* cfg, void* workspace, void* stream) {

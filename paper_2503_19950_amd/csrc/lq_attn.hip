@@ -12,6 +12,8 @@ hipError_t launch_decode_attn_ref(const Shape& s, const lq_cache& c, const void*
 hipError_t launch_decode_attn_mfma(const Shape& s, const lq_cache& c, const void* q, float scale,
                                    void* out, void* ws, const lq_plan& plan, hipStream_t st);
 
+constexpr int WPB = 8;   // wavefronts per workgroup of the attention kernel
+
 static int env_int(const char* name, int dflt) {
   const char* v = getenv(name);
   return v && *v ? atoi(v) : dflt;
@@ -27,14 +29,14 @@ void plan_decode(const Shape& s, int n_fp, int n_q, lq_plan* plan) {
   const double units = TQ + r * TF;
   const int hb = s.gh % 4 == 0 ? 4 : (s.gh % 2 == 0 ? 2 : 1);
   const int groups = s.B * s.Hkv * (s.gh / hb);
-  static const int target_blocks = env_int("LOGQUANT_ATTN_BLOCKS", 512);
+  static const int target_blocks = env_int("LOGQUANT_ATTN_BLOCKS", 256);
   static const int min_tiles = env_int("LOGQUANT_ATTN_MIN_TILES", 2);
   int splits = (target_blocks + groups - 1) / groups;
-  const int by_work = (int)ceil(units / (4.0 * min_tiles));
+  const int by_work = (int)ceil(units / (WPB * (double)min_tiles));
   if (splits > by_work) splits = by_work;
   if (splits > max_splits(s)) splits = max_splits(s);
   if (splits < 1) splits = 1;
-  const int NW = 4 * splits;
+  const int NW = WPB * splits;
   int nwf = (int)lround(NW * (r * TF) / units);
   if (TF > 0) {
     if (nwf < 1) nwf = 1;
@@ -45,7 +47,7 @@ void plan_decode(const Shape& s, int n_fp, int n_q, lq_plan* plan) {
   if (TQ > 0 && nwf > NW - 1) nwf = NW - 1;
   if (TQ == 0) nwf = NW;
   plan->splits = splits;
-  plan->waves_per_block = 4;
+  plan->waves_per_block = WPB;
   plan->blocks = splits * groups;
   plan->fp_waves = nwf;
   plan->bytes_read = cache_bytes_read(s, n_fp, n_q);

@@ -29,10 +29,11 @@
 // tiles, so one accumulator quad per lane ends up holding logits of 64 tokens x 4
 // heads with every lane busy in the softmax.
 //
-// Work split: a workgroup has four independent wavefronts; the wavefronts of all
+// Work split: a workgroup has eight independent wavefronts; the wavefronts of all
 // workgroups of one (batch row, kv head) are numbered 0..NW-1, the first `nwf` walk
-// the fp rows in units of 32, the others walk the quantized rows in tiles of 64,
-// each taking every NWQ-th tile so that all wavefronts sweep memory side by side.
+// the fp rows in units of 32, the others walk the quantized rows in tiles of 64:
+// slot w owns every NWQ-th tile starting at w (all wavefronts sweep memory side by
+// side), and the slots of one workgroup are pooled and drawn dynamically.
 // Partial (max, sum, output) triples are merged in LDS per workgroup and written
 // to the workspace.  Every workgroup then takes a ticket from a counter of its
 // (batch row, kv head, head group); the one that draws the last ticket merges all
@@ -63,7 +64,7 @@ struct AttnParams {
   const uint16_t* v_scale;
   const uint16_t* v_zero;
   float* ws;          // partials
-  int* counters;      // one ticket counter per grid.y index, zero between launches
+  int* counters;      // CTR_LINES lines per group (ticket, tile pools), zero between launches
   uint16_t* out;
   int cap, qcap, n_fp, n_q, gh, hb, splits, nwf;
   float c;  // softmax scale * log2(e)
@@ -171,6 +172,21 @@ __device__ __forceinline__ float head_sum(float v) {
   xor32_pair(v, &a, &b); v = a + b;
   return v;
 }
+// all-reduce over the 16 lanes of a lane row (lanes that share lane >> 4)
+__device__ __forceinline__ float row_sum(float v) {
+  v += dpp_f<0x128>(v);   // row_ror:8
+  v += dpp_f<0x124>(v);
+  v += dpp_f<0x122>(v);
+  v += dpp_f<0x121>(v);
+  return v;
+}
+__device__ __forceinline__ float row_max(float v) {
+  v = fmaxf(v, dpp_f<0x128>(v));
+  v = fmaxf(v, dpp_f<0x124>(v));
+  v = fmaxf(v, dpp_f<0x122>(v));
+  v = fmaxf(v, dpp_f<0x121>(v));
+  return v;
+}
 // sum over the four lanes that differ in lane >> 4
 __device__ __forceinline__ float rows_sum(float v) {
   float a, b;
@@ -247,35 +263,81 @@ __device__ __forceinline__ void online_softmax(State<NNT>& st, const float* s, f
   }
 }
 
+// Quantized-row variant: lane row q4 = lane >> 4 is a query head, the 16 lanes of a
+// row hold different tokens; s[u], u = 0..3, are this lane's tokens.  The output
+// accumulators and zacc are laid out by the output step: acc[nt][j] belongs to head
+// j, zacc to head g = lane & 3.
+template <int NNT>
+__device__ __forceinline__ void online_softmax_rows(State<NNT>& st, const float* s, float* p, int g) {
+  float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+  if (__any(mx > st.m + MAX_SLACK)) {
+    mx = row_max(mx);
+    const float m_new = fmaxf(st.m, mx);
+    const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);   // 0 on the first tile (m = -inf)
+#pragma unroll
+    for (int u = 0; u < 4; ++u) st.l[u] *= alpha;
+    float a4[4];
+#pragma unroll
+    for (int gg = 0; gg < 4; ++gg)
+      a4[gg] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(alpha), 16 * gg));
+    const float ag = g == 0 ? a4[0] : g == 1 ? a4[1] : g == 2 ? a4[2] : a4[3];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) st.zacc[i] *= ag;
+#pragma unroll
+    for (int nt = 0; nt < NNT; ++nt) {
+#pragma unroll
+      for (int gg = 0; gg < 4; ++gg) st.acc[nt][gg] *= a4[gg];
+    }
+    st.m = m_new;
+  }
+  const float mref = st.m - (float)PSHIFT;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    p[u] = __builtin_amdgcn_exp2f(s[u] - mref);
+    st.l[u] += p[u];
+  }
+}
+
+constexpr int NWB = 8;   // wavefronts per workgroup
+
 template <bool BF16, int D, int G>
-__global__ void __launch_bounds__(256, 2)
+__global__ void __launch_bounds__(64 * NWB, 2)
 attn_mfma_kernel(const AttnParams P) {
   constexpr int NKC = D / 32, NNT = D / 16, NGC = (D + G - 1) / G;
   constexpr int NGRP = G < 64 ? 64 / G : 1;     // key groups per 64-token tile
-  // fp16 head/tail of q*s per wave.  A 16-byte read per lane touches 16 distinct
-  // chunks (4 heads x 4 lane groups); rows are padded so that the row pitch is 64 or
-  // 192 bytes modulo the 256 bytes of the 64 banks, which spreads the 16 chunks over
-  // all banks.
-  constexpr int QS_ROW = (D * 2) % 256 == 64 || (D * 2) % 256 == 192 ? D : D + 32;
-  static_assert((QS_ROW * 2) % 256 == 64 || (QS_ROW * 2) % 256 == 192, "q*s row pitch");
-  __shared__ __attribute__((aligned(16))) uint16_t qs_lds[4][NGRP][2][4][QS_ROW];
-  __shared__ __attribute__((aligned(16))) uint2 p_lds[4][4][4][4];            // [wave][q4][g][up]: 4 fp16 probabilities
-  __shared__ float o_lds[4][4][D];
-  __shared__ float ml_lds[4][4][2];
-  __shared__ float zs_lds[4][4][4];
+  // fp16 head/tail of q*s per wave, one row per (piece, head).  The 16 lanes of a
+  // lane row read 16 bytes each from nine different rows at the same column; a row
+  // pitch that is an odd number of 16-byte units puts those on different banks.
+  constexpr int QS_ROW = D + 8;
+  static_assert((QS_ROW * 2 / 16) % 2 == 1, "q*s row pitch");
+  __shared__ __attribute__((aligned(16))) uint16_t qs_lds[NWB][NGRP][9][QS_ROW];   // rows 4*piece+head, row 8 = zeros
+  __shared__ __attribute__((aligned(16))) uint16_t p_lds[NWB][2][5][32];            // [wave][32-token step][head, 4 = zeros][token]
+  __shared__ float o_lds[NWB][4][D];
+  __shared__ float ml_lds[NWB][4][2];
+  __shared__ float zs_lds[NWB][4][4];
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nhg = P.gh / P.hb;
-  const int split = blockIdx.x, hsub = blockIdx.y % nhg, bh = blockIdx.y / nhg;
+  // Workgroups are handed to the eight XCDs in turn (linear index mod 8).  When the
+  // number of groups allows it, all splits of one group are placed on one XCD, so
+  // that the partials they exchange at the end meet in that XCD's L2.
+  int split = blockIdx.x, group = blockIdx.y;
+  if (gridDim.y % 8 == 0) {
+    const int L = blockIdx.y * gridDim.x + blockIdx.x;
+    const int r = L >> 3;
+    group = (L & 7) + 8 * (r / (int)gridDim.x);
+    split = r % (int)gridDim.x;
+  }
+  const int hsub = group % nhg, bh = group / nhg;
   const int q4 = lane >> 4, n16 = lane & 15, up = n16 >> 2, g = lane & 3;
   const bool head_ok = g < P.hb;
   const int64_t qrow = ((int64_t)bh * P.gh + hsub * P.hb + (head_ok ? g : 0)) * D;
 
-  const int NW = P.splits * 4, NWF = P.nwf, NWQ = NW - NWF;
-  const int gw = split * 4 + wave;
+  const int NW = P.splits * NWB, NWF = P.nwf, NWQ = NW - NWF;
+  const int gw = split * NWB + wave;
   const int TQ = (P.n_q + 63) >> 6, TF = (P.n_fp + 31) >> 5;
-
+  const int64_t part_base = (((int64_t)bh * P.splits + split) * P.gh + hsub * P.hb) * (D + 4);
   State<NNT> st;
 #pragma unroll
   for (int nt = 0; nt < NNT; ++nt) st.acc[nt] = floatx4{0.f, 0.f, 0.f, 0.f};
@@ -297,29 +359,14 @@ attn_mfma_kernel(const AttnParams P) {
     const int upc = up < NGC ? up : 0;
     const uint32_t code_off = lane * NKC * 4;                 // byte offsets of this lane
     const uint32_t vm_off = (upc * 32 + 8 * q4) * 2;
-    const int c8 = lane >> 2;                                  // channel octet this lane prepares q*s for
+    // Lane roles.  Logits and softmax: lane row q4 is query head q4, lane column n16
+    // is a token of each of the four 16-token tiles.  q*s preparation: head q4,
+    // channel octet n16.  Output step: row n16 = (channel group up, head g) of the
+    // probability operand, token octet q4.
+    const int c8 = n16;
     const bool prep = 8 * c8 < D;
     const uint32_t km_off = (prep ? 8 * c8 : 0) * 2;
-
-    // q of (head g, channels 8*c8..+7): raw pairs for the bias dot products, and
-    // fp16 pairs pre-multiplied by 2^(3-2v) (v = pair index) for the q*s operands
-    uint32_t qraw[4];
-    half2_t qh[4];
-    {
-      uint4 raw = *reinterpret_cast<const uint4*>(P.q + qrow + (prep ? 8 * c8 : 0));
-      if (!prep || !head_ok) raw = make_uint4(0, 0, 0, 0);
-      qraw[0] = raw.x; qraw[1] = raw.y; qraw[2] = raw.z; qraw[3] = raw.w;
-      const float f[4] = {8.f, 2.f, 0.5f, 0.125f};
-#pragma unroll
-      for (int v = 0; v < 4; ++v)
-        qh[v] = half2_t{(_Float16)(lo_T<BF16>(qraw[v]) * f[v]), (_Float16)(hi_T<BF16>(qraw[v]) * f[v])};
-    }
-    const float c21 = P.c * 2097152.f;        // codes enter as code * 2^-24, q*s as 2^3 q s
-    // slot offsets: token slot j of this lane is element i = 4*(up&1) + j of its
-    // lane group in the output step, whose codes sit at position v = i >> 1
-    float offs[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) offs[j] = (float)(3 - 2 * (2 * (up & 1) + (j >> 1)));
+    const bool headq_ok = q4 < P.hb;
 
     struct Tile {
       Words<NKC> kc[2], vc[2];
@@ -348,6 +395,67 @@ attn_mfma_kernel(const AttnParams P) {
       return T;
     };
 
+
+    // Tile schedule.  The first two tiles of a wavefront are fixed (wq and wq + NWQ)
+    // and their loads go out before anything else touches memory.  The later tiles
+    // are dealt out dynamically, so that wavefronts that start late or see slower
+    // memory take fewer of them: tile 2 * NWQ + v * NSUB + j belongs to pool j (NSUB pools, fewer when there are fewer wavefronts), and
+    // the wavefronts with wq % NSUB == j (one or two per workgroup, spread over the
+    // whole chip) draw v from that pool's counter.  Several pools because atomics on
+    // one address are serialised at a rate that a single counter could not sustain.
+    // A draw is issued a whole tile ahead of its use and before that tile's loads:
+    // loads and atomics return in issue order, so waiting for the drawn index does not
+    // wait for the loads behind it.  The draw is a buffer atomic over a 4-byte buffer:
+    // only lane 0 is in range, the other lanes are dropped by the bounds check, and no
+    // branch is needed (the join of a branch would make the compiler wait for every
+    // outstanding load).
+    const int nsub = NWQ < NSUB ? NWQ : NSUB;   // every pool needs a wavefront that draws from it
+    const int sub = wq % nsub;
+    const __amdgpu_buffer_rsrc_t pool = __builtin_amdgcn_make_buffer_rsrc(
+        P.counters + (group * CTR_LINES + 1 + sub) * CTR_LINE, 0, 4, 0x00020000);
+    auto draw = [&]() {   // raw counter value in lane 0
+      return __builtin_amdgcn_raw_ptr_buffer_atomic_add_i32(1, pool, lane * 4, 0, 0);
+    };
+    auto drawn_tile = [&](int k) { return 2 * NWQ + __builtin_amdgcn_readfirstlane(k) * nsub + sub; };
+    int ta = wq, tb = wq + NWQ;
+    Tile A;
+    if (ta < TQ) A = load_tile(ta);
+
+    // q of (head q4, channels 8*c8..+7): raw pairs for the bias dot products, and
+    // fp16 pairs pre-multiplied by 2^(3-2v) (v = pair index) for the q*s operands
+    uint32_t qraw[4];
+    half2_t qh[4];
+    {
+      const int64_t qrow_q = ((int64_t)bh * P.gh + hsub * P.hb + (headq_ok ? q4 : 0)) * D;
+      uint4 raw = *reinterpret_cast<const uint4*>(P.q + qrow_q + (prep ? 8 * c8 : 0));
+      if (!prep || !headq_ok) raw = make_uint4(0, 0, 0, 0);
+      qraw[0] = raw.x; qraw[1] = raw.y; qraw[2] = raw.z; qraw[3] = raw.w;
+      const float f[4] = {8.f, 2.f, 0.5f, 0.125f};
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        qh[v] = half2_t{(_Float16)(lo_T<BF16>(qraw[v]) * f[v]), (_Float16)(hi_T<BF16>(qraw[v]) * f[v])};
+    }
+    const float c21 = P.c * 2097152.f;        // codes enter as code * 2^-24, q*s as 2^3 q s
+    // slot offsets: this lane's token of tile u is token x = 16*(u&1) + n16 of its
+    // 32-token output step, element i = 4*(x/16) + x%4 of its lane group there, whose
+    // codes sit at position v = i >> 1
+    float offs[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) offs[u] = (float)(3 - 2 * (2 * (u & 1) + ((n16 & 3) >> 1)));
+
+    // rows of the q*s operand: matrix row n16 = 4*head + piece, pieces 2 and 3 are zero
+    const uint16_t* qs_rd = &qs_lds[wave][0][(n16 & 3) < 2 ? 4 * (n16 & 3) + (n16 >> 2) : 8][8 * q4];
+    uint16_t* qs_wr = &qs_lds[wave][0][q4][8 * c8];
+    // probabilities: written per (head q4, token), read per (head g, token octet q4);
+    // lanes of absent channel groups read the zero row
+    const uint16_t* p_rd = &p_lds[wave][0][up < NGC ? g : 4][4 * q4];
+    uint16_t* p_wr = &p_lds[wave][0][q4][n16];
+    {
+      for (int e = 0; e < NGRP; ++e)
+        for (int c = lane; c < QS_ROW; c += 64) qs_lds[wave][e][8][c] = 0;
+      if (lane < 32) { p_lds[wave][0][4][lane] = 0; p_lds[wave][1][4][lane] = 0; }
+    }
+
     auto process = [&](const Tile& cur, int t) {
       // ---- q*s (fp16 head and tail) and bias = sum_c q_c z_c for each key group
       float bo[4];
@@ -369,18 +477,17 @@ attn_mfma_kernel(const AttnParams P) {
             l[v] = __builtin_bit_cast(uint32_t, lo);
           }
           if (prep) {
-            *reinterpret_cast<uint4*>(&qs_lds[wave][e][0][g][8 * c8]) = make_uint4(h[0], h[1], h[2], h[3]);
-            *reinterpret_cast<uint4*>(&qs_lds[wave][e][1][g][8 * c8]) = make_uint4(l[0], l[1], l[2], l[3]);
+            *reinterpret_cast<uint4*>(qs_wr + e * (9 * QS_ROW)) = make_uint4(h[0], h[1], h[2], h[3]);
+            *reinterpret_cast<uint4*>(qs_wr + e * (9 * QS_ROW) + 4 * QS_ROW) = make_uint4(l[0], l[1], l[2], l[3]);
           }
-          bias[e] = head_sum(bp) * P.c;
+          bias[e] = row_sum(bp) * P.c;
         }
-        const float b = bias[NGRP == 1 ? 0 : (up * NGRP) >> 2];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) bo[j] = b + offs[j];
+        for (int u = 0; u < 4; ++u) bo[u] = bias[(u * NGRP) >> 2] + offs[u];
       }
       wave_lds_sync();
 
-      // ---- logits: four 16-token tiles x NKC channel chunks, head and tail of q*s
+      // ---- logits: rows (head, piece) x four 16-token tiles, NKC channel chunks each
       floatx4 Du[4];
 #pragma unroll
       for (int u = 0; u < 4; ++u) Du[u] = floatx4{0.f, 0.f, 0.f, 0.f};
@@ -388,43 +495,39 @@ attn_mfma_kernel(const AttnParams P) {
       for (int e = 0; e < NGRP; ++e) {
 #pragma unroll
         for (int kc = 0; kc < NKC; ++kc) {
-          const uint4 bh_ = *reinterpret_cast<const uint4*>(&qs_lds[wave][e][0][g][32 * kc + 8 * q4]);
-          const uint4 bl_ = *reinterpret_cast<const uint4*>(&qs_lds[wave][e][1][g][32 * kc + 8 * q4]);
+          const uint4 qa = *reinterpret_cast<const uint4*>(qs_rd + e * (9 * QS_ROW) + 32 * kc);
 #pragma unroll
           for (int u = e * (4 / NGRP); u < (e + 1) * (4 / NGRP); ++u) {
             const int o = (u & 1) * NKC + kc;
-            const uint4 a = codes_of(cur.kc[u >> 1].w[o >> 1], o & 1);
-            Du[u] = mfma_f16(a, bh_, Du[u]);
-            Du[u] = mfma_f16(a, bl_, Du[u]);
+            const uint4 b = codes_of(cur.kc[u >> 1].w[o >> 1], o & 1);
+            Du[u] = mfma_f16(qa, b, Du[u]);
           }
         }
       }
 
+      // this lane: head q4, token 16*u + n16 of the tile; head and tail rows are j = 0, 1
       float s[4], p[4];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const float x = (up & 1) ? Du[1][j] : Du[0][j];
-        const float y = (up & 1) ? Du[3][j] : Du[2][j];
-        s[j] = fmaf((up & 2) ? y : x, c21, bo[j]);
-      }
+      for (int u = 0; u < 4; ++u) s[u] = fmaf(Du[u][0] + Du[u][1], c21, bo[u]);
       const bool partial = 64 * t + 64 > P.n_q;
       if (partial) {
-        const int tok0 = 64 * t + 16 * up + 4 * q4;
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-          if (tok0 + j >= P.n_q) s[j] = -INFINITY;
+        for (int u = 0; u < 4; ++u)
+          if (64 * t + 16 * u + n16 >= P.n_q) s[u] = -INFINITY;
       }
-      online_softmax<NNT, true>(st, s, p);
+      online_softmax_rows<NNT>(st, s, p, g);
 
       // ---- hand the probabilities (fp16) to the lanes that feed the output step
-      p_lds[wave][q4][g][up] = make_uint2(pack_f16(p[0], p[1]), pack_f16(p[2], p[3]));
+#pragma unroll
+      for (int u = 0; u < 4; ++u) p_wr[(u >> 1) * (5 * 32) + 16 * (u & 1)] = __builtin_bit_cast(uint16_t, (_Float16)p[u]);
       wave_lds_sync();
 
       // ---- output: two 32-token steps x NNT channel tiles
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks) {
-        const uint4 pw = *reinterpret_cast<const uint4*>(&p_lds[wave][q4][g][2 * ks]);
-        const uint32_t ph[4] = {pw.x, pw.y, pw.z, pw.w};      // slots (0,1) (2,3) (4,5) (6,7)
+        const uint2 pa = *reinterpret_cast<const uint2*>(p_rd + ks * (5 * 32));        // tokens 4*q4 .. +3
+        const uint2 pb = *reinterpret_cast<const uint2*>(p_rd + ks * (5 * 32) + 16);   // tokens 16 + 4*q4 .. +3
+        const uint32_t ph[4] = {pa.x, pa.y, pb.x, pb.y};      // slots (0,1) (2,3) (4,5) (6,7)
         uint4 vsr = cur.vs[ks], vzr = cur.vz[ks];
         if (partial) {   // slots beyond n_q hold unspecified bits: keep them out of the sums
           uint32_t keep[4];
@@ -446,11 +549,6 @@ attn_mfma_kernel(const AttnParams P) {
           aw[v] = __builtin_bit_cast(uint32_t, pp * pair_to_f16<BF16>(vsw[v]));
           st.zacc[v] = __builtin_amdgcn_fdot2(pp, pair_to_f16<BF16>(vzw[v]), st.zacc[v], false);
         }
-        if constexpr (NGC < 4) {
-          const uint32_t live = up < NGC ? 0xFFFFFFFFu : 0u;   // rows of absent channel groups
-#pragma unroll
-          for (int v = 0; v < 4; ++v) aw[v] &= live;
-        }
         const uint4 a = make_uint4(aw[0], aw[1], aw[2], aw[3]);
 #pragma unroll
         for (int nt = 0; nt < NNT; ++nt) {
@@ -461,26 +559,26 @@ attn_mfma_kernel(const AttnParams P) {
       wave_lds_sync();   // p_lds and qs_lds are rewritten by the next tile
     };
 
-    if (wq < TQ) {
-      int t = wq;
-      Tile A = load_tile(t);
+    if (ta < TQ) {
+      int kd = draw();
       while (true) {
-        const int t1 = t + NWQ;
-        Tile B = load_tile(t1 < TQ ? t1 : t);
-        process(A, t);
-        if (t1 >= TQ) break;
-        const int t2 = t1 + NWQ;
-        A = load_tile(t2 < TQ ? t2 : t1);
-        process(B, t1);
-        if (t2 >= TQ) break;
-        t = t2;
+        Tile B = load_tile(tb < TQ ? tb : ta);
+        process(A, ta);
+        if (tb >= TQ) break;
+        ta = drawn_tile(kd);
+        kd = draw();
+        A = load_tile(ta < TQ ? ta : tb);
+        process(B, tb);
+        if (ta >= TQ) break;
+        tb = drawn_tile(kd);
+        kd = draw();
       }
     }
     // canonical partial of this wavefront: o[g][c], m[g], l[g]
     float lsum = 0.f;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) lsum += st.l[j] * __builtin_amdgcn_exp2f(-offs[j]);
-    const float l_tot = head_sum(lsum);
+    for (int u = 0; u < 4; ++u) lsum += st.l[u] * __builtin_amdgcn_exp2f(-offs[u]);
+    const float l_tot = row_sum(lsum);
     float zs = 0.f;
     {
       const float f[4] = {0.125f, 0.5f, 2.f, 8.f};   // 2^-(3-2v)
@@ -489,7 +587,7 @@ attn_mfma_kernel(const AttnParams P) {
     }
     zs = rows_sum(zs);
     if (q4 == 0) zs_lds[wave][up][g] = zs;
-    if (lane < 4) { ml_lds[wave][g][0] = st.m; ml_lds[wave][g][1] = l_tot; }
+    if (n16 == 0) { ml_lds[wave][q4][0] = st.m; ml_lds[wave][q4][1] = l_tot; }
     wave_lds_sync();
 #pragma unroll
     for (int nt = 0; nt < NNT; ++nt) {
@@ -583,21 +681,21 @@ attn_mfma_kernel(const AttnParams P) {
     }
   }
   __syncthreads();
-  // merge the four wavefronts; write this split's partial: per head D floats, then m, l
-  for (int idx = threadIdx.x; idx < P.hb * D; idx += 256) {
+  // merge the wavefronts; write this split's partial: per head D floats, then m, l
+  for (int idx = threadIdx.x; idx < P.hb * D; idx += 64 * NWB) {
     const int gg = idx / D, c = idx % D;
     float M = -INFINITY;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) M = fmaxf(M, ml_lds[w][gg][0]);
+    for (int w = 0; w < NWB; ++w) M = fmaxf(M, ml_lds[w][gg][0]);
     float acc = 0.f, L = 0.f;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
+    for (int w = 0; w < NWB; ++w) {
       const float mw = ml_lds[w][gg][0];
       const float a = mw == -INFINITY ? 0.f : exp2f(mw - M);
       acc += a * o_lds[w][gg][c];
       L += a * ml_lds[w][gg][1];
     }
-    const int64_t base = (((int64_t)bh * P.splits + split) * P.gh + hsub * P.hb + gg) * (D + 2);
+    const int64_t base = part_base + gg * (D + 4);
     st_dev(P.ws + base + c, acc);
     if (c == 0) { st_dev(P.ws + base + D, M); st_dev(P.ws + base + D + 1, L); }
   }
@@ -610,26 +708,59 @@ attn_mfma_kernel(const AttnParams P) {
   __builtin_amdgcn_s_waitcnt(0);   // vmcnt(0): the write-through stores above have been acknowledged
   __syncthreads();
   if (threadIdx.x == 0) {
-    const int old = __hip_atomic_fetch_add(P.counters + blockIdx.y, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    int* ctr = P.counters + group * (CTR_LINES * CTR_LINE);
+    const int old = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     is_last = old == P.splits - 1;
-    if (is_last)   // every other workgroup has drawn already: re-arm for the next launch
-      __hip_atomic_store(P.counters + blockIdx.y, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (is_last) {   // every other workgroup is past its tile loop and its ticket: re-arm for the next launch
+#pragma unroll
+      for (int i = 0; i < CTR_LINES; ++i)
+        __hip_atomic_store(ctr + i * CTR_LINE, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
   }
   __syncthreads();
   if (!is_last) return;
+  static_assert(NWB * 4 * D >= 4 * 256, "o_lds too small for the merge weights");
   float* w_lds = &o_lds[0][0][0];              // [4][256] weights, o_lds is free again
-  const int64_t gstride = (int64_t)P.gh * (D + 2);
-  const float* gbase = P.ws + ((int64_t)bh * P.splits * P.gh + hsub * P.hb) * (D + 2);
-  if (wave < P.hb) {                            // wavefront w: weights of head w
-    const float* hb_ = gbase + wave * (D + 2);
-    float m[4], l[4], mx = -INFINITY;
+  // Wavefront w merges head w.  The partials are read past the caches (device-
+  // coherent loads), 16 bytes per lane so that the address unit sees few, wide
+  // instructions, and all of them are issued before anything is consumed: the merge
+  // then costs about one memory round trip.
+  if (wave < P.hb) {
+    constexpr int PR = D + 4;                    // floats per partial row
+    constexpr int C4 = D / 4;                    // 16-byte chunks per row
+    constexpr int RPI = 64 / C4;                 // rows covered by one wave-level load
+    constexpr int PASS = 32;                     // splits per pass
+    constexpr int NI = PASS / RPI;               // loads per pass
+    const int rows = P.splits;
+    const int64_t gstride = (int64_t)P.gh * PR;  // floats between consecutive splits
+    const float* gbase = P.ws + ((int64_t)bh * P.splits * P.gh + hsub * P.hb + wave) * PR;
+    // buffer descriptor over this head's rows of all splits: out-of-range lanes read 0
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(gbase), 0, (int)(((int64_t)(rows - 1) * gstride + PR) * 4), 0x00020000);
+    const int r = lane / C4, c4 = lane % C4;
+    const int oob = 0x7FFFFFF0;
+    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+    typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+    u32x2 ml[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       const int sidx = lane + 64 * k;
-      m[k] = -INFINITY; l[k] = 0.f;
-      if (sidx < P.splits) { m[k] = ld_dev(hb_ + sidx * gstride + D); l[k] = ld_dev(hb_ + sidx * gstride + D + 1); }
-      mx = fmaxf(mx, m[k]);
+      ml[k] = __builtin_amdgcn_raw_buffer_load_b64(rs, sidx < rows ? (int)((sidx * gstride + D) * 4) : oob, 0, 16);
     }
+    u32x4 ov[NI];
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int sidx = i * RPI + r;
+      ov[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, (r < RPI && sidx < rows) ? (int)((sidx * gstride + 4 * c4) * 4) : oob, 0, 16);
+    }
+    float m[4], l[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const bool live = lane + 64 * k < rows;
+      m[k] = live ? __uint_as_float(ml[k][0]) : -INFINITY;
+      l[k] = live ? __uint_as_float(ml[k][1]) : 0.f;
+    }
+    float mx = fmaxf(fmaxf(m[0], m[1]), fmaxf(m[2], m[3]));
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
     float ls = 0.f;
@@ -641,29 +772,38 @@ attn_mfma_kernel(const AttnParams P) {
     }
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) ls += __shfl_xor(ls, o);
-    if (lane == 0) ml_lds[wave][0][0] = ls;
-  }
-  __syncthreads();
-  if (wave < P.hb) {                            // wavefront w: output channels of head w
-    constexpr int NCH = (D + 63) / 64;
-    const float* hb_ = gbase + wave * (D + 2);
-    float acc[NCH];
+    wave_lds_sync();
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int s0 = 0;;) {
 #pragma unroll
-    for (int k = 0; k < NCH; ++k) acc[k] = 0.f;
-#pragma unroll 8
-    for (int sidx = 0; sidx < P.splits; ++sidx) {
-      const float w = w_lds[wave * 256 + sidx];
+      for (int i = 0; i < NI; ++i) {
+        const int sidx = s0 + i * RPI + r;
+        const float w = (r < RPI && sidx < rows) ? w_lds[wave * 256 + sidx] : 0.f;
 #pragma unroll
-      for (int k = 0; k < NCH; ++k) {
-        const int c = lane + 64 * k;
-        if (c < D) acc[k] = fmaf(w, ld_dev(hb_ + sidx * gstride + c), acc[k]);
+        for (int e = 0; e < 4; ++e) acc[e] = fmaf(w, __uint_as_float(ov[i][e]), acc[e]);
+      }
+      s0 += PASS;
+      if (s0 >= rows) break;
+#pragma unroll
+      for (int i = 0; i < NI; ++i) {
+        const int sidx = s0 + i * RPI + r;
+        ov[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, (r < RPI && sidx < rows) ? (int)((sidx * gstride + 4 * c4) * 4) : oob, 0, 16);
       }
     }
-    const float inv = 1.0f / ml_lds[wave][0][0];
+    // add the RPI row classes: lanes c4, c4 + C4, ...
 #pragma unroll
-    for (int k = 0; k < NCH; ++k) {
-      const int c = lane + 64 * k;
-      if (c < D) P.out[((int64_t)bh * P.gh + hsub * P.hb + wave) * D + c] = f2t<BF16>(acc[k] * inv);
+    for (int e = 0; e < 4; ++e) {
+      float t = acc[e];
+#pragma unroll
+      for (int k = 1; k < RPI; ++k) t += __shfl(acc[e], (lane + k * C4) & 63);
+      acc[e] = t;
+    }
+    if (lane < C4) {
+      const float inv = 1.0f / ls;
+      uint16_t* o = P.out + ((int64_t)bh * P.gh + hsub * P.hb + wave) * D + 4 * c4;
+      const uint32_t lo = (uint32_t)f2t<BF16>(acc[0] * inv) | ((uint32_t)f2t<BF16>(acc[1] * inv) << 16);
+      const uint32_t hi = (uint32_t)f2t<BF16>(acc[2] * inv) | ((uint32_t)f2t<BF16>(acc[3] * inv) << 16);
+      *reinterpret_cast<uint2*>(o) = make_uint2(lo, hi);
     }
   }
 }
@@ -679,8 +819,8 @@ combine_kernel(const float* __restrict__ ws, uint16_t* __restrict__ out, int d, 
   __shared__ float stat[2];
   const int bhq = blockIdx.x, tid = threadIdx.x;
   const int bh = bhq / gh, g = bhq % gh;
-  const int64_t stride = (int64_t)gh * (d + 2);
-  const float* base = ws + ((int64_t)bh * splits * gh + g) * (d + 2);
+  const int64_t stride = (int64_t)gh * (d + 4);
+  const float* base = ws + ((int64_t)bh * splits * gh + g) * (d + 4);
   // weights: w_s = 2^(m_s - M); L = sum_s w_s l_s
   float m = -INFINITY, l = 0.f;
   if (tid < splits) { m = base[tid * stride + d]; l = base[tid * stride + d + 1]; }
@@ -729,9 +869,9 @@ hipError_t launch_combine(const Shape& s, const float* ws, void* out, int splits
 template <bool BF16, int D>
 static hipError_t launch_mfma_dg(const Shape& s, const AttnParams& P, dim3 grid, hipStream_t st) {
   switch (s.G) {
-    case 32: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 32>), grid, dim3(256), 0, st, P); break;
-    case 64: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 64>), grid, dim3(256), 0, st, P); break;
-    default: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 128>), grid, dim3(256), 0, st, P); break;
+    case 32: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 32>), grid, dim3(64 * NWB), 0, st, P); break;
+    case 64: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 64>), grid, dim3(64 * NWB), 0, st, P); break;
+    default: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 128>), grid, dim3(64 * NWB), 0, st, P); break;
   }
   return launch_status(__func__);
 }

@@ -110,7 +110,7 @@ attn_ref_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_f
       acc += a * sm_o[w][g][c];
       L += a * sm_ml[w][g][1];
     }
-    const int64_t base = (((int64_t)bh * splits + split) * gh + hsub * HB + g) * (d + 2);
+    const int64_t base = (((int64_t)bh * splits + split) * gh + hsub * HB + g) * (d + 4);
     ws[base + c] = acc;
     if (c == 0) { ws[base + d] = M; ws[base + d + 1] = L; }
   }

@@ -19,10 +19,13 @@ lq_status make_shape(const lq_config* cfg, Shape* s);
 // Upper bound on context splits per (b, kv head) that decode_attn may use.
 int max_splits(const Shape& s);
 
-// The workspace starts with one ticket counter per (b, kv head, head group), padded
-// to 256 bytes; the splits' partial results follow.
+// The workspace starts with the counters of the attention kernel: per (b, kv head,
+// head group) CTR_LINES cache lines of CTR_LINE ints, each holding one counter in
+// its first int: line 0 the ticket counter, lines 1..NSUB the tile pool counters.
+// The splits' partial results follow.
+constexpr int CTR_LINE = 32, NSUB = 8, CTR_LINES = 1 + NSUB;
 inline size_t counter_bytes(const Shape& s) {
-  return (((size_t)s.B * s.Hkv * s.gh * sizeof(int)) + 255) / 256 * 256;
+  return (size_t)s.B * s.Hkv * s.gh * CTR_LINES * CTR_LINE * sizeof(int);
 }
 hipError_t launch_workspace_init(const Shape& s, void* ws, hipStream_t st);
 
