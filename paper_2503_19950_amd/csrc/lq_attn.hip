@@ -12,15 +12,19 @@ hipError_t launch_decode_attn_ref(const Shape& s, const lq_cache& c, const void*
 hipError_t launch_decode_attn_mfma(const Shape& s, const lq_cache& c, const void* q, float scale,
                                    void* out, void* ws, const lq_plan& plan, hipStream_t st);
 
-constexpr int WPB = 8;   // wavefronts per workgroup of the attention kernel
-
 static int env_int(const char* name, int dflt) {
   const char* v = getenv(name);
   return v && *v ? atoi(v) : dflt;
 }
 
-// Context splits and the share of wavefronts that walks the fp rows.  Work is
-// counted in bytes: a 64-slot quantized tile against a 32-row fp unit.
+// Launch shape: wavefronts per workgroup (8 or 4), context splits per (b, kv head,
+// head group), and the share of wavefronts that walks the fp rows.  Work is counted
+// in units of one 64-slot quantized tile; a 32-row fp unit weighs its bytes relative
+// to that.  A compute unit holds eight wavefronts of this kernel, i.e. one
+// workgroup of 8 or two of 4; the candidate shapes are ranked by
+//     rounds * (units per wavefront + fixed) + merge cost per split,
+// rounds = how many times the chip has to be refilled, fixed = start-up and merge
+// tail of a workgroup expressed in tiles.
 void plan_decode(const Shape& s, int n_fp, int n_q, lq_plan* plan) {
   const int TQ = (n_q + 63) / 64, TF = (n_fp + 31) / 32;
   const double q_tile_bytes = 64.0 * (s.d / 2 + 4 * s.ngc + 4.0 * s.d / s.G);
@@ -29,13 +33,26 @@ void plan_decode(const Shape& s, int n_fp, int n_q, lq_plan* plan) {
   const double units = TQ + r * TF;
   const int hb = s.gh % 4 == 0 ? 4 : (s.gh % 2 == 0 ? 2 : 1);
   const int groups = s.B * s.Hkv * (s.gh / hb);
-  static const int target_blocks = env_int("LOGQUANT_ATTN_BLOCKS", 256);
-  static const int min_tiles = env_int("LOGQUANT_ATTN_MIN_TILES", 2);
-  int splits = (target_blocks + groups - 1) / groups;
-  const int by_work = (int)ceil(units / (WPB * (double)min_tiles));
-  if (splits > by_work) splits = by_work;
-  if (splits > max_splits(s)) splits = max_splits(s);
-  if (splits < 1) splits = 1;
+  static const int cus = env_int("LOGQUANT_ATTN_CUS", 256);
+  static const int force_wpb = env_int("LOGQUANT_ATTN_WPB", 0);
+  static const int force_splits = env_int("LOGQUANT_ATTN_SPLITS", 0);
+  const double fixed = 2.5, per_split = 0.02;
+  int best_wpb = 8, best_splits = 1;
+  double best = 1e300;
+  for (int wpb = 8; wpb >= 4; wpb -= 4) {
+    if (force_wpb && wpb != force_wpb) continue;
+    const int slots = cus * (8 / wpb);
+    int smax = (int)ceil(units / wpb);            // at least one unit per wavefront
+    if (smax > max_splits(s)) smax = max_splits(s);
+    if (smax < 1) smax = 1;
+    for (int sp = 1; sp <= smax; ++sp) {
+      if (force_splits && sp != force_splits && force_splits <= smax) continue;
+      const int rounds = (sp * groups + slots - 1) / slots;
+      const double t = rounds * (units / ((double)sp * wpb) + fixed) + per_split * sp;
+      if (t < best - 1e-9) { best = t; best_wpb = wpb; best_splits = sp; }
+    }
+  }
+  const int splits = best_splits, WPB = best_wpb;
   const int NW = WPB * splits;
   int nwf = (int)lround(NW * (r * TF) / units);
   if (TF > 0) {

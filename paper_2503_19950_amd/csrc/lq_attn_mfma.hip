@@ -42,6 +42,8 @@
 // The partials and the counter are accessed with device-scope relaxed atomics
 // (write-through stores, cache-bypassing loads): a device-scope fence would write
 // back and invalidate a whole L2 per workgroup, which costs more than the kernel.
+#include <stdlib.h>
+
 #include "lq_device.h"
 #include "lq_internal.h"
 
@@ -67,6 +69,7 @@ struct AttnParams {
   int* counters;      // CTR_LINES lines per group (ticket, tile pools), zero between launches
   uint16_t* out;
   int cap, qcap, n_fp, n_q, gh, hb, splits, nwf;
+  int dynamic;        // 0: static tile schedule only
   float c;  // softmax scale * log2(e)
 };
 
@@ -298,9 +301,9 @@ __device__ __forceinline__ void online_softmax_rows(State<NNT>& st, const float*
   }
 }
 
-constexpr int NWB = 8;   // wavefronts per workgroup
-
-template <bool BF16, int D, int G>
+// NWB: wavefronts per workgroup (8, or 4 when there are enough (b, kv head) groups to
+// put two workgroups on every compute unit).
+template <bool BF16, int D, int G, int NWB>
 __global__ void __launch_bounds__(64 * NWB, 2)
 attn_mfma_kernel(const AttnParams P) {
   constexpr int NKC = D / 32, NNT = D / 16, NGC = (D + G - 1) / G;
@@ -396,27 +399,35 @@ attn_mfma_kernel(const AttnParams P) {
     };
 
 
-    // Tile schedule.  The first two tiles of a wavefront are fixed (wq and wq + NWQ)
-    // and their loads go out before anything else touches memory.  The later tiles
-    // are dealt out dynamically, so that wavefronts that start late or see slower
-    // memory take fewer of them: tile 2 * NWQ + v * NSUB + j belongs to pool j (NSUB pools, fewer when there are fewer wavefronts), and
-    // the wavefronts with wq % NSUB == j (one or two per workgroup, spread over the
-    // whole chip) draw v from that pool's counter.  Several pools because atomics on
+    // Tile schedule.  The first two tiles of a wavefront are fixed (wq, wq + NWQ) and
+    // the loads of the first go out before anything else touches memory.  The later
+    // tiles are dealt out dynamically, so that wavefronts that start late or see
+    // slower memory take fewer of them: tile 2 * NWQ + v * NSUB + j belongs to
+    // pool j (NSUB pools), and the wavefronts with wq % NSUB == j, spread over the
+    // whole chip, draw v from that pool's counter.  Several pools because atomics on
     // one address are serialised at a rate that a single counter could not sustain.
-    // A draw is issued a whole tile ahead of its use and before that tile's loads:
-    // loads and atomics return in issue order, so waiting for the drawn index does not
-    // wait for the loads behind it.  The draw is a buffer atomic over a 4-byte buffer:
-    // only lane 0 is in range, the other lanes are dropped by the bounds check, and no
+    // A draw is issued a whole tile ahead of its use and before that tile's loads: loads
+    // and atomics return in issue order, so waiting for the drawn index does not wait
+    // for the loads behind it.  The draw is a buffer atomic over a 4-byte buffer: only
+    // lane 0 is in range, the other lanes are dropped by the bounds check, and no
     // branch is needed (the join of a branch would make the compiler wait for every
     // outstanding load).
-    const int nsub = NWQ < NSUB ? NWQ : NSUB;   // every pool needs a wavefront that draws from it
+    // With few tiles per wavefront, or no more wavefronts than pools, there is nothing
+    // to balance: the schedule is then static (tile wq + v * NWQ) and the atomic is
+    // aimed out of range.
+    const bool dyn = P.dynamic && NWQ > NSUB && TQ >= 5 * NWQ;
+    const int nsub = dyn ? NSUB : NWQ;
     const int sub = wq % nsub;
+    int v_static = 0;
     const __amdgpu_buffer_rsrc_t pool = __builtin_amdgcn_make_buffer_rsrc(
         P.counters + (group * CTR_LINES + 1 + sub) * CTR_LINE, 0, 4, 0x00020000);
     auto draw = [&]() {   // raw counter value in lane 0
-      return __builtin_amdgcn_raw_ptr_buffer_atomic_add_i32(1, pool, lane * 4, 0, 0);
+      return __builtin_amdgcn_raw_ptr_buffer_atomic_add_i32(1, pool, dyn ? lane * 4 : 4, 0, 0);
     };
-    auto drawn_tile = [&](int k) { return 2 * NWQ + __builtin_amdgcn_readfirstlane(k) * nsub + sub; };
+    auto drawn_tile = [&](int k) {
+      const int v = dyn ? __builtin_amdgcn_readfirstlane(k) : v_static++;
+      return 2 * NWQ + v * nsub + sub;
+    };
     int ta = wq, tb = wq + NWQ;
     Tile A;
     if (ta < TQ) A = load_tile(ta);
@@ -866,22 +877,22 @@ hipError_t launch_combine(const Shape& s, const float* ws, void* out, int splits
   return launch_status(__func__);
 }
 
-template <bool BF16, int D>
+template <bool BF16, int D, int NWB>
 static hipError_t launch_mfma_dg(const Shape& s, const AttnParams& P, dim3 grid, hipStream_t st) {
   switch (s.G) {
-    case 32: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 32>), grid, dim3(64 * NWB), 0, st, P); break;
-    case 64: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 64>), grid, dim3(64 * NWB), 0, st, P); break;
-    default: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 128>), grid, dim3(64 * NWB), 0, st, P); break;
+    case 32: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 32, NWB>), grid, dim3(64 * NWB), 0, st, P); break;
+    case 64: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 64, NWB>), grid, dim3(64 * NWB), 0, st, P); break;
+    default: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 128, NWB>), grid, dim3(64 * NWB), 0, st, P); break;
   }
   return launch_status(__func__);
 }
 
-template <bool BF16>
+template <bool BF16, int NWB>
 static hipError_t launch_mfma_d(const Shape& s, const AttnParams& P, dim3 grid, hipStream_t st) {
   switch (s.d) {
-    case 64: return launch_mfma_dg<BF16, 64>(s, P, grid, st);
-    case 96: return launch_mfma_dg<BF16, 96>(s, P, grid, st);
-    default: return launch_mfma_dg<BF16, 128>(s, P, grid, st);
+    case 64: return launch_mfma_dg<BF16, 64, NWB>(s, P, grid, st);
+    case 96: return launch_mfma_dg<BF16, 96, NWB>(s, P, grid, st);
+    default: return launch_mfma_dg<BF16, 128, NWB>(s, P, grid, st);
   }
 }
 
@@ -901,8 +912,12 @@ hipError_t launch_decode_attn_mfma(const Shape& s, const lq_cache& c, const void
   P.hb = s.gh % 4 == 0 ? 4 : (s.gh % 2 == 0 ? 2 : 1);
   P.splits = plan.splits; P.nwf = plan.fp_waves;
   P.c = scale * 1.4426950408889634f;
+  static const int dynamic = [] { const char* v = getenv("LOGQUANT_ATTN_DYNAMIC"); return v && *v ? atoi(v) : 1; }();
+  P.dynamic = dynamic;
   dim3 grid(plan.splits, s.B * s.Hkv * (s.gh / P.hb));
-  return s.bf16 ? launch_mfma_d<true>(s, P, grid, st) : launch_mfma_d<false>(s, P, grid, st);
+  if (plan.waves_per_block == 4)
+    return s.bf16 ? launch_mfma_d<true, 4>(s, P, grid, st) : launch_mfma_d<false, 4>(s, P, grid, st);
+  return s.bf16 ? launch_mfma_d<true, 8>(s, P, grid, st) : launch_mfma_d<false, 8>(s, P, grid, st);
 }
 
 }  // namespace lq
