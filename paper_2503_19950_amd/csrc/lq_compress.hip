@@ -33,17 +33,16 @@ __device__ __forceinline__ uint32_t code_of(float x, float z, float s) {
   return s == 0.f ? 0u : c;
 }
 
-// grid (W/G, B*Hkv), block 256.  Dynamic LDS: G * (d + 2) uint16.
+// Quantize the G evicted tokens of group j of slice bh.  256 threads; sm: G * (d + 2)
+// uint16 of LDS, red: 8 * 128 floats.
 template <bool BF16>
-__global__ void __launch_bounds__(256)
-quantize_kernel(const uint16_t* __restrict__ k_fp, const uint16_t* __restrict__ v_fp,
-                const int32_t* __restrict__ pos_fp, uint32_t* __restrict__ k_codes,
-                uint32_t* __restrict__ v_codes, uint16_t* __restrict__ k_scale,
-                uint16_t* __restrict__ k_zero, uint16_t* __restrict__ v_scale,
-                uint16_t* __restrict__ v_zero, int32_t* __restrict__ pos_q, int d, int G, int cap,
-                int qcap, int n_q, int Hkv) {
-  extern __shared__ uint16_t sm[];  // [G][d + 2]; values first, then their codes in place
-  const int j = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x;
+__device__ __forceinline__ void quantize_group(
+    uint16_t* sm, float* red, int j, int bh, const uint16_t* __restrict__ k_fp,
+    const uint16_t* __restrict__ v_fp, const int32_t* __restrict__ pos_fp,
+    uint32_t* __restrict__ k_codes, uint32_t* __restrict__ v_codes, uint16_t* __restrict__ k_scale,
+    uint16_t* __restrict__ k_zero, uint16_t* __restrict__ v_scale, uint16_t* __restrict__ v_zero,
+    int32_t* __restrict__ pos_q, int d, int G, int cap, int qcap, int n_q, int Hkv) {
+  const int tid = threadIdx.x;
   const int nkc = d >> 5, nnt = d >> 4, ngc = (d + G - 1) / G, ld = d + 2;
   const int64_t fp_slice = (int64_t)bh * cap * d;
   const int q0 = n_q + j * G;  // first quantized slot written by this block
@@ -58,21 +57,37 @@ quantize_kernel(const uint16_t* __restrict__ k_fp, const uint16_t* __restrict__ 
     dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
   }
   __syncthreads();
-  if (tid < d) {
-    const int c = tid;
+  // per channel: 256 / d threads each scan a share of the G tokens, exchange their
+  // partial minima and maxima, and then encode their own share
+  {
+    const int parts = 256 / d, c = tid % d, part = tid / d;
+    const int per = G / parts, e0 = part * per;   // d in {64, 96, 128}: parts in {4, 2, 2} divide G
     float mn = INFINITY, mx = -INFINITY;
-    for (int e = 0; e < G; ++e) {
-      const float x = t2f<BF16>(sm[e * ld + c]);
-      mn = fminf(mn, x);
-      mx = fmaxf(mx, x);
+    if (part < parts) {
+      for (int e = e0; e < e0 + per; ++e) {
+        const float x = t2f<BF16>(sm[e * ld + c]);
+        mn = fminf(mn, x);
+        mx = fmaxf(mx, x);
+      }
+      red[part * d + c] = mn;
+      red[(4 + part) * d + c] = mx;
     }
-    float z, s;
-    uint16_t zt, st;
-    group_params<BF16>(mn, mx, &z, &s, &zt, &st);
-    const int64_t mi = ((int64_t)bh * (qcap / G) + q0 / G) * d + c;
-    k_scale[mi] = st;
-    k_zero[mi] = zt;
-    for (int e = 0; e < G; ++e) sm[e * ld + c] = (uint16_t)code_of(t2f<BF16>(sm[e * ld + c]), z, s);
+    __syncthreads();
+    if (part < parts) {
+      for (int pp = 0; pp < parts; ++pp) {
+        mn = fminf(mn, red[pp * d + c]);
+        mx = fmaxf(mx, red[(4 + pp) * d + c]);
+      }
+      float z, sc;
+      uint16_t zt, st;
+      group_params<BF16>(mn, mx, &z, &sc, &zt, &st);
+      if (part == 0) {
+        const int64_t mi = ((int64_t)bh * (qcap / G) + q0 / G) * d + c;
+        k_scale[mi] = st;
+        k_zero[mi] = zt;
+      }
+      for (int e = e0; e < e0 + per; ++e) sm[e * ld + c] = (uint16_t)code_of(t2f<BF16>(sm[e * ld + c]), z, sc);
+    }
   }
   __syncthreads();
   for (int idx = tid; idx < (G >> 5) * 64 * nkc; idx += 256) {
@@ -110,22 +125,36 @@ quantize_kernel(const uint16_t* __restrict__ k_fp, const uint16_t* __restrict__ 
     }
   }
   __syncthreads();
-  for (int idx = tid; idx < G * ngc; idx += 256) {
-    const int e = idx % G, gc = idx / G;
-    const int lo = gc * G, hi = min(lo + G, d);
-    float mn = INFINITY, mx = -INFINITY;
-    for (int c = lo; c < hi; ++c) {
-      const float x = t2f<BF16>(sm[e * ld + c]);
-      mn = fminf(mn, x);
-      mx = fmaxf(mx, x);
+  // per (token, channel group): VP threads each scan a share of the channels; the
+  // shares of one group sit in neighbouring lanes and are combined by lane shuffles
+  {
+    int vp = 1;
+    while (2 * vp * G * ngc <= 256 && vp < 8) vp *= 2;
+    for (int idx = tid; idx < G * ngc * vp; idx += 256) {   // a multiple of vp; all lanes of a group take the same trips
+      const int part = idx % vp, e = (idx / vp) % G, gc = idx / (vp * G);
+      const int lo = gc * G, hi = min(lo + G, d);
+      const int per = (hi - lo + vp - 1) / vp;
+      const int c0 = lo + part * per, c1 = min(c0 + per, hi);
+      float mn = INFINITY, mx = -INFINITY;
+      for (int c = c0; c < c1; ++c) {
+        const float x = t2f<BF16>(sm[e * ld + c]);
+        mn = fminf(mn, x);
+        mx = fmaxf(mx, x);
+      }
+      for (int o = 1; o < vp; o <<= 1) {
+        mn = fminf(mn, __shfl_xor(mn, o));
+        mx = fmaxf(mx, __shfl_xor(mx, o));
+      }
+      float z, sc;
+      uint16_t zt, st;
+      group_params<BF16>(mn, mx, &z, &sc, &zt, &st);
+      if (part == 0) {
+        const int64_t mi = (int64_t)bh * (qcap >> 5) * ngc * 32 + v_meta_index(q0 + e, gc, ngc);
+        v_scale[mi] = st;
+        v_zero[mi] = zt;
+      }
+      for (int c = c0; c < c1; ++c) sm[e * ld + c] = (uint16_t)code_of(t2f<BF16>(sm[e * ld + c]), z, sc);
     }
-    float z, s;
-    uint16_t zt, st;
-    group_params<BF16>(mn, mx, &z, &s, &zt, &st);
-    const int64_t mi = (int64_t)bh * (qcap >> 5) * ngc * 32 + v_meta_index(q0 + e, gc, ngc);
-    v_scale[mi] = st;
-    v_zero[mi] = zt;
-    for (int c = lo; c < hi; ++c) sm[e * ld + c] = (uint16_t)code_of(t2f<BF16>(sm[e * ld + c]), z, s);
   }
   __syncthreads();
   for (int idx = tid; idx < (G >> 5) * 64 * nkc; idx += 256) {
@@ -152,13 +181,12 @@ quantize_kernel(const uint16_t* __restrict__ k_fp, const uint16_t* __restrict__ 
   }
 }
 
-// Kept rows -> rows 0..2W-1 of the other fp buffer.  grid (2W/32, B*Hkv), block 256.
-__global__ void __launch_bounds__(256)
-compact_kernel(const uint16_t* __restrict__ k_old, const uint16_t* __restrict__ v_old,
-               const int32_t* __restrict__ pos_old, uint16_t* __restrict__ k_new,
-               uint16_t* __restrict__ v_new, int32_t* __restrict__ pos_new, int d, int W, int cap,
-               int Hkv) {
-  const int nb = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x;
+// Kept rows -> rows 32*nb .. 32*nb+31 of the other fp buffer of slice bh.  256 threads.
+__device__ __forceinline__ void compact_rows(
+    int nb, int bh, const uint16_t* __restrict__ k_old, const uint16_t* __restrict__ v_old,
+    const int32_t* __restrict__ pos_old, uint16_t* __restrict__ k_new, uint16_t* __restrict__ v_new,
+    int32_t* __restrict__ pos_new, int d, int W, int cap, int Hkv) {
+  const int tid = threadIdx.x;
   const int nkc = d >> 5, nnt = d >> 4;
   const int64_t slice = (int64_t)bh * cap * d;
   for (int idx = tid; idx < 32 * nkc * 4; idx += 256) {
@@ -189,21 +217,49 @@ compact_kernel(const uint16_t* __restrict__ k_old, const uint16_t* __restrict__ 
   }
 }
 
+struct CompressParams {
+  const uint16_t *k_old, *v_old;
+  const int32_t* pos_old;
+  uint16_t *k_new, *v_new;
+  int32_t* pos_new;
+  uint32_t *k_codes, *v_codes;
+  uint16_t *k_scale, *k_zero, *v_scale, *v_zero;
+  int32_t* pos_q;
+  int d, G, W, cap, qcap, n_q, Hkv;
+};
+
+// One launch does both halves of the filtering branch; they read the same buffer and
+// write disjoint ones.  grid (W/G + 2W/32, B*Hkv), block 256: workgroups x < W/G
+// quantize one key group each, the others move 32 kept rows each.
+// Dynamic LDS: G * (d + 2) uint16.
+template <bool BF16>
+__global__ void __launch_bounds__(256) compress_kernel(const CompressParams P) {
+  extern __shared__ uint16_t sm[];  // [G][d + 2]; values first, then their codes in place
+  __shared__ float red[8 * 128];    // partial minima [4][d] and maxima [4][d] of the key channels
+  const int nq = P.W / P.G, bh = blockIdx.y;
+  if ((int)blockIdx.x < nq)
+    quantize_group<BF16>(sm, red, blockIdx.x, bh, P.k_old, P.v_old, P.pos_old, P.k_codes, P.v_codes,
+                         P.k_scale, P.k_zero, P.v_scale, P.v_zero, P.pos_q, P.d, P.G, P.cap, P.qcap,
+                         P.n_q, P.Hkv);
+  else
+    compact_rows(blockIdx.x - nq, bh, P.k_old, P.v_old, P.pos_old, P.k_new, P.v_new, P.pos_new, P.d,
+                 P.W, P.cap, P.Hkv);
+}
+
 hipError_t launch_compress(const Shape& s, const lq_cache& c, hipStream_t st) {
   const int cur = c.cur, alt = cur ^ 1;
+  CompressParams P;
+  P.k_old = (const uint16_t*)c.k_fp[cur]; P.v_old = (const uint16_t*)c.v_fp[cur]; P.pos_old = c.pos_fp[cur];
+  P.k_new = (uint16_t*)c.k_fp[alt]; P.v_new = (uint16_t*)c.v_fp[alt]; P.pos_new = c.pos_fp[alt];
+  P.k_codes = c.k_codes; P.v_codes = c.v_codes;
+  P.k_scale = (uint16_t*)c.k_scale; P.k_zero = (uint16_t*)c.k_zero;
+  P.v_scale = (uint16_t*)c.v_scale; P.v_zero = (uint16_t*)c.v_zero;
+  P.pos_q = c.pos_q;
+  P.d = s.d; P.G = s.G; P.W = s.W; P.cap = s.cap; P.qcap = s.qcap; P.n_q = c.n_q; P.Hkv = s.Hkv;
   const size_t lds = (size_t)s.G * (s.d + 2) * sizeof(uint16_t);
-  dim3 grid(s.W / s.G, s.B * s.Hkv);
-  auto kern = s.bf16 ? quantize_kernel<true> : quantize_kernel<false>;
-  hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, (const uint16_t*)c.k_fp[cur],
-                     (const uint16_t*)c.v_fp[cur], c.pos_fp[cur], c.k_codes, c.v_codes,
-                     (uint16_t*)c.k_scale, (uint16_t*)c.k_zero, (uint16_t*)c.v_scale,
-                     (uint16_t*)c.v_zero, c.pos_q, s.d, s.G, s.cap, s.qcap, c.n_q, s.Hkv);
-  hipError_t e = launch_status(__func__);
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(compact_kernel, dim3(2 * s.W / 32, s.B * s.Hkv), dim3(256), 0, st,
-                     (const uint16_t*)c.k_fp[cur], (const uint16_t*)c.v_fp[cur], c.pos_fp[cur],
-                     (uint16_t*)c.k_fp[alt], (uint16_t*)c.v_fp[alt], c.pos_fp[alt], s.d, s.W, s.cap,
-                     s.Hkv);
+  dim3 grid(s.W / s.G + 2 * s.W / 32, s.B * s.Hkv);
+  if (s.bf16) hipLaunchKernelGGL(compress_kernel<true>, grid, dim3(256), lds, st, P);
+  else hipLaunchKernelGGL(compress_kernel<false>, grid, dim3(256), lds, st, P);
   return launch_status(__func__);
 }
 
