@@ -35,7 +35,10 @@ def parse():
 
 def build_states(wl, cfg_id, copies):
     """Cache copy 0 is 5 tokens short of a full window (it fires one compress during
-    the timed region), the others have just been compressed: L tokens."""
+    the timed region), the others have just been compressed: L tokens.  The states are
+    built with logquant_prefill (bit-identical to streaming the tokens through
+    logquant_append / logquant_compress; tests/test_gpu_prefill.py), which is timed on
+    the way.  Returns (cfg, caches, prefill record)."""
     import torch
     from paper_2503_19950_amd import binding, inputs
     from tests.gpu_util import to_dev
@@ -44,21 +47,40 @@ def build_states(wl, cfg_id, copies):
     while qcap % 64:
         qcap += W
     cfg = binding.make_config(wl["B"], wl["Hq"], wl["Hkv"], wl["d"], wl["F"], wl["G"], dt, qcap)
-    dc = binding.DeviceCache(cfg)
-    near = L - 5
-    step = 8 * 3 * W
-    t0 = 0
-    while t0 < near:
-        t1 = min(near, t0 + step)
+    tdt = torch.bfloat16 if dt == "bf16" else torch.float16
+    Kd = torch.empty((wl["B"], wl["Hkv"], L, wl["d"]), dtype=tdt, device="cuda:0")
+    Vd = torch.empty_like(Kd)
+    step = 1 << 14
+    for t0 in range(0, L, step):
+        t1 = min(L, t0 + step)
         K, V = inputs.batch_kv(cfg_id, t0, t1, wl)
-        dc.stream_in(to_dev(K, dt), to_dev(V, dt))
-        t0 = t1
-    first = dc.clone()
-    K, V = inputs.batch_kv(cfg_id, near, L, wl)
-    dc.stream_in(to_dev(K, dt), to_dev(V, dt))
+        Kd[:, :, t0:t1] = to_dev(K, dt)
+        Vd[:, :, t0:t1] = to_dev(V, dt)
+    near = L - 5
+    first = binding.DeviceCache(cfg)
+    first.prefill(Kd[:, :, :near].contiguous(), Vd[:, :, :near].contiguous())
+    dc = binding.DeviceCache(cfg)
+    stream = torch.cuda.current_stream()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(8)]
+    for i in range(4):                                   # same buffers, counts rewound: 1 warm-up + 3 timed
+        dc.set_counts((0, 0, 0))
+        ev[2 * i].record(stream)
+        dc.prefill(Kd, Vd)
+        ev[2 * i + 1].record(stream)
+    torch.cuda.synchronize()
+    ms = sorted(ev[2 * i].elapsed_time(ev[2 * i + 1]) for i in range(1, 4))[1]
+    n_q = dc.c.n_q
+    sizes = binding.logquant_sizes(cfg)
+    bh = wl["B"] * wl["Hkv"]
+    written = bh * (n_q * (wl["d"] // 2 + 4 * -(-wl["d"] // wl["G"])) + n_q // wl["G"] * 4 * wl["d"]
+                    + dc.c.n_fp * 4 * wl["d"])
+    read = 2 * Kd.numel() * 2
+    prefill = {"ms_per_call": ms, "tokens_per_s": wl["B"] * L / (ms * 1e-3),
+               "algorithmic_bytes": read + written, "GBps": (read + written) / (ms * 1e-3) / 1e9}
+    del Kd, Vd, sizes
     caches = [first, dc] + [dc.clone() for _ in range(copies - 2)]
     torch.cuda.synchronize()
-    return cfg, caches
+    return cfg, caches, prefill
 
 
 def main():
@@ -82,7 +104,7 @@ def main():
     plan0 = binding.logquant_decode_plan(cfg_probe, 2 * W, (L - 2 * W) // W * W)
     copies = a.copies or max(2, min(16, -(-(1 << 30) // max(1, plan0.bytes_read))))
     t_build = time.time()
-    cfg, caches = build_states(wl, a.workload, copies)
+    cfg, caches, prefill = build_states(wl, a.workload, copies)
     t_build = time.time() - t_build
 
     # per-step inputs: one new token per sequence and one query, seeded
@@ -197,6 +219,7 @@ def main():
                      "in_step_loop_event_pair_us": attn_event_us},
         "compress_us_per_call": float(np.mean(comp)) if comp else None,
         "token_heads_per_s": wl["B"] * wl["Hkv"] * L / (ms_per_step * 1e-3),
+        "prefill": prefill,
         "state_build_s": t_build,
     }
     if a.calibration_copy:

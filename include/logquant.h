@@ -151,6 +151,31 @@ lq_status logquant_append(const lq_config *cfg, lq_cache *cache, const void *k_n
 lq_status logquant_compress(const lq_config *cfg, lq_cache *cache, void *workspace,
                             void *stream);
 
+/* Bulk prefill: the state that Algorithm 1 reaches after L calls of
+ * logquant_append(.., 1) on an empty cache, with logquant_compress run each time the
+ * list becomes full (3W rows), produced from the whole prompt in one launch.  The
+ * result is bit-identical to that sequence of calls: the same rows stay at original
+ * precision in the same logical order, the evicted rows of each filtering event are
+ * quantized in the same groups (Sec. 2.5; Fig. 6 caption) and stored in the same
+ * slots.
+ *   k, v : DEVICE [B][Hkv][L][d] T, row-major (as for logquant_append with n_new = L).
+ * Requires an empty cache (n_fp == n_q == 0, else LQ_ERR_STATE), L >= 1 (else
+ * LQ_ERR_SHAPE) and E*W <= q_capacity for the E = 0 (L < 3W) or floor((L-3W)/W)+1
+ * events (else LQ_ERR_CAPACITY).  On success n_q = E*W, n_fp = L - E*W, and the live fp
+ * buffer is unchanged (cache->cur). */
+lq_status logquant_prefill(const lq_config *cfg, lq_cache *cache, const void *k, const void *v,
+                           int32_t L, void *stream);
+
+/* Algorithm 1 in closed form (pure host arithmetic, no config needed): the positions
+ * that L appends with window W (filtering as soon as the list holds 3W rows) leave
+ * in the original-precision list (logical order: pos_fp, *n_fp entries, fewer than
+ * 3W) and hand to the quantizer (eviction order: pos_q, *n_q entries).  HOST arrays:
+ * pos_fp needs room for min(L, 3W) ints, pos_q for max(0, L - 2W) ints; either may be
+ * null to get only the counts.
+ * Returns LQ_ERR_SHAPE for W < 1 or L < 0. */
+lq_status logquant_prefill_positions(int32_t W, int32_t L, int32_t *pos_fp, int32_t *n_fp,
+                                     int32_t *pos_q, int32_t *n_q);
+
 /* Decode attention, Eq. 2 with Eq. 6's scaling, over the whole cache:
  *   out[b][h] = softmax_t( scale * q[b][h] . k_t ) applied to v_t,
  * t running over the n_fp original-precision rows and the n_q dequantized rows

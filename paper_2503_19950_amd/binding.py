@@ -46,7 +46,8 @@ class lq_plan(C.Structure):
 
 
 EXPORTS = ("logquant_sizes", "logquant_workspace_bytes", "logquant_workspace_init", "logquant_append", "logquant_compress",
-           "logquant_decode_attn", "logquant_decode_plan", "logquant_status_string")
+           "logquant_prefill", "logquant_prefill_positions", "logquant_decode_attn", "logquant_decode_plan",
+           "logquant_status_string")
 
 if not os.path.exists(LIB_PATH):
     raise ImportError("liblogquant.so is not built: run `python -m paper_2503_19950_amd.build` "
@@ -64,6 +65,12 @@ _lib.logquant_append.argtypes = [C.POINTER(lq_config), C.POINTER(lq_cache), C.c_
 _lib.logquant_append.restype = C.c_int
 _lib.logquant_compress.argtypes = [C.POINTER(lq_config), C.POINTER(lq_cache), C.c_void_p, C.c_void_p]
 _lib.logquant_compress.restype = C.c_int
+_lib.logquant_prefill.argtypes = [C.POINTER(lq_config), C.POINTER(lq_cache), C.c_void_p, C.c_void_p, C.c_int32,
+                                  C.c_void_p]
+_lib.logquant_prefill.restype = C.c_int
+_lib.logquant_prefill_positions.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
+                                            C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+_lib.logquant_prefill_positions.restype = C.c_int
 _lib.logquant_decode_attn.argtypes = [C.POINTER(lq_config), C.POINTER(lq_cache), C.c_void_p, C.c_float,
                                       C.c_void_p, C.c_void_p, C.c_void_p]
 _lib.logquant_decode_attn.restype = C.c_int
@@ -118,6 +125,22 @@ def logquant_append(cfg, cache, k_new, v_new, n_new, stream=0):
 
 def logquant_compress(cfg, cache, workspace=None, stream=0):
     return _lib.logquant_compress(_p(cfg), _p(cache), _ptr(workspace), stream)
+
+
+def logquant_prefill(cfg, cache, k, v, L, stream=0):
+    return _lib.logquant_prefill(_p(cfg), _p(cache), _ptr(k), _ptr(v), int(L), stream)
+
+
+def logquant_prefill_positions(W, L):
+    """-> (status, pos_fp list, pos_q list); host arithmetic only."""
+    n_fp, n_q = C.c_int32(0), C.c_int32(0)
+    st = _lib.logquant_prefill_positions(int(W), int(L), None, C.byref(n_fp), None, C.byref(n_q))
+    if st != LQ_OK:
+        return st, None, None
+    a = (C.c_int32 * max(1, n_fp.value))()
+    q = (C.c_int32 * max(1, n_q.value))()
+    st = _lib.logquant_prefill_positions(int(W), int(L), a, C.byref(n_fp), q, C.byref(n_q))
+    return st, list(a[:n_fp.value]), list(q[:n_q.value])
 
 
 def logquant_decode_attn(cfg, cache, q, softmax_scale, out, workspace, stream=0):
@@ -216,6 +239,11 @@ class DeviceCache:
 
     def compress(self):
         self._check(logquant_compress(self.cfg, self.c, self.workspace, self._stream()), "logquant_compress")
+
+    def prefill(self, K, V):
+        """K, V: [B][Hkv][L][d] tensors of the cache dtype, contiguous; the cache must be empty."""
+        assert K.is_contiguous() and V.is_contiguous()
+        self._check(logquant_prefill(self.cfg, self.c, K, V, K.shape[2], self._stream()), "logquant_prefill")
 
     def stream_in(self, K, V):
         """Append [B][Hkv][n][d] rows with the eager trigger: compress whenever the

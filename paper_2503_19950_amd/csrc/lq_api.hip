@@ -3,6 +3,7 @@
 // on machines without a GPU as well.
 #include <stdio.h>
 
+#include "lq_device.h"
 #include "lq_internal.h"
 
 namespace lq {
@@ -139,6 +140,44 @@ lq_status logquant_compress(const lq_config* cfg, lq_cache* cache, void* workspa
   cache->cur ^= 1;
   cache->n_fp = 2 * s.W;
   cache->n_q += s.W;
+  return LQ_OK;
+}
+
+// number of filtering events after L appends (filtering as soon as the list holds 3W)
+static int events_after(int L, int W) { return L < 3 * W ? 0 : (L - 3 * W) / W + 1; }
+
+lq_status logquant_prefill(const lq_config* cfg, lq_cache* cache, const void* k, const void* v,
+                           int32_t L, void* stream) {
+  if (!cfg || !cache || !k || !v) return LQ_ERR_NULL;
+  Shape s;
+  lq_status st = make_shape(cfg, &s);
+  if (st != LQ_OK) return st;
+  if (!cache_ptrs_ok(cache)) return LQ_ERR_NULL;
+  if ((st = cache_state_ok(s, cache)) != LQ_OK) return st;
+  if (L < 1) return LQ_ERR_SHAPE;
+  if (cache->n_fp != 0 || cache->n_q != 0) return LQ_ERR_STATE;
+  const int E = events_after(L, s.W);
+  if ((int64_t)E * s.W > s.qcap) return LQ_ERR_CAPACITY;
+  const int n_fp = L - E * s.W;
+  clear_stale_error();
+  if (launch_prefill(s, *cache, k, v, L, E, n_fp, (hipStream_t)stream) != hipSuccess) return LQ_ERR_HIP;
+  cache->n_fp = n_fp;
+  cache->n_q = E * s.W;
+  return LQ_OK;
+}
+
+lq_status logquant_prefill_positions(int32_t W, int32_t L, int32_t* pos_fp, int32_t* n_fp,
+                                     int32_t* pos_q, int32_t* n_q) {
+  if (W < 1 || L < 0) return LQ_ERR_SHAPE;
+  const int E = events_after(L, W);
+  const int nf = L - E * W, nq = E * W;
+  if (n_fp) *n_fp = nf;
+  if (n_q) *n_q = nq;
+  if (pos_fp)
+    for (int i = 0; i < nf; ++i) pos_fp[i] = fp_position(E, i, W);
+  if (pos_q)
+    for (int e = 1; e <= E; ++e)
+      for (int i = 0; i < W; ++i) pos_q[(e - 1) * W + i] = evicted_position(e, i, W);
   return LQ_OK;
 }
 

@@ -33,29 +33,75 @@ __device__ __forceinline__ uint32_t code_of(float x, float z, float s) {
   return s == 0.f ? 0u : c;
 }
 
-// Quantize the G evicted tokens of group j of slice bh.  256 threads; sm: G * (d + 2)
-// uint16 of LDS, red: 8 * 128 floats.
-template <bool BF16>
+// Where the G rows of one key group come from.
+// (a) the filtering step on a full list: odd logical slots of the live fp buffer
+struct FpSource {
+  const uint16_t* k_fp;   // slice base
+  const uint16_t* v_fp;
+  const int32_t* pos_fp;  // row of this batch entry
+  int j, G, nkc, nnt;
+  __device__ __forceinline__ void stage_keys(uint16_t* sm, int ld) const {
+    for (int idx = threadIdx.x; idx < G * nkc * 4; idx += 256) {
+      const int oct = idx % (nkc * 4), e = idx / (nkc * 4);
+      const int ts = 2 * (j * G + e) + 1;
+      const uint4 v = *reinterpret_cast<const uint4*>(k_fp + k_fp_index(ts, oct * 8, nkc));
+      uint32_t* dst = reinterpret_cast<uint32_t*>(sm + e * ld + oct * 8);
+      dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+    }
+  }
+  // source rows: logical slots 2jG .. 2jG + 2G - 1 (whole 32-slot tiles)
+  __device__ __forceinline__ void stage_values(uint16_t* sm, int ld) const {
+    for (int idx = threadIdx.x; idx < (2 * G >> 5) * nnt * 64; idx += 256) {
+      const int lane = idx & 63, nt = (idx >> 6) % nnt, sb = idx / (64 * nnt);
+      const int qq = lane >> 4, n = lane & 15;
+      const int64_t src = ((((int64_t)((2 * j * G) >> 5) + sb) * nnt + nt) * 64 + lane) * 8;
+      const uint4 v = *reinterpret_cast<const uint4*>(v_fp + src);
+      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int i = 1; i < 8; i += 2) {  // odd element <=> odd logical slot <=> evicted
+        const int x = kperm_inv(8 * qq + i);
+        const int e = (sb * 32 + x - 1) >> 1;
+        sm[e * ld + 16 * nt + n] = (uint16_t)(w[i >> 1] >> 16);
+      }
+    }
+  }
+  __device__ __forceinline__ int position(int e) const { return pos_fp[2 * (j * G + e) + 1]; }
+};
+// (b) bulk prefill: rows of a row-major prompt tensor, at the positions Algorithm 1
+// evicts at event `ev`
+struct PromptSource {
+  const uint16_t* k;      // slice base, [L][d]
+  const uint16_t* v;
+  const int* posl;        // LDS: positions of the G rows
+  int G, d;
+  __device__ __forceinline__ void stage_keys(uint16_t* sm, int ld) const { stage(k, sm, ld); }
+  __device__ __forceinline__ void stage_values(uint16_t* sm, int ld) const { stage(v, sm, ld); }
+  __device__ __forceinline__ void stage(const uint16_t* x, uint16_t* sm, int ld) const {
+    const int octs = d >> 3;
+    for (int idx = threadIdx.x; idx < G * octs; idx += 256) {
+      const int oct = idx % octs, e = idx / octs;
+      const uint4 val = *reinterpret_cast<const uint4*>(x + (int64_t)posl[e] * d + oct * 8);
+      uint32_t* dst = reinterpret_cast<uint32_t*>(sm + e * ld + oct * 8);
+      dst[0] = val.x; dst[1] = val.y; dst[2] = val.z; dst[3] = val.w;
+    }
+  }
+  __device__ __forceinline__ int position(int e) const { return posl[e]; }
+};
+
+// Quantize one key group (G rows) of slice bh into quantized slots q0 .. q0+G-1.
+// 256 threads; sm: G * (d + 2) uint16 of LDS, red: 8 * 128 floats.
+template <bool BF16, class Src>
 __device__ __forceinline__ void quantize_group(
-    uint16_t* sm, float* red, int j, int bh, const uint16_t* __restrict__ k_fp,
-    const uint16_t* __restrict__ v_fp, const int32_t* __restrict__ pos_fp,
-    uint32_t* __restrict__ k_codes, uint32_t* __restrict__ v_codes, uint16_t* __restrict__ k_scale,
-    uint16_t* __restrict__ k_zero, uint16_t* __restrict__ v_scale, uint16_t* __restrict__ v_zero,
-    int32_t* __restrict__ pos_q, int d, int G, int cap, int qcap, int n_q, int Hkv) {
+    uint16_t* sm, float* red, const Src& src, int bh, int q0, uint32_t* __restrict__ k_codes,
+    uint32_t* __restrict__ v_codes, uint16_t* __restrict__ k_scale, uint16_t* __restrict__ k_zero,
+    uint16_t* __restrict__ v_scale, uint16_t* __restrict__ v_zero, int32_t* __restrict__ pos_q, int d,
+    int G, int qcap, int Hkv) {
   const int tid = threadIdx.x;
-  const int nkc = d >> 5, nnt = d >> 4, ngc = (d + G - 1) / G, ld = d + 2;
-  const int64_t fp_slice = (int64_t)bh * cap * d;
-  const int q0 = n_q + j * G;  // first quantized slot written by this block
+  const int nkc = d >> 5, ngc = (d + G - 1) / G, ld = d + 2;
   const int64_t code_base = ((int64_t)bh * (qcap >> 5) + (q0 >> 5)) * 64 * nkc;
 
   // ---------------- keys ----------------
-  for (int idx = tid; idx < G * nkc * 4; idx += 256) {
-    const int oct = idx % (nkc * 4), e = idx / (nkc * 4);
-    const int ts = 2 * (j * G + e) + 1;
-    const uint4 v = *reinterpret_cast<const uint4*>(k_fp + fp_slice + k_fp_index(ts, oct * 8, nkc));
-    uint32_t* dst = reinterpret_cast<uint32_t*>(sm + e * ld + oct * 8);
-    dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
-  }
+  src.stage_keys(sm, ld);
   __syncthreads();
   // per channel: 256 / d threads each scan a share of the G tokens, exchange their
   // partial minima and maxima, and then encode their own share
@@ -110,20 +156,7 @@ __device__ __forceinline__ void quantize_group(
   __syncthreads();
 
   // ---------------- values ----------------
-  // source rows of this block: logical slots 2jG .. 2jG + 2G - 1 (whole 32-slot tiles)
-  for (int idx = tid; idx < (2 * G >> 5) * nnt * 64; idx += 256) {
-    const int lane = idx & 63, nt = (idx >> 6) % nnt, sb = idx / (64 * nnt);
-    const int qq = lane >> 4, n = lane & 15;
-    const int64_t src = fp_slice + ((((int64_t)((2 * j * G) >> 5) + sb) * nnt + nt) * 64 + lane) * 8;
-    const uint4 v = *reinterpret_cast<const uint4*>(v_fp + src);
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-    for (int i = 1; i < 8; i += 2) {  // odd element <=> odd logical slot <=> evicted
-      const int x = kperm_inv(8 * qq + i);
-      const int e = (sb * 32 + x - 1) >> 1;
-      sm[e * ld + 16 * nt + n] = (uint16_t)(w[i >> 1] >> 16);
-    }
-  }
+  src.stage_values(sm, ld);
   __syncthreads();
   // per (token, channel group): VP threads each scan a share of the channels; the
   // shares of one group sit in neighbouring lanes and are combined by lane shuffles
@@ -176,8 +209,7 @@ __device__ __forceinline__ void quantize_group(
   // positions of the evicted tokens, once per batch row
   if (bh % Hkv == 0) {
     const int b = bh / Hkv;
-    for (int e = tid; e < G; e += 256)
-      pos_q[(int64_t)b * qcap + q0 + e] = pos_fp[b * cap + 2 * (j * G + e) + 1];
+    for (int e = tid; e < G; e += 256) pos_q[(int64_t)b * qcap + q0 + e] = src.position(e);
   }
 }
 
@@ -237,13 +269,17 @@ __global__ void __launch_bounds__(256) compress_kernel(const CompressParams P) {
   extern __shared__ uint16_t sm[];  // [G][d + 2]; values first, then their codes in place
   __shared__ float red[8 * 128];    // partial minima [4][d] and maxima [4][d] of the key channels
   const int nq = P.W / P.G, bh = blockIdx.y;
-  if ((int)blockIdx.x < nq)
-    quantize_group<BF16>(sm, red, blockIdx.x, bh, P.k_old, P.v_old, P.pos_old, P.k_codes, P.v_codes,
-                         P.k_scale, P.k_zero, P.v_scale, P.v_zero, P.pos_q, P.d, P.G, P.cap, P.qcap,
-                         P.n_q, P.Hkv);
-  else
+  if ((int)blockIdx.x < nq) {
+    const int j = blockIdx.x;
+    const int64_t fp_slice = (int64_t)bh * P.cap * P.d;
+    const FpSource src{P.k_old + fp_slice, P.v_old + fp_slice, P.pos_old + (bh / P.Hkv) * P.cap,
+                       j, P.G, P.d >> 5, P.d >> 4};
+    quantize_group<BF16>(sm, red, src, bh, P.n_q + j * P.G, P.k_codes, P.v_codes, P.k_scale, P.k_zero,
+                         P.v_scale, P.v_zero, P.pos_q, P.d, P.G, P.qcap, P.Hkv);
+  } else {
     compact_rows(blockIdx.x - nq, bh, P.k_old, P.v_old, P.pos_old, P.k_new, P.v_new, P.pos_new, P.d,
                  P.W, P.cap, P.Hkv);
+  }
 }
 
 hipError_t launch_compress(const Shape& s, const lq_cache& c, hipStream_t st) {
@@ -260,6 +296,90 @@ hipError_t launch_compress(const Shape& s, const lq_cache& c, hipStream_t st) {
   dim3 grid(s.W / s.G + 2 * s.W / 32, s.B * s.Hkv);
   if (s.bf16) hipLaunchKernelGGL(compress_kernel<true>, grid, dim3(256), lds, st, P);
   else hipLaunchKernelGGL(compress_kernel<false>, grid, dim3(256), lds, st, P);
+  return launch_status(__func__);
+}
+
+// ---- bulk prefill ---------------------------------------------------------------
+// The state Algorithm 1 (filtering as soon as the list is full) reaches after L
+// appends, computed from the whole prompt in one launch.  Which position ends up in
+// which slot is known in closed form (list_entry / evicted_position), so every key
+// group of every event is independent: grid (E * W/G + ceil(n_fp/32), B*Hkv), block
+// 256; workgroups x < E*W/G quantize key group x % (W/G) of event x / (W/G) + 1
+// exactly as the filtering step would have, the others place 32 fp rows each.
+struct PrefillParams {
+  const uint16_t *k, *v;          // [B*Hkv][L][d]
+  uint16_t *k_fp, *v_fp;
+  int32_t* pos_fp;
+  uint32_t *k_codes, *v_codes;
+  uint16_t *k_scale, *k_zero, *v_scale, *v_zero;
+  int32_t* pos_q;
+  int d, G, W, cap, qcap, Hkv, L, E, n_fp;
+};
+
+template <bool BF16>
+__global__ void __launch_bounds__(256) prefill_kernel(const PrefillParams P) {
+  extern __shared__ uint16_t sm[];
+  __shared__ float red[8 * 128];
+  __shared__ int posl[128];
+  const int tid = threadIdx.x, bh = blockIdx.y;
+  const int per_event = P.W / P.G, nqb = P.E * per_event;
+  const int64_t prompt = (int64_t)bh * P.L * P.d;
+  if ((int)blockIdx.x < nqb) {
+    const int ev = blockIdx.x / per_event + 1, j = blockIdx.x % per_event;
+    if (tid < P.G) posl[tid] = evicted_position(ev, j * P.G + tid, P.W);
+    __syncthreads();
+    const PromptSource src{P.k + prompt, P.v + prompt, posl, P.G, P.d};
+    quantize_group<BF16>(sm, red, src, bh, (ev - 1) * P.W + j * P.G, P.k_codes, P.v_codes, P.k_scale,
+                         P.k_zero, P.v_scale, P.v_zero, P.pos_q, P.d, P.G, P.qcap, P.Hkv);
+    return;
+  }
+  const int nb = blockIdx.x - nqb;
+  const int nkc = P.d >> 5, nnt = P.d >> 4;
+  const int64_t slice = (int64_t)bh * P.cap * P.d;
+  if (tid < 32) {
+    const int tn = nb * 32 + tid;
+    posl[tid] = tn < P.n_fp ? fp_position(P.E, tn, P.W) : -1;
+  }
+  __syncthreads();
+  for (int idx = tid; idx < 32 * nkc * 4; idx += 256) {
+    const int x = idx & 31, oct = idx >> 5;
+    const int p = posl[x];
+    if (p >= 0)
+      *reinterpret_cast<uint4*>(P.k_fp + slice + k_fp_index(nb * 32 + x, oct * 8, nkc)) =
+          *reinterpret_cast<const uint4*>(P.k + prompt + (int64_t)p * P.d + oct * 8);
+  }
+  for (int idx = tid; idx < nnt * 64; idx += 256) {
+    const int lane = idx & 63, nt = idx >> 6;
+    const int qq = lane >> 4, n = lane & 15;
+    uint32_t w[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int p = posl[kperm_inv(8 * qq + i)];
+      const uint32_t e = p >= 0 ? P.v[prompt + (int64_t)p * P.d + 16 * nt + n] : 0u;
+      w[i >> 1] |= e << (16 * (i & 1));
+    }
+    *reinterpret_cast<uint4*>(P.v_fp + slice + (((int64_t)nb * nnt + nt) * 64 + lane) * 8) =
+        make_uint4(w[0], w[1], w[2], w[3]);
+  }
+  if (bh % P.Hkv == 0 && tid < 32 && posl[tid] >= 0)
+    P.pos_fp[(bh / P.Hkv) * P.cap + nb * 32 + tid] = posl[tid];
+}
+
+hipError_t launch_prefill(const Shape& s, const lq_cache& c, const void* k, const void* v, int L, int E,
+                          int n_fp, hipStream_t st) {
+  PrefillParams P;
+  P.k = (const uint16_t*)k; P.v = (const uint16_t*)v;
+  P.k_fp = (uint16_t*)c.k_fp[c.cur]; P.v_fp = (uint16_t*)c.v_fp[c.cur]; P.pos_fp = c.pos_fp[c.cur];
+  P.k_codes = c.k_codes; P.v_codes = c.v_codes;
+  P.k_scale = (uint16_t*)c.k_scale; P.k_zero = (uint16_t*)c.k_zero;
+  P.v_scale = (uint16_t*)c.v_scale; P.v_zero = (uint16_t*)c.v_zero;
+  P.pos_q = c.pos_q;
+  P.d = s.d; P.G = s.G; P.W = s.W; P.cap = s.cap; P.qcap = s.qcap; P.Hkv = s.Hkv;
+  P.L = L; P.E = E; P.n_fp = n_fp;
+  const size_t lds = (size_t)s.G * (s.d + 2) * sizeof(uint16_t);
+  dim3 grid(E * (s.W / s.G) + (n_fp + 31) / 32, s.B * s.Hkv);
+  if (s.bf16) hipLaunchKernelGGL(prefill_kernel<true>, grid, dim3(256), lds, st, P);
+  else hipLaunchKernelGGL(prefill_kernel<false>, grid, dim3(256), lds, st, P);
   return launch_status(__func__);
 }
 

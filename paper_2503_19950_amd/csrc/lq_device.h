@@ -50,4 +50,29 @@ __host__ __device__ __forceinline__ int64_t v_meta_index(int t, int gc, int ngc)
   return ((int64_t)(t >> 5) * ngc + gc) * 32 + kperm(t & 31);
 }
 
+// ---- Algorithm 1 in closed form ------------------------------------------------
+// Filtering events are numbered e = 1, 2, ..; event e happens when (e + 2) * W tokens
+// have arrived.  Right after event e the list holds 2W entries: the newest window
+// [(e+1)W, (e+2)W) in its upper half, and in its lower half entry i is what entry 2i
+// was after event e - 1 (the even logical indices survive).  With the convention
+// that "after event 0" entry i is position i:
+//   entry(e, i) = e*W + i                 for W <= i < 2W, e >= 1
+//               = entry(e - 1, 2i)        for i < W, e >= 1
+//               = i                       for e = 0
+__host__ __device__ __forceinline__ int list_entry(int e, int i, int W) {
+  if (i == 0) return 0;   // position 0 never leaves
+  while (e >= 1 && i < W) { i <<= 1; --e; }
+  return e == 0 ? i : e * W + i;
+}
+// position of the i-th row (0 <= i < W) that leaves the list at event e >= 1: odd
+// logical index 2i + 1 of the list as it stood after event e - 1
+__host__ __device__ __forceinline__ int evicted_position(int e, int i, int W) {
+  return list_entry(e - 1, 2 * i + 1, W);
+}
+// position held by logical fp slot i after L tokens (E events happened)
+__host__ __device__ __forceinline__ int fp_position(int E, int i, int W) {
+  if (E == 0) return i;
+  return i < 2 * W ? list_entry(E, i, W) : E * W + i;
+}
+
 }  // namespace lq

@@ -42,6 +42,8 @@ hipError_t launch_status(const char* what);
 hipError_t launch_append(const Shape& s, const lq_cache& c, const void* k_new, const void* v_new,
                          int n_new, hipStream_t st);
 hipError_t launch_compress(const Shape& s, const lq_cache& c, hipStream_t st);
+hipError_t launch_prefill(const Shape& s, const lq_cache& c, const void* k, const void* v, int L, int E,
+                          int n_fp, hipStream_t st);
 hipError_t launch_decode_attn(const Shape& s, const lq_cache& c, const void* q, float scale,
                               void* out, void* ws, const lq_plan& plan, hipStream_t st);
 void plan_decode(const Shape& s, int n_fp, int n_q, lq_plan* plan);

@@ -156,3 +156,45 @@ def build_gpu_sampled(wl, seed_id, L, distinct, q_capacity=None):
         dc.stream_in(to_dev(K, wl["dtype"]), to_dev(V, wl["dtype"]))
         print("  streamed", t1, "of", L, flush=True)
     return dc
+
+
+def new_cache(wl, L, q_capacity=None, poison=False):
+    from paper_2503_19950_amd import binding
+    W = wl["F"] // 2
+    if q_capacity is None:
+        q_capacity = max(64, -(-L // (2 * W)) * 2 * W)
+        while q_capacity % 64 or q_capacity % W:
+            q_capacity += W
+    cfg = binding.make_config(wl["B"], wl["Hq"], wl["Hkv"], wl["d"], wl["F"], wl["G"], wl["dtype"],
+                              q_capacity)
+    return binding.DeviceCache(cfg, poison=poison)
+
+
+def build_gpu_prefill(wl, seed_id, L, q_capacity=None, poison=False, kv=None):
+    """The same state as build_gpu, through one logquant_prefill call."""
+    dc = new_cache(wl, L, q_capacity, poison)
+    K, V = kv if kv is not None else inputs.batch_kv(seed_id, 0, L, wl)
+    dc.prefill(to_dev(K, wl["dtype"]), to_dev(V, wl["dtype"]))
+    return dc
+
+
+def live_buffers(dc, wl):
+    """Every buffer of the cache restricted to what the counts make meaningful, as numpy."""
+    d, G = wl["d"], wl["G"]
+    W = wl["F"] // 2
+    cap, qcap, BH = 3 * W, dc.cfg.q_capacity, wl["B"] * wl["Hkv"]
+    nkc, ngc = d // 32, -(-d // G)
+    cur, n_fp, n_q = dc.c.cur, dc.c.n_fp, dc.c.n_q
+    out = {"counts": np.array([n_fp, n_q])}
+    out["pos_fp"] = _np(dc.pos_fp[cur], np.int32).reshape(wl["B"], cap)[:, :n_fp]
+    out["pos_q"] = _np(dc.pos_q, np.int32).reshape(wl["B"], qcap)[:, :n_q]
+    for which, buf in (("k", dc.k_fp[cur]), ("v", dc.v_fp[cur])):
+        flat = _np(buf, np.uint16).reshape(BH, cap * d)
+        out["fp_" + which] = np.stack([layout.gather_fp(flat[i], which, n_fp, d) for i in range(BH)])
+    out["k_codes"] = _np(dc.k_codes, np.uint32).reshape(BH, -1)[:, :n_q // 32 * 64 * nkc]
+    out["v_codes"] = _np(dc.v_codes, np.uint32).reshape(BH, -1)[:, :n_q // 32 * 64 * nkc]
+    out["k_scale"] = _np(dc.k_scale, np.uint16).reshape(BH, -1)[:, :n_q // G * d]
+    out["k_zero"] = _np(dc.k_zero, np.uint16).reshape(BH, -1)[:, :n_q // G * d]
+    out["v_scale"] = _np(dc.v_scale, np.uint16).reshape(BH, -1)[:, :n_q // 32 * ngc * 32]
+    out["v_zero"] = _np(dc.v_zero, np.uint16).reshape(BH, -1)[:, :n_q // 32 * ngc * 32]
+    return out

@@ -90,6 +90,41 @@ def test_null_and_state_errors_without_a_gpu():
     assert cache.n_fp == 0 and cache.cur == 0                           # nothing was modified
 
 
+def test_prefill_argument_and_state_errors_without_a_gpu():
+    cfg = _cfg()                                # W = 64, q_capacity 1024
+    cache = B.lq_cache()
+    assert B.logquant_prefill(cfg, cache, 4096, 4096, 10) == B.LQ_ERR_NULL     # null cache buffers
+    assert B.logquant_prefill(cfg, cache, None, 4096, 10) == B.LQ_ERR_NULL
+    for name, _ in B.lq_cache._fields_[3:10]:
+        setattr(cache, name, 4096)
+    for i in range(2):
+        cache.k_fp[i] = cache.v_fp[i] = cache.pos_fp[i] = 4096
+    assert B.logquant_prefill(cfg, cache, 4096, 4096, 0) == B.LQ_ERR_SHAPE
+    # 18 events fit 1024 + ... : L = 3W + 15W = 18W -> 16 events -> 1024 slots; one more window does not fit
+    assert B.logquant_prefill(cfg, cache, 4096, 4096, 19 * 64) == B.LQ_ERR_CAPACITY
+    cache.n_fp = 5
+    assert B.logquant_prefill(cfg, cache, 4096, 4096, 10) == B.LQ_ERR_STATE    # cache not empty
+    assert (cache.n_fp, cache.n_q, cache.cur) == (5, 0, 0)
+
+
+@pytest.mark.parametrize("W", [1, 2, 3, 5, 8, 42, 64, 96, 128, 192, 256])
+def test_prefill_positions_match_algorithm_1(W):
+    """The closed form the prefill kernel places rows by (host entry point) against the
+    literal list simulation of Algorithm 1 in the oracle (Sec. 2.5)."""
+    from oracle import selection
+    import random
+    rnd = random.Random(W)
+    Ls = list(range(0, 14 * W + 2)) if W <= 8 else \
+        [0, 1, W, 2 * W, 3 * W - 1, 3 * W, 3 * W + 1, 4 * W - 1, 4 * W, 5 * W + 7, 12 * W, 40 * W + 3] + \
+        [rnd.randrange(1, 70 * W) for _ in range(12)]
+    for L in Ls:
+        st, a, q = B.logquant_prefill_positions(W, L)
+        A, Q = selection.stream_eager(L, W)
+        assert st == B.LQ_OK and a == A and q == Q, (W, L)
+    assert B.logquant_prefill_positions(0, 5)[0] == B.LQ_ERR_SHAPE
+    assert B.logquant_prefill_positions(4, -1)[0] == B.LQ_ERR_SHAPE
+
+
 def test_plan_reports_the_algorithmic_bytes():
     # cfg 1: 128 fp rows and 384 quantized rows per slice, 8 slices:
     # 128*512 + 384*96 bytes each

@@ -25,11 +25,21 @@ def _check(dc, wl, cfg_id, L, slices, q_step=0):
     return ocs
 
 
+def _check_prefill(streamed, wl, cfg_id, L):
+    """logquant_prefill on the whole prompt against the streamed state, every live buffer."""
+    bulk = U.build_gpu_prefill(wl, cfg_id, L, q_capacity=streamed.cfg.q_capacity)
+    a, b = U.live_buffers(streamed, wl), U.live_buffers(bulk, wl)
+    for key in a:
+        assert np.array_equal(a[key], b[key]), key
+    print("  prefill state identical to the streamed one", flush=True)
+
+
 def test_workload_2_llama3_8b_b8_l8192():
     wl = dict(inputs.WORKLOADS[2])
     dc = U.build_gpu(wl, 2, wl["L"])
     assert (dc.c.n_fp, dc.c.n_q) == (256, 7936)
     _check(dc, wl, 2, wl["L"], [(0, 0), (3, 5), (7, 7)])
+    _check_prefill(dc, wl, 2, wl["L"])
 
 
 def test_workload_3_long_context_l131072():
@@ -37,6 +47,7 @@ def test_workload_3_long_context_l131072():
     dc = U.build_gpu(wl, 3, wl["L"])
     assert (dc.c.n_fp, dc.c.n_q) == (512, 130560)
     _check(dc, wl, 3, wl["L"], [(0, 0), (0, 6)])
+    _check_prefill(dc, wl, 3, wl["L"])
 
 
 def test_workload_4_batch64_128_decode_steps():

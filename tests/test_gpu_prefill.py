@@ -1,0 +1,72 @@
+"""GPU parity of logquant_prefill: one call on the whole prompt must leave exactly the
+state that streaming the same tokens through logquant_append / logquant_compress
+leaves (every live buffer bit for bit), which in turn is the oracle's state."""
+import numpy as np
+import pytest
+
+from paper_2503_19950_amd import inputs
+from tests import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    # name, workload, L
+    ("cfg1", dict(inputs.WORKLOADS[1]), 512),
+    ("below_first_event", U.make_wl(B=2, Hq=8, Hkv=2, d=128, G=32, F=128), 50),
+    ("single_token", U.make_wl(B=1, Hq=4, Hkv=1, d=128, G=32, F=64), 1),
+    ("one_before_event", U.make_wl(B=1, Hq=4, Hkv=1, d=128, G=32, F=64), 95),
+    ("exactly_at_event", U.make_wl(B=1, Hq=4, Hkv=1, d=128, G=32, F=64), 96),
+    ("one_after_event", U.make_wl(B=1, Hq=4, Hkv=1, d=128, G=32, F=64), 97),
+    ("many_events_w32", U.make_wl(B=1, Hq=4, Hkv=2, d=128, G=32, F=64), 32 * 41 + 17),
+    ("w96_not_a_power_of_two_d96_bf16", U.make_wl(B=2, Hq=4, Hkv=4, d=96, G=32, F=192, dtype="bf16",
+                                                  dist="laplace"), 96 * 9 + 50),
+    ("d64_g32_gqa2", U.make_wl(B=2, Hq=4, Hkv=2, d=64, G=32, F=64), 333),
+    ("d96_g64_ragged_value_group", U.make_wl(B=1, Hq=4, Hkv=4, d=96, G=64, F=128, dtype="bf16"), 700),
+    ("d128_g128", U.make_wl(B=1, Hq=8, Hkv=1, d=128, G=128, F=256), 900),
+    ("d128_g64_bf16_sinks", U.make_wl(B=1, Hq=8, Hkv=2, d=128, G=64, F=128, dtype="bf16", sinks=4), 1000),
+]
+
+
+@pytest.mark.parametrize("name,wl,L", CASES, ids=[c[0] for c in CASES])
+def test_prefill_equals_streaming_and_oracle(name, wl, L):
+    seed_id = 300 + [c[0] for c in CASES].index(name)
+    print("case", name, "L", L, flush=True)
+    streamed = U.build_gpu(wl, seed_id, L, poison=True)
+    bulk = U.build_gpu_prefill(wl, seed_id, L, poison=True)
+    a, b = U.live_buffers(streamed, wl), U.live_buffers(bulk, wl)
+    for key in a:
+        assert np.array_equal(a[key], b[key]), key
+    ocs = {}
+    for bb in range(wl["B"]):
+        for h in range(wl["Hkv"]):
+            oc = U.build_oracle(wl, seed_id, L, bb, h)
+            U.check_state(bulk, oc, wl, bb, h)
+            ocs[(bb, h)] = oc
+    U.check_attention(bulk, ocs, wl, inputs.queries(seed_id, 0, wl))
+
+
+def test_decode_continues_after_prefill():
+    """Prefill, then decode steps with appends and the next filtering event: the state
+    stays identical to the fully streamed one."""
+    wl = U.make_wl(B=2, Hq=8, Hkv=2, d=128, G=32, F=64)
+    L0, extra = 200, 70                       # W = 32: events at 96, 128, ...; two more fall in the extra steps
+    K, V = inputs.batch_kv(320, 0, L0 + extra, wl)
+    bulk = U.build_gpu_prefill(wl, 320, L0, q_capacity=512, kv=(K[:, :, :L0], V[:, :, :L0]))
+    bulk.stream_in(U.to_dev(K[:, :, L0:], "f16"), U.to_dev(V[:, :, L0:], "f16"))
+    streamed = U.build_gpu(wl, 320, L0 + extra, q_capacity=512)
+    a, b = U.live_buffers(streamed, wl), U.live_buffers(bulk, wl)
+    for key in a:
+        assert np.array_equal(a[key], b[key]), key
+
+
+def test_prefill_errors_with_live_buffers():
+    from paper_2503_19950_amd import binding as B
+    wl = U.make_wl(B=1, Hq=4, Hkv=1, d=128, G=32, F=64)
+    dc = U.new_cache(wl, 0, q_capacity=64)
+    K, V = inputs.batch_kv(330, 0, 200, wl)
+    Kd, Vd = U.to_dev(K, "f16"), U.to_dev(V, "f16")
+    assert B.logquant_prefill(dc.cfg, dc.c, Kd, Vd, 200) == B.LQ_ERR_CAPACITY   # 4 events need 128 slots
+    assert (dc.c.n_fp, dc.c.n_q) == (0, 0)
+    assert B.logquant_prefill(dc.cfg, dc.c, Kd, Vd, 130) == B.LQ_OK             # 2 events: 64 slots
+    assert (dc.c.n_fp, dc.c.n_q) == (66, 64)
+    assert B.logquant_prefill(dc.cfg, dc.c, Kd, Vd, 10) == B.LQ_ERR_STATE       # not empty any more
