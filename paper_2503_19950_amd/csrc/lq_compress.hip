@@ -35,11 +35,13 @@ __device__ __forceinline__ uint32_t code_of(float x, float z, float s) {
 
 // Where the G rows of one key group come from.
 // (a) the filtering step on a full list: odd logical slots of the live fp buffer
+template <int d, int G>
 struct FpSource {
+  static constexpr int nkc = d >> 5, nnt = d >> 4;
   const uint16_t* k_fp;   // slice base
   const uint16_t* v_fp;
   const int32_t* pos_fp;  // row of this batch entry
-  int j, G, nkc, nnt;
+  int j;
   __device__ __forceinline__ void stage_keys(uint16_t* sm, int ld) const {
     for (int idx = threadIdx.x; idx < G * nkc * 4; idx += 256) {
       const int oct = idx % (nkc * 4), e = idx / (nkc * 4);
@@ -69,15 +71,15 @@ struct FpSource {
 };
 // (b) bulk prefill: rows of a row-major prompt tensor, at the positions Algorithm 1
 // evicts at event `ev`
+template <int d, int G>
 struct PromptSource {
   const uint16_t* k;      // slice base, [L][d]
   const uint16_t* v;
   const int* posl;        // LDS: positions of the G rows
-  int G, d;
   __device__ __forceinline__ void stage_keys(uint16_t* sm, int ld) const { stage(k, sm, ld); }
   __device__ __forceinline__ void stage_values(uint16_t* sm, int ld) const { stage(v, sm, ld); }
   __device__ __forceinline__ void stage(const uint16_t* x, uint16_t* sm, int ld) const {
-    const int octs = d >> 3;
+    constexpr int octs = d >> 3;
     for (int idx = threadIdx.x; idx < G * octs; idx += 256) {
       const int oct = idx % octs, e = idx / octs;
       const uint4 val = *reinterpret_cast<const uint4*>(x + (int64_t)posl[e] * d + oct * 8);
@@ -90,14 +92,14 @@ struct PromptSource {
 
 // Quantize one key group (G rows) of slice bh into quantized slots q0 .. q0+G-1.
 // 256 threads; sm: G * (d + 2) uint16 of LDS, red: 8 * 128 floats.
-template <bool BF16, class Src>
+template <bool BF16, int d, int G, class Src>
 __device__ __forceinline__ void quantize_group(
     uint16_t* sm, float* red, const Src& src, int bh, int q0, uint32_t* __restrict__ k_codes,
     uint32_t* __restrict__ v_codes, uint16_t* __restrict__ k_scale, uint16_t* __restrict__ k_zero,
-    uint16_t* __restrict__ v_scale, uint16_t* __restrict__ v_zero, int32_t* __restrict__ pos_q, int d,
-    int G, int qcap, int Hkv) {
+    uint16_t* __restrict__ v_scale, uint16_t* __restrict__ v_zero, int32_t* __restrict__ pos_q,
+    int qcap, int Hkv) {
   const int tid = threadIdx.x;
-  const int nkc = d >> 5, ngc = (d + G - 1) / G, ld = d + 2;
+  constexpr int nkc = d >> 5, ngc = (d + G - 1) / G, ld = d + 2;
   const int64_t code_base = ((int64_t)bh * (qcap >> 5) + (q0 >> 5)) * 64 * nkc;
 
   // ---------------- keys ----------------
@@ -106,8 +108,9 @@ __device__ __forceinline__ void quantize_group(
   // per channel: 256 / d threads each scan a share of the G tokens, exchange their
   // partial minima and maxima, and then encode their own share
   {
-    const int parts = 256 / d, c = tid % d, part = tid / d;
-    const int per = G / parts, e0 = part * per;   // d in {64, 96, 128}: parts in {4, 2, 2} divide G
+    constexpr int parts = 256 / d, per = G / parts;
+    const int c = tid % d, part = tid / d;
+    const int e0 = part * per;   // d in {64, 96, 128}: parts in {4, 2, 2} divide G
     float mn = INFINITY, mx = -INFINITY;
     if (part < parts) {
       for (int e = e0; e < e0 + per; ++e) {
@@ -161,8 +164,7 @@ __device__ __forceinline__ void quantize_group(
   // per (token, channel group): VP threads each scan a share of the channels; the
   // shares of one group sit in neighbouring lanes and are combined by lane shuffles
   {
-    int vp = 1;
-    while (2 * vp * G * ngc <= 256 && vp < 8) vp *= 2;
+    constexpr int vp = 2 * G * ngc > 256 ? 1 : 4 * G * ngc > 256 ? 2 : 8 * G * ngc > 256 ? 4 : 8;
     for (int idx = tid; idx < G * ngc * vp; idx += 256) {   // a multiple of vp; all lanes of a group take the same trips
       const int part = idx % vp, e = (idx / vp) % G, gc = idx / (vp * G);
       const int lo = gc * G, hi = min(lo + G, d);
@@ -264,39 +266,21 @@ struct CompressParams {
 // write disjoint ones.  grid (W/G + 2W/32, B*Hkv), block 256: workgroups x < W/G
 // quantize one key group each, the others move 32 kept rows each.
 // Dynamic LDS: G * (d + 2) uint16.
-template <bool BF16>
+template <bool BF16, int D, int G>
 __global__ void __launch_bounds__(256) compress_kernel(const CompressParams P) {
   extern __shared__ uint16_t sm[];  // [G][d + 2]; values first, then their codes in place
   __shared__ float red[8 * 128];    // partial minima [4][d] and maxima [4][d] of the key channels
-  const int nq = P.W / P.G, bh = blockIdx.y;
+  const int nq = P.W / G, bh = blockIdx.y;
   if ((int)blockIdx.x < nq) {
     const int j = blockIdx.x;
-    const int64_t fp_slice = (int64_t)bh * P.cap * P.d;
-    const FpSource src{P.k_old + fp_slice, P.v_old + fp_slice, P.pos_old + (bh / P.Hkv) * P.cap,
-                       j, P.G, P.d >> 5, P.d >> 4};
-    quantize_group<BF16>(sm, red, src, bh, P.n_q + j * P.G, P.k_codes, P.v_codes, P.k_scale, P.k_zero,
-                         P.v_scale, P.v_zero, P.pos_q, P.d, P.G, P.qcap, P.Hkv);
+    const int64_t fp_slice = (int64_t)bh * P.cap * D;
+    const FpSource<D, G> src{P.k_old + fp_slice, P.v_old + fp_slice, P.pos_old + (bh / P.Hkv) * P.cap, j};
+    quantize_group<BF16, D, G>(sm, red, src, bh, P.n_q + j * G, P.k_codes, P.v_codes, P.k_scale, P.k_zero,
+                               P.v_scale, P.v_zero, P.pos_q, P.qcap, P.Hkv);
   } else {
     compact_rows(blockIdx.x - nq, bh, P.k_old, P.v_old, P.pos_old, P.k_new, P.v_new, P.pos_new, P.d,
                  P.W, P.cap, P.Hkv);
   }
-}
-
-hipError_t launch_compress(const Shape& s, const lq_cache& c, hipStream_t st) {
-  const int cur = c.cur, alt = cur ^ 1;
-  CompressParams P;
-  P.k_old = (const uint16_t*)c.k_fp[cur]; P.v_old = (const uint16_t*)c.v_fp[cur]; P.pos_old = c.pos_fp[cur];
-  P.k_new = (uint16_t*)c.k_fp[alt]; P.v_new = (uint16_t*)c.v_fp[alt]; P.pos_new = c.pos_fp[alt];
-  P.k_codes = c.k_codes; P.v_codes = c.v_codes;
-  P.k_scale = (uint16_t*)c.k_scale; P.k_zero = (uint16_t*)c.k_zero;
-  P.v_scale = (uint16_t*)c.v_scale; P.v_zero = (uint16_t*)c.v_zero;
-  P.pos_q = c.pos_q;
-  P.d = s.d; P.G = s.G; P.W = s.W; P.cap = s.cap; P.qcap = s.qcap; P.n_q = c.n_q; P.Hkv = s.Hkv;
-  const size_t lds = (size_t)s.G * (s.d + 2) * sizeof(uint16_t);
-  dim3 grid(s.W / s.G + 2 * s.W / 32, s.B * s.Hkv);
-  if (s.bf16) hipLaunchKernelGGL(compress_kernel<true>, grid, dim3(256), lds, st, P);
-  else hipLaunchKernelGGL(compress_kernel<false>, grid, dim3(256), lds, st, P);
-  return launch_status(__func__);
 }
 
 // ---- bulk prefill ---------------------------------------------------------------
@@ -316,21 +300,21 @@ struct PrefillParams {
   int d, G, W, cap, qcap, Hkv, L, E, n_fp;
 };
 
-template <bool BF16>
+template <bool BF16, int D, int G>
 __global__ void __launch_bounds__(256) prefill_kernel(const PrefillParams P) {
   extern __shared__ uint16_t sm[];
   __shared__ float red[8 * 128];
   __shared__ int posl[128];
   const int tid = threadIdx.x, bh = blockIdx.y;
-  const int per_event = P.W / P.G, nqb = P.E * per_event;
-  const int64_t prompt = (int64_t)bh * P.L * P.d;
+  const int per_event = P.W / G, nqb = P.E * per_event;
+  const int64_t prompt = (int64_t)bh * P.L * D;
   if ((int)blockIdx.x < nqb) {
     const int ev = blockIdx.x / per_event + 1, j = blockIdx.x % per_event;
-    if (tid < P.G) posl[tid] = evicted_position(ev, j * P.G + tid, P.W);
+    if (tid < G) posl[tid] = evicted_position(ev, j * G + tid, P.W);
     __syncthreads();
-    const PromptSource src{P.k + prompt, P.v + prompt, posl, P.G, P.d};
-    quantize_group<BF16>(sm, red, src, bh, (ev - 1) * P.W + j * P.G, P.k_codes, P.v_codes, P.k_scale,
-                         P.k_zero, P.v_scale, P.v_zero, P.pos_q, P.d, P.G, P.qcap, P.Hkv);
+    const PromptSource<D, G> src{P.k + prompt, P.v + prompt, posl};
+    quantize_group<BF16, D, G>(sm, red, src, bh, (ev - 1) * P.W + j * G, P.k_codes, P.v_codes, P.k_scale,
+                               P.k_zero, P.v_scale, P.v_zero, P.pos_q, P.qcap, P.Hkv);
     return;
   }
   const int nb = blockIdx.x - nqb;
@@ -365,6 +349,58 @@ __global__ void __launch_bounds__(256) prefill_kernel(const PrefillParams P) {
     P.pos_fp[(bh / P.Hkv) * P.cap + nb * 32 + tid] = posl[tid];
 }
 
+// compile-time head dimension and group size: the index arithmetic of the staging,
+// encoding and packing loops is then shifts and masks
+struct CompressLaunch {
+  template <bool BF16, int D, int G>
+  static void go(dim3 grid, size_t lds, hipStream_t st, const CompressParams& P) {
+    hipLaunchKernelGGL((compress_kernel<BF16, D, G>), grid, dim3(256), lds, st, P);
+  }
+};
+struct PrefillLaunch {
+  template <bool BF16, int D, int G>
+  static void go(dim3 grid, size_t lds, hipStream_t st, const PrefillParams& P) {
+    hipLaunchKernelGGL((prefill_kernel<BF16, D, G>), grid, dim3(256), lds, st, P);
+  }
+};
+template <class L, bool BF16, int D, class Params>
+static void dispatch_g(const Shape& s, dim3 grid, size_t lds, hipStream_t st, const Params& P) {
+  switch (s.G) {
+    case 32: L::template go<BF16, D, 32>(grid, lds, st, P); break;
+    case 64: L::template go<BF16, D, 64>(grid, lds, st, P); break;
+    default: L::template go<BF16, D, 128>(grid, lds, st, P); break;
+  }
+}
+template <class L, bool BF16, class Params>
+static void dispatch_d(const Shape& s, dim3 grid, size_t lds, hipStream_t st, const Params& P) {
+  switch (s.d) {
+    case 64: dispatch_g<L, BF16, 64>(s, grid, lds, st, P); break;
+    case 96: dispatch_g<L, BF16, 96>(s, grid, lds, st, P); break;
+    default: dispatch_g<L, BF16, 128>(s, grid, lds, st, P); break;
+  }
+}
+template <class L, class Params>
+static void dispatch_dg(const Shape& s, dim3 grid, size_t lds, hipStream_t st, const Params& P) {
+  if (s.bf16) dispatch_d<L, true>(s, grid, lds, st, P);
+  else dispatch_d<L, false>(s, grid, lds, st, P);
+}
+
+hipError_t launch_compress(const Shape& s, const lq_cache& c, hipStream_t st) {
+  const int cur = c.cur, alt = cur ^ 1;
+  CompressParams P;
+  P.k_old = (const uint16_t*)c.k_fp[cur]; P.v_old = (const uint16_t*)c.v_fp[cur]; P.pos_old = c.pos_fp[cur];
+  P.k_new = (uint16_t*)c.k_fp[alt]; P.v_new = (uint16_t*)c.v_fp[alt]; P.pos_new = c.pos_fp[alt];
+  P.k_codes = c.k_codes; P.v_codes = c.v_codes;
+  P.k_scale = (uint16_t*)c.k_scale; P.k_zero = (uint16_t*)c.k_zero;
+  P.v_scale = (uint16_t*)c.v_scale; P.v_zero = (uint16_t*)c.v_zero;
+  P.pos_q = c.pos_q;
+  P.d = s.d; P.G = s.G; P.W = s.W; P.cap = s.cap; P.qcap = s.qcap; P.n_q = c.n_q; P.Hkv = s.Hkv;
+  const size_t lds = (size_t)s.G * (s.d + 2) * sizeof(uint16_t);
+  dim3 grid(s.W / s.G + 2 * s.W / 32, s.B * s.Hkv);
+  dispatch_dg<CompressLaunch>(s, grid, lds, st, P);
+  return launch_status(__func__);
+}
+
 hipError_t launch_prefill(const Shape& s, const lq_cache& c, const void* k, const void* v, int L, int E,
                           int n_fp, hipStream_t st) {
   PrefillParams P;
@@ -378,8 +414,7 @@ hipError_t launch_prefill(const Shape& s, const lq_cache& c, const void* k, cons
   P.L = L; P.E = E; P.n_fp = n_fp;
   const size_t lds = (size_t)s.G * (s.d + 2) * sizeof(uint16_t);
   dim3 grid(E * (s.W / s.G) + (n_fp + 31) / 32, s.B * s.Hkv);
-  if (s.bf16) hipLaunchKernelGGL(prefill_kernel<true>, grid, dim3(256), lds, st, P);
-  else hipLaunchKernelGGL(prefill_kernel<false>, grid, dim3(256), lds, st, P);
+  dispatch_dg<PrefillLaunch>(s, grid, lds, st, P);
   return launch_status(__func__);
 }
 
