@@ -40,6 +40,11 @@
  *   v_codes     u32   word  ((bh*(q_capacity/32) + t/32)*64 + 16*(k/8) + c%16)*NKC + (c/16)/2,
  *                     k = kperm(t % 32),
  *                     bits [p, p+2) with p = 8*((c/16)%2) + 2*((k%8)/2) + 16*(k%2)
+ *   with bits = 4 a lane owns one word per operand instead of half a word:
+ *   k_codes     u32   word  ((bh*(q_capacity/32) + t/32)*64 + 16*((c%32)/8) + t%16)*2*NKC + o,
+ *                     bits [p, p+4) with p = 4*((c%8)/2) + 16*(c%2)
+ *   v_codes     u32   word  ((bh*(q_capacity/32) + t/32)*64 + 16*(k/8) + c%16)*2*NKC + c/16,
+ *                     bits [p, p+4) with p = 4*((k%8)/2) + 16*(k%2)
  *   k_scale, k_zero   T   index (bh*(q_capacity/G) + t/G)*d + c      one per channel per G slots
  *   v_scale, v_zero   T   index ((bh*(q_capacity/32) + t/32)*NGC + c/G)*32 + kperm(t % 32)
  *   pos_q       i32   index b*q_capacity + t              absolute position of quantized slot t
@@ -48,12 +53,13 @@
  * list; slots 0..n_q-1 of the quantized region are in eviction order.  Content
  * of slots beyond the counts is unspecified and never influences a result.
  *
- * Quantizer (one group of values x_i of type T; a reading, the paper prints no
- * formula): zero z = min x_i (with -0 stored as +0); scale
- * s = T((f32(max) - f32(min)) / 3) with IEEE fp32 subtract and divide and
- * round-to-nearest-even to T; code_i = [x_i - z >= s/2] + [x_i - z >= 3s/2] +
- * [x_i - z >= 5s/2] with the subtraction exact (fp64), all 0 when s == 0;
- * dequantized value z + code_i * s.  Key groups: one channel, G consecutive
+ * Quantizer (one group of values x_i of type T, n = 2^bits - 1 steps; a reading, the
+ * paper prints no formula): zero z = min x_i (with -0 stored as +0); scale
+ * s = T((f32(max) - f32(min)) / n) with IEEE fp32 subtract and divide and
+ * round-to-nearest-even to T; code_i = sum over k = 0..n-1 of [x_i - z >= (k + 1/2) s]
+ * with the subtraction exact (fp64), all 0 when s == 0; dequantized value
+ * z + code_i * s.  bits = 2 is the paper's main setting (INT2, Sec. 3.1), bits = 4 its
+ * higher-precision variant (Sec. 3.2.1, Table 3).  Key groups: one channel, G consecutive
  * quantized slots (G tokens evicted together).  Value groups: one slot, G
  * consecutive channels, the last group shorter when G does not divide d.
  */
@@ -71,7 +77,7 @@ typedef enum {
   LQ_OK = 0,
   LQ_ERR_NULL = 1,        /* a required pointer is null                              */
   LQ_ERR_SHAPE = 2,       /* inconsistent B/Hq/Hkv/d/fp_budget/group/q_capacity       */
-  LQ_ERR_UNSUPPORTED = 3, /* valid in the paper but not built: bits != 2, G not in
+  LQ_ERR_UNSUPPORTED = 3, /* valid in the paper but not built: bits not 2 or 4, G not in
                              {32,64,128}, G not dividing W, d not in {64,96,128}      */
   LQ_ERR_CAPACITY = 4,    /* fp region or quantized region would overflow             */
   LQ_ERR_STATE = 5,       /* call not allowed in the cache's current state            */
@@ -88,7 +94,7 @@ typedef struct {
   int32_t d;           /* head dimension, one of 64, 96, 128                           */
   int32_t fp_budget;   /* F = 2W: fp tokens left after a compress; fp capacity is 3W   */
   int32_t group;       /* G: quantization group size, 32/64/128, must divide W         */
-  int32_t bits;        /* 2                                                            */
+  int32_t bits;        /* 2 or 4                                                       */
   int32_t dtype;       /* lq_dtype                                                     */
   int32_t q_capacity;  /* max quantized slots per sequence; multiple of W and of 64    */
 } lq_config;

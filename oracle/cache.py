@@ -14,8 +14,8 @@ from . import quantizer
 
 
 class SliceCache:
-    def __init__(self, W, G, d, dtype):
-        self.W, self.G, self.d, self.dtype = W, G, d, dtype
+    def __init__(self, W, G, d, dtype, bits=2):
+        self.W, self.G, self.d, self.dtype, self.bits = W, G, d, dtype, bits
         self.pos_fp = []                                   # absolute positions, logical order
         self.K_fp = np.zeros((0, d), dtype=np.float32)     # exact values of T
         self.V_fp = np.zeros((0, d), dtype=np.float32)
@@ -75,8 +75,8 @@ class SliceCache:
         self.K_fp = np.concatenate([self.K_fp[0:2 * W:2], self.K_fp[2 * W:3 * W]], 0)
         self.V_fp = np.concatenate([self.V_fp[0:2 * W:2], self.V_fp[2 * W:3 * W]], 0)
         self.pos_fp = kept
-        kc, ks, kz = quantizer.quantize_keys(K_ev, self.G, self.dtype)
-        vc, vs, vz = quantizer.quantize_values(V_ev, self.G, self.dtype)
+        kc, ks, kz = quantizer.quantize_keys(K_ev, self.G, self.dtype, self.bits)
+        vc, vs, vz = quantizer.quantize_values(V_ev, self.G, self.dtype, self.bits)
         self.pos_q = self.pos_q + evicted
         for name, arr in (("K_codes", kc), ("V_codes", vc), ("K_scale", ks),
                           ("K_zero", kz), ("V_scale", vs), ("V_zero", vz)):

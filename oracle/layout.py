@@ -28,20 +28,30 @@ def v_fp_index(t, c, d):
     return (((t // 32) * nnt + c // 16) * 64 + 16 * (k // 8) + c % 16) * 8 + k % 8
 
 
-def k_code_word_bit(t, c, d):
-    """(word index, first bit) of the 2-bit key code of (slot t, channel c)."""
+def k_code_word_bit(t, c, d, bits=2):
+    """(word index, first bit) of the key code of (slot t, channel c)."""
     nkc = d // 32
     o = ((t % 32) // 16) * nkc + c // 32
-    word = ((t // 32) * 64 + 16 * ((c % 32) // 8) + t % 16) * nkc + o // 2
-    bit = 8 * (o % 2) + 2 * ((c % 8) // 2) + 16 * (c % 2)
+    lane = 16 * ((c % 32) // 8) + t % 16
+    if bits == 2:
+        word = ((t // 32) * 64 + lane) * nkc + o // 2
+        bit = 8 * (o % 2) + 2 * ((c % 8) // 2) + 16 * (c % 2)
+    else:
+        word = ((t // 32) * 64 + lane) * 2 * nkc + o
+        bit = 4 * ((c % 8) // 2) + 16 * (c % 2)
     return word, bit
 
 
-def v_code_word_bit(t, c, d):
+def v_code_word_bit(t, c, d, bits=2):
     nkc = d // 32
     k = kperm(t % 32)
-    word = ((t // 32) * 64 + 16 * (k // 8) + c % 16) * nkc + (c // 16) // 2
-    bit = 8 * ((c // 16) % 2) + 2 * ((k % 8) // 2) + 16 * (k % 2)
+    lane = 16 * (k // 8) + c % 16
+    if bits == 2:
+        word = ((t // 32) * 64 + lane) * nkc + (c // 16) // 2
+        bit = 8 * ((c // 16) % 2) + 2 * ((k % 8) // 2) + 16 * (k % 2)
+    else:
+        word = ((t // 32) * 64 + lane) * 2 * nkc + c // 16
+        bit = 4 * ((k % 8) // 2) + 16 * (k % 2)
     return word, bit
 
 
@@ -60,28 +70,28 @@ def _grid(n, d):
     return t, c
 
 
-def pack_codes(codes, which, n_slots_alloc=None):
-    """codes uint8 [n][d] (values 0..3) -> uint32 words of one slice.
+def pack_codes(codes, which, n_slots_alloc=None, bits=2):
+    """codes uint8 [n][d] (values below 2^bits) -> uint32 words of one slice.
 
     `which` is 'k' or 'v'.  The result covers ceil(n/32) blocks of 32 slots
     (or n_slots_alloc/32 blocks when given); untouched bits are zero."""
     n, d = codes.shape
     n_alloc = n_slots_alloc if n_slots_alloc is not None else -(-n // 32) * 32
-    words = np.zeros(n_alloc // 32 * 64 * (d // 32), dtype=np.uint32)
+    words = np.zeros(n_alloc // 32 * 64 * (d // 32) * (bits // 2), dtype=np.uint32)
     t, c = _grid(n, d)
     fn = k_code_word_bit if which == "k" else v_code_word_bit
-    w, b = fn(t, c, d)
+    w, b = fn(t, c, d, bits)
     w = np.broadcast_to(w, (n, d)).ravel()
     b = np.broadcast_to(b, (n, d)).ravel().astype(np.uint32)
     np.bitwise_or.at(words, w, codes.ravel().astype(np.uint32) << b)
     return words
 
 
-def unpack_codes(words, which, n, d):
+def unpack_codes(words, which, n, d, bits=2):
     t, c = _grid(n, d)
     fn = k_code_word_bit if which == "k" else v_code_word_bit
-    w, b = fn(t, c, d)
-    return ((words[w] >> b.astype(np.uint32)) & np.uint32(3)).astype(np.uint8)
+    w, b = fn(t, c, d, bits)
+    return ((words[w] >> b.astype(np.uint32)) & np.uint32((1 << bits) - 1)).astype(np.uint8)
 
 
 def scatter_fp(rows, which, cap):

@@ -1,16 +1,18 @@
-"""2-bit group quantizer of the evicted tokens.  Test infrastructure only.
+"""Group quantizer of the evicted tokens (2 bits; 4 bits as the paper's higher-
+precision variant).  Test infrastructure only.
 
-The paper fixes the bit width (INT2), the group size G and the axis for keys
-("Key-per-channel", Sec. 2.5; G and INT2 in Sec. 3.1) but prints no formula.
-The reading used everywhere in this repository, for one group of values x_i
-held in the cache type T (fp16 or bf16):
+The paper fixes the bit width (INT2 in the main experiments, 4-bit in Sec. 3.2.1 /
+Table 3), the group size G and the axis for keys ("Key-per-channel", Sec. 2.5; G and
+INT2 in Sec. 3.1) but prints no formula.  The reading used everywhere in this
+repository, for one group of values x_i held in the cache type T (fp16 or bf16) and
+b bits, with n = 2^b - 1 steps (3 or 15):
 
     zero  z = min_i x_i                      (an element of T; a minimum or maximum
                                               equal to zero is taken as +0.0)
-    scale s = round_to_T( (f32(max) - f32(min)) / 3 )   one fp32 subtract, one
+    scale s = round_to_T( (f32(max) - f32(min)) / n )   one fp32 subtract, one
             correctly rounded fp32 divide, one round-to-nearest-even to T
-    code_i = [d_i >= 0.5 s] + [d_i >= 1.5 s] + [d_i >= 2.5 s],  d_i = x_i - z in fp64
-             (round-half-up of d_i / s clamped to 0..3, written without a
+    code_i = sum_{k=0}^{n-1} [d_i >= (k + 0.5) s],  d_i = x_i - z in fp64
+             (round-half-up of d_i / s clamped to 0..n, written without a
              division); all codes are 0 when s == 0
     dequantized value  z + code_i * s        (fp64)
 
@@ -39,30 +41,33 @@ def round_to_T(x, dtype):
     raise ValueError("dtype must be 'f16' or 'bf16'")
 
 
-def quantize_groups(x, dtype):
-    """Quantize every group along the LAST axis of x.
+def quantize_groups(x, dtype, bits=2):
+    """Quantize every group along the LAST axis of x to `bits` bits.
 
     x : array [..., n] of values exactly representable in T.
     Returns (codes uint8 [..., n], scale fp32 [...], zero fp32 [...]); scale and
     zero hold values of T.
     """
+    if bits not in (2, 4):
+        raise ValueError("bits must be 2 or 4")
+    steps = (1 << bits) - 1
     x32 = np.asarray(x, dtype=np.float32)
     mn = x32.min(axis=-1)
     mx = x32.max(axis=-1)
     mn = np.where(mn == 0, np.float32(0.0), mn).astype(np.float32)  # -0.0 -> +0.0
     mx = np.where(mx == 0, np.float32(0.0), mx).astype(np.float32)  # (min/max do not order signed zeros)
     diff = (mx.astype(np.float32) - mn).astype(np.float32)          # fp32 subtract
-    s = round_to_T((diff / np.float32(3.0)).astype(np.float32), dtype)
+    s = round_to_T((diff / np.float32(steps)).astype(np.float32), dtype)
     d = x32.astype(np.float64) - mn.astype(np.float64)[..., None]   # fp64 subtract
     s64 = s.astype(np.float64)[..., None]
-    codes = ((d >= 0.5 * s64).astype(np.uint8)
-             + (d >= 1.5 * s64).astype(np.uint8)
-             + (d >= 2.5 * s64).astype(np.uint8))
+    codes = np.zeros(d.shape, dtype=np.uint8)
+    for k in range(steps):
+        codes += (d >= (k + 0.5) * s64).astype(np.uint8)    # (k + 0.5) * s is exact in fp64
     codes = np.where(s64 == 0, np.uint8(0), codes).astype(np.uint8)
     return codes, s, mn
 
 
-def quantize_keys(K_ev, G, dtype):
+def quantize_keys(K_ev, G, dtype, bits=2):
     """Keys of one compress event, [W][d] in eviction order, W % G == 0.
 
     Returns codes [W][d] uint8, scale [W/G][d], zero [W/G][d]."""
@@ -70,7 +75,7 @@ def quantize_keys(K_ev, G, dtype):
     if W % G:
         raise ValueError("group size must divide the number of evicted tokens")
     x = np.asarray(K_ev, dtype=np.float32).reshape(W // G, G, d).transpose(0, 2, 1)
-    codes, s, z = quantize_groups(x, dtype)          # [W/G][d][G]
+    codes, s, z = quantize_groups(x, dtype, bits)    # [W/G][d][G]
     return codes.transpose(0, 2, 1).reshape(W, d), s, z
 
 
@@ -79,7 +84,7 @@ def value_group_bounds(d, G):
     return [(lo, min(lo + G, d)) for lo in range(0, d, G)]
 
 
-def quantize_values(V_ev, G, dtype):
+def quantize_values(V_ev, G, dtype, bits=2):
     """Values of one compress event, [W][d].
 
     Returns codes [W][d] uint8, scale [W][ceil(d/G)], zero [W][ceil(d/G)]."""
@@ -89,7 +94,7 @@ def quantize_values(V_ev, G, dtype):
     s = np.zeros((W, len(bounds)), dtype=np.float32)
     z = np.zeros((W, len(bounds)), dtype=np.float32)
     for j, (lo, hi) in enumerate(bounds):
-        c, sj, zj = quantize_groups(np.asarray(V_ev, dtype=np.float32)[:, lo:hi], dtype)
+        c, sj, zj = quantize_groups(np.asarray(V_ev, dtype=np.float32)[:, lo:hi], dtype, bits)
         codes[:, lo:hi] = c
         s[:, j] = sj
         z[:, j] = zj

@@ -69,3 +69,33 @@ def test_pack_unpack_roundtrip(d):
         assert np.array_equal(layout.gather_fp(layout.scatter_fp(rows, which, 96), which, 96, d), rows)
     meta = rng.standard_normal((64, -(-d // 64))).astype(np.float32)
     assert np.array_equal(layout.gather_v_meta(layout.scatter_v_meta(meta, d, 64), 64, d, 64), meta)
+
+
+# ---- 4-bit codes: one word per (lane, operand) ----
+
+@pytest.mark.parametrize("d", [64, 96, 128])
+def test_four_bit_code_positions_are_a_bijection_onto_nibbles(d):
+    n = 128
+    t = np.arange(n)[:, None]
+    c = np.arange(d)[None, :]
+    for fn in (layout.k_code_word_bit, layout.v_code_word_bit):
+        w, b = fn(t, c, d, 4)
+        assert (b % 4 == 0).all() and b.max() == 28
+        key = (np.broadcast_to(w, (n, d)) * 8 + np.broadcast_to(b, (n, d)) // 4).ravel()
+        assert sorted(key.tolist()) == list(range(n * d))      # every nibble used once
+
+
+def test_four_bit_hand_evaluated_positions_and_roundtrip():
+    d = 128
+    # key code of slot 53 (block 1, upper 16-row tile, row 5), channel 77 (chunk 2, octet 1, element 5)
+    w, b = layout.k_code_word_bit(53, 77, d, 4)
+    assert int(w) == (1 * 64 + 16 * 1 + 5) * 8 + (1 * 4 + 2) and int(b) == 4 * 2 + 16 * 1
+    # value code of slot 53 (k = 13: lane group 1, element 5), channel 77 (tile 4, column 13)
+    w, b = layout.v_code_word_bit(53, 77, d, 4)
+    assert int(w) == (1 * 64 + 16 * 1 + 13) * 8 + 4 and int(b) == 4 * 2 + 16 * 1
+    rng = np.random.default_rng(1)
+    codes = rng.integers(0, 16, (96, d)).astype(np.uint8)
+    for which in ("k", "v"):
+        words = layout.pack_codes(codes, which, bits=4)
+        assert words.shape == (96 // 32 * 64 * (d // 32) * 2,)
+        assert np.array_equal(layout.unpack_codes(words, which, 96, d, bits=4), codes)

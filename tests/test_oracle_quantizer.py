@@ -53,19 +53,20 @@ def test_constant_group_and_signed_zero():
     assert not np.signbit(z) and s == 1.0 and c.tolist() == [0, 3]
 
 
-def _exact_reference(xs, dtype):
+def _exact_reference(xs, dtype, bits=2):
     """Brute force in exact rational arithmetic, the scale taken from the
     definition (correctly rounded fp32 quotient, then nearest-even to T)."""
+    steps = (1 << bits) - 1
     fx = [Fraction(float(v)) for v in xs]
     mn, mx = min(fx), max(fx)
     # fp32 subtract: correctly rounded value of the exact difference
     diff = _round_fraction_to_f32(mx - mn)
-    quo = _round_fraction_to_f32(Fraction(float(diff)) / 3)
+    quo = _round_fraction_to_f32(Fraction(float(diff)) / steps)
     s = Fraction(float(Q.round_to_T(np.float32(quo), dtype)))
     codes = []
     for v in fx:
         dlt = v - mn
-        codes.append(0 if s == 0 else int(dlt >= s / 2) + int(dlt >= 3 * s / 2) + int(dlt >= 5 * s / 2))
+        codes.append(0 if s == 0 else sum(int(dlt >= (2 * k + 1) * s / 2) for k in range(steps)))
     return codes, s, mn
 
 
@@ -79,17 +80,18 @@ def _round_fraction_to_f32(fr):
     return min(cands, key=lambda t: (t[0], t[1]))[2]
 
 
+@pytest.mark.parametrize("bits", [2, 4])
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
-def test_against_exact_rational_arithmetic(dtype):
-    rng = np.random.default_rng(7)
+def test_against_exact_rational_arithmetic(dtype, bits):
+    rng = np.random.default_rng(7 + bits)
     for trial in range(300):
-        n = int(rng.integers(2, 9))
+        n = int(rng.integers(2, 9 if bits == 2 else 40))
         scale = 10.0 ** rng.uniform(-3, 2)
         x = Q.round_to_T((rng.standard_normal(n) * scale).astype(np.float32), dtype)
         if trial % 5 == 0:      # grids with many exact ties
-            x = Q.round_to_T((rng.integers(0, 7, n) * 0.5).astype(np.float32), dtype)
-        codes, s, z = Q.quantize_groups(x, dtype)
-        rc, rs, rz = _exact_reference(x, dtype)
+            x = Q.round_to_T((rng.integers(0, 7 if bits == 2 else 31, n) * 0.5).astype(np.float32), dtype)
+        codes, s, z = Q.quantize_groups(x, dtype, bits)
+        rc, rs, rz = _exact_reference(x, dtype, bits)
         assert Fraction(float(s)) == rs and Fraction(float(z)) == rz
         assert codes.tolist() == rc
 
@@ -149,3 +151,42 @@ def test_key_and_value_grouping_axes():
 def test_quantize_keys_needs_divisible_window():
     with pytest.raises(ValueError):
         Q.quantize_keys(np.zeros((42, 8), np.float32), 32, "f16")
+
+
+# ---- 4-bit variant (Sec. 3.2.1, Table 3: the same method at higher precision) ----
+
+def test_four_bit_tie_vectors_and_exact_grid():
+    # 16 values on a grid of step 0.5: s = 7.5 / 15 = 0.5 exactly, every value is its own level
+    x = _f16([k * 0.5 for k in range(16)])
+    c, s, z = Q.quantize_groups(x, "f16", bits=4)
+    assert s == 0.5 and z == 0 and c.tolist() == list(range(16))
+    assert np.array_equal(z + c * np.float64(s), x.astype(np.float64))
+    # s = 1 (range 15): the half-integers are exact ties and go up (half-even would send 0.5 -> 0, 2.5 -> 2)
+    c, s, z = Q.quantize_groups(_f16([0, 15, 0.5, 1.5, 2.5, 13.5, 14.5]), "f16", bits=4)
+    assert s == 1.0 and c.tolist() == [0, 15, 1, 2, 3, 14, 15]
+    # a value just below a tie stays down
+    c, s, z = Q.quantize_groups(_f16([0, 15, 2.498046875]), "f16", bits=4)
+    assert c.tolist() == [0, 15, 2]
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_four_bit_invariants(dtype):
+    rng = np.random.default_rng(13)
+    x = Q.round_to_T(rng.standard_normal((400, 64)).astype(np.float32) * 3, dtype)
+    x[:, 9] *= 10
+    codes, s, z = Q.quantize_groups(x, dtype, bits=4)
+    assert codes.min() == 0 and codes.max() == 15
+    rows = np.arange(x.shape[0])
+    assert (codes[rows, x.argmin(1)] == 0).all() and (codes[rows, x.argmax(1)] == 15).all()
+    order = np.argsort(x, axis=1, kind="stable")
+    assert (np.diff(np.take_along_axis(codes.astype(int), order, 1), axis=1) >= 0).all()
+    xhat = z.astype(np.float64)[:, None] + codes * s.astype(np.float64)[:, None]
+    err = np.abs(xhat - x)
+    rng_ = (x.max(1) - x.min(1)).astype(np.float64)
+    assert (err <= np.maximum(s / 2.0, rng_ - 15.0 * s)[:, None] + 1e-300).all()
+    # five times finer than 2 bits on the same data
+    c2, s2, _ = Q.quantize_groups(x, dtype, bits=2)
+    ratio = s2.astype(np.float64) / s.astype(np.float64)
+    assert (np.abs(ratio - 5.0) < 0.05).all()
+    with pytest.raises(ValueError):
+        Q.quantize_groups(x, dtype, bits=3)
