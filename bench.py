@@ -27,6 +27,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", type=int, default=3, help="1..5, see BASELINE.json configs")
     ap.add_argument("--copies", type=int, default=0, help="cache copies to rotate over (0 = auto)")
+    ap.add_argument("--bits", type=int, default=2, choices=(2, 4),
+                    help="code width; 2 is BASELINE.json's setting, 4 the paper's higher-precision variant")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 256 MiB device copy a few times (reference for HBM counters)")
@@ -46,7 +48,8 @@ def build_states(wl, cfg_id, copies):
     qcap = (L // W + 4) * W
     while qcap % 64:
         qcap += W
-    cfg = binding.make_config(wl["B"], wl["Hq"], wl["Hkv"], wl["d"], wl["F"], wl["G"], dt, qcap)
+    cfg = binding.make_config(wl["B"], wl["Hq"], wl["Hkv"], wl["d"], wl["F"], wl["G"], dt, qcap,
+                              wl.get("bits", 2))
     tdt = torch.bfloat16 if dt == "bf16" else torch.float16
     Kd = torch.empty((wl["B"], wl["Hkv"], L, wl["d"]), dtype=tdt, device="cuda:0")
     Vd = torch.empty_like(Kd)
@@ -72,7 +75,7 @@ def build_states(wl, cfg_id, copies):
     n_q = dc.c.n_q
     sizes = binding.logquant_sizes(cfg)
     bh = wl["B"] * wl["Hkv"]
-    written = bh * (n_q * (wl["d"] // 2 + 4 * -(-wl["d"] // wl["G"])) + n_q // wl["G"] * 4 * wl["d"]
+    written = bh * (n_q * (wl["d"] * wl.get("bits", 2) // 4 + 4 * -(-wl["d"] // wl["G"])) + n_q // wl["G"] * 4 * wl["d"]
                     + dc.c.n_fp * 4 * wl["d"])
     read = 2 * Kd.numel() * 2
     prefill = {"ms_per_call": ms, "tokens_per_s": wl["B"] * L / (ms * 1e-3),
@@ -95,12 +98,16 @@ def main():
     from tests.gpu_util import to_dev
 
     wl = dict(inputs.WORKLOADS[a.workload])
+    wl["bits"] = a.bits
+    if a.bits != 2:
+        wl["name"] += "_bits%d" % a.bits
     W, L, dt = wl["F"] // 2, wl["L"], wl["dtype"]
     steps = a.steps or W
     plan0 = None
     # enough copies that the rotation's footprint is >= 1 GiB (4x the 256 MB last-level cache)
     cfg_probe = binding.make_config(wl["B"], wl["Hq"], wl["Hkv"], wl["d"], wl["F"], wl["G"], dt,
-                                    (L // W + 4) * W if ((L // W + 4) * W) % 64 == 0 else (L // W + 5) * W)
+                                    (L // W + 4) * W if ((L // W + 4) * W) % 64 == 0 else (L // W + 5) * W,
+                                    a.bits)
     plan0 = binding.logquant_decode_plan(cfg_probe, 2 * W, (L - 2 * W) // W * W)
     copies = a.copies or max(2, min(16, -(-(1 << 30) // max(1, plan0.bytes_read))))
     t_build = time.time()
@@ -209,7 +216,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": dt, "data": "synthetic",
         "config": {"workload": wl["name"], "B": wl["B"], "Hq": wl["Hq"], "Hkv": wl["Hkv"],
-                   "d": wl["d"], "L": L, "group": wl["G"], "fp_budget": wl["F"], "bits": 2,
+                   "d": wl["d"], "L": L, "group": wl["G"], "fp_budget": wl["F"], "bits": wl["bits"],
                    "cache_copies_rotated": len(caches), "compress_events_in_timed_region": n_compress,
                    "attn_blocks": plan.blocks, "attn_splits": plan.splits},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

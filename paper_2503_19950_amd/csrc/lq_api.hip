@@ -16,7 +16,7 @@ lq_status make_shape(const lq_config* cfg, Shape* s) {
   if (cfg->Hq % cfg->Hkv) return LQ_ERR_SHAPE;
   if (cfg->fp_budget % 2) return LQ_ERR_SHAPE;
   if (cfg->dtype != LQ_F16 && cfg->dtype != LQ_BF16) return LQ_ERR_SHAPE;
-  if (cfg->bits != 2) return LQ_ERR_UNSUPPORTED;
+  if (cfg->bits != 2 && cfg->bits != 4) return LQ_ERR_UNSUPPORTED;
   if (cfg->d != 64 && cfg->d != 96 && cfg->d != 128) return LQ_ERR_UNSUPPORTED;
   if (cfg->group != 32 && cfg->group != 64 && cfg->group != 128) return LQ_ERR_UNSUPPORTED;
   const int W = cfg->fp_budget / 2;
@@ -29,6 +29,7 @@ lq_status make_shape(const lq_config* cfg, Shape* s) {
   s->gh = cfg->Hq / cfg->Hkv;
   s->nkc = cfg->d / 32; s->nnt = cfg->d / 16; s->ngc = (cfg->d + cfg->group - 1) / cfg->group;
   s->bf16 = cfg->dtype == LQ_BF16;
+  s->bits = cfg->bits;
   return LQ_OK;
 }
 
@@ -41,9 +42,9 @@ int max_splits(const Shape& s) {
 }
 
 int64_t cache_bytes_read(const Shape& s, int n_fp, int n_q) {
-  // per quantized slot: K codes d/4 + V codes d/4 bytes; key scale+zero 4d bytes
-  // per G slots; value scale+zero 4 bytes per channel group.
-  const int64_t q_bytes = (int64_t)n_q * (s.d / 2 + 4 * s.ngc) + (int64_t)(n_q / s.G) * 4 * s.d;
+  // per quantized slot: K codes and V codes d*bits/8 bytes each; key scale+zero 4d
+  // bytes per G slots; value scale+zero 4 bytes per channel group.
+  const int64_t q_bytes = (int64_t)n_q * (s.d * s.bits / 4 + 4 * s.ngc) + (int64_t)(n_q / s.G) * 4 * s.d;
   const int64_t fp_bytes = (int64_t)n_fp * 4 * s.d;
   return (int64_t)s.B * s.Hkv * (q_bytes + fp_bytes);
 }
@@ -82,7 +83,7 @@ lq_status logquant_sizes(const lq_config* cfg, lq_sizes* out) {
   out->k_fp = bh * s.cap * s.d * 2;
   out->v_fp = out->k_fp;
   out->pos_fp = (size_t)s.B * s.cap * 4;
-  out->k_codes = bh * s.qcap * s.d / 4;
+  out->k_codes = bh * s.qcap * s.d * s.bits / 8;
   out->v_codes = out->k_codes;
   out->k_meta = bh * (s.qcap / s.G) * s.d * 2;
   out->v_meta = bh * s.qcap * s.ngc * 2;

@@ -27,7 +27,7 @@ static int env_int(const char* name, int dflt) {
 // tail of a workgroup expressed in tiles.
 void plan_decode(const Shape& s, int n_fp, int n_q, lq_plan* plan) {
   const int TQ = (n_q + 63) / 64, TF = (n_fp + 31) / 32;
-  const double q_tile_bytes = 64.0 * (s.d / 2 + 4 * s.ngc + 4.0 * s.d / s.G);
+  const double q_tile_bytes = 64.0 * (s.d * s.bits / 4 + 4 * s.ngc + 4.0 * s.d / s.G);
   const double fp_unit_bytes = 32.0 * 4 * s.d;
   const double r = fp_unit_bytes / q_tile_bytes;
   const double units = TQ + r * TF;

@@ -99,6 +99,28 @@ __device__ __forceinline__ uint4 codes_odd(uint32_t w) { return codes_even(w >> 
 __device__ __forceinline__ uint4 codes_of(uint32_t w, int odd) {
   return odd ? codes_odd(w) : codes_even(w);
 }
+// 4-bit codes: a word holds the eight codes of one operand, element i = 2v + h in
+// nibble v of half h.  Registers 0 and 2 keep their codes at mantissa bits 0..3
+// (code * 2^-24), registers 1 and 3 at bits 4..7 (code * 2^-20); two of the four
+// nibbles of a half would reach into the exponent and are shifted down first.
+__device__ __forceinline__ uint4 codes4(uint32_t w) {
+  const uint32_t h = w >> 8;
+  return make_uint4(w & 0x000F000Fu, w & 0x00F000F0u, h & 0x000F000Fu, h & 0x00F000F0u);
+}
+// Operand o (of the 2 * NKC a lane holds for one 32-slot block) of a code tile, and
+// the power of two by which the other operand's register v has to be scaled so that
+// every product carries the common factor 2^-CODE_SHIFT.
+template <int BITS, int N>
+__device__ __forceinline__ uint4 operand_codes(const uint32_t (&w)[N], int o) {
+  if constexpr (BITS == 2) return codes_of(w[o >> 1], o & 1);
+  else return codes4(w[o]);
+}
+template <int BITS>
+__device__ __forceinline__ constexpr int pos_exp(int v) {   // log2 of the scale of register v's partner
+  return BITS == 2 ? 3 - 2 * v : 2 - 4 * (v & 1);
+}
+template <int BITS>
+constexpr float CODE_SCALE = BITS == 2 ? 2097152.f : 4194304.f;   // 2^21, 2^22
 
 __device__ __forceinline__ uint32_t pack_f16(float a, float b) {
   half2_t h = {(_Float16)a, (_Float16)b};
@@ -303,10 +325,11 @@ __device__ __forceinline__ void online_softmax_rows(State<NNT>& st, const float*
 
 // NWB: wavefronts per workgroup (8, or 4 when there are enough (b, kv head) groups to
 // put two workgroups on every compute unit).
-template <bool BF16, int D, int G, int NWB>
+template <bool BF16, int D, int G, int NWB, int BITS>
 __global__ void __launch_bounds__(64 * NWB, 2)
 attn_mfma_kernel(const AttnParams P) {
   constexpr int NKC = D / 32, NNT = D / 16, NGC = (D + G - 1) / G;
+  constexpr int WPL = NKC * (BITS / 2);           // code words per lane and 32-slot block
   constexpr int NGRP = G < 64 ? 64 / G : 1;     // key groups per 64-token tile
   // fp16 head/tail of q*s per wave, one row per (piece, head).  The 16 lanes of a
   // lane row read 16 bytes each from nine different rows at the same column; a row
@@ -353,14 +376,14 @@ attn_mfma_kernel(const AttnParams P) {
   if (gw >= NWF) {
     // ------------------------- quantized rows -------------------------
     const int wq = gw - NWF;
-    const char* kcb = (const char*)(P.k_codes + (int64_t)bh * (P.qcap >> 5) * 64 * NKC);
-    const char* vcb = (const char*)(P.v_codes + (int64_t)bh * (P.qcap >> 5) * 64 * NKC);
+    const char* kcb = (const char*)(P.k_codes + (int64_t)bh * (P.qcap >> 5) * 64 * WPL);
+    const char* vcb = (const char*)(P.v_codes + (int64_t)bh * (P.qcap >> 5) * 64 * WPL);
     const char* ksb = (const char*)(P.k_scale + (int64_t)bh * (P.qcap / G) * D);
     const char* kzb = (const char*)(P.k_zero + (int64_t)bh * (P.qcap / G) * D);
     const char* vsb = (const char*)(P.v_scale + (int64_t)bh * (P.qcap >> 5) * NGC * 32);
     const char* vzb = (const char*)(P.v_zero + (int64_t)bh * (P.qcap >> 5) * NGC * 32);
     const int upc = up < NGC ? up : 0;
-    const uint32_t code_off = lane * NKC * 4;                 // byte offsets of this lane
+    const uint32_t code_off = lane * WPL * 4;                 // byte offsets of this lane
     const uint32_t vm_off = (upc * 32 + 8 * q4) * 2;
     // Lane roles.  Logits and softmax: lane row q4 is query head q4, lane column n16
     // is a token of each of the four 16-token tiles.  q*s preparation: head q4,
@@ -372,20 +395,20 @@ attn_mfma_kernel(const AttnParams P) {
     const bool headq_ok = q4 < P.hb;
 
     struct Tile {
-      Words<NKC> kc[2], vc[2];
+      Words<WPL> kc[2], vc[2];
       uint4 vs[2], vz[2];
       uint4 ks8[NGRP], kz8[NGRP];
     };
     auto load_tile = [&](int t) {
       Tile T;
-      const char* kcp = kcb + (int64_t)t * (2 * 64 * NKC * 4);
-      const char* vcp = vcb + (int64_t)t * (2 * 64 * NKC * 4);
+      const char* kcp = kcb + (int64_t)t * (2 * 64 * WPL * 4);
+      const char* vcp = vcb + (int64_t)t * (2 * 64 * WPL * 4);
       const char* vsp = vsb + (int64_t)t * (2 * NGC * 32 * 2);
       const char* vzp = vzb + (int64_t)t * (2 * NGC * 32 * 2);
 #pragma unroll
       for (int b2 = 0; b2 < 2; ++b2) {
-        T.kc[b2] = *reinterpret_cast<const Words<NKC>*>(kcp + b2 * (64 * NKC * 4) + code_off);
-        T.vc[b2] = *reinterpret_cast<const Words<NKC>*>(vcp + b2 * (64 * NKC * 4) + code_off);
+        T.kc[b2] = *reinterpret_cast<const Words<WPL>*>(kcp + b2 * (64 * WPL * 4) + code_off);
+        T.vc[b2] = *reinterpret_cast<const Words<WPL>*>(vcp + b2 * (64 * WPL * 4) + code_off);
         T.vs[b2] = *reinterpret_cast<const uint4*>(vsp + b2 * (NGC * 32 * 2) + vm_off);
         T.vz[b2] = *reinterpret_cast<const uint4*>(vzp + b2 * (NGC * 32 * 2) + vm_off);
       }
@@ -441,18 +464,22 @@ attn_mfma_kernel(const AttnParams P) {
       uint4 raw = *reinterpret_cast<const uint4*>(P.q + qrow_q + (prep ? 8 * c8 : 0));
       if (!prep || !headq_ok) raw = make_uint4(0, 0, 0, 0);
       qraw[0] = raw.x; qraw[1] = raw.y; qraw[2] = raw.z; qraw[3] = raw.w;
-      const float f[4] = {8.f, 2.f, 0.5f, 0.125f};
 #pragma unroll
-      for (int v = 0; v < 4; ++v)
-        qh[v] = half2_t{(_Float16)(lo_T<BF16>(qraw[v]) * f[v]), (_Float16)(hi_T<BF16>(qraw[v]) * f[v])};
+      for (int v = 0; v < 4; ++v) {
+        const float f = __builtin_ldexpf(1.f, pos_exp<BITS>(v));
+        qh[v] = half2_t{(_Float16)(lo_T<BF16>(qraw[v]) * f), (_Float16)(hi_T<BF16>(qraw[v]) * f)};
+      }
     }
-    const float c21 = P.c * 2097152.f;        // codes enter as code * 2^-24, q*s as 2^3 q s
+    const float c21 = P.c * CODE_SCALE<BITS>;   // codes and the pre-scaled q*s together carry 1 / CODE_SCALE
     // slot offsets: this lane's token of tile u is token x = 16*(u&1) + n16 of its
     // 32-token output step, element i = 4*(x/16) + x%4 of its lane group there, whose
     // codes sit at position v = i >> 1
     float offs[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) offs[u] = (float)(3 - 2 * (2 * (u & 1) + ((n16 & 3) >> 1)));
+    for (int u = 0; u < 4; ++u) {
+      const int v = 2 * (u & 1) + ((n16 & 3) >> 1);
+      offs[u] = (float)(BITS == 2 ? 3 - 2 * v : 2 - 4 * (v & 1));
+    }
 
     // rows of the q*s operand: matrix row n16 = 4*head + piece, pieces 2 and 3 are zero
     const uint16_t* qs_rd = &qs_lds[wave][0][(n16 & 3) < 2 ? 4 * (n16 & 3) + (n16 >> 2) : 8][8 * q4];
@@ -510,7 +537,7 @@ attn_mfma_kernel(const AttnParams P) {
 #pragma unroll
           for (int u = e * (4 / NGRP); u < (e + 1) * (4 / NGRP); ++u) {
             const int o = (u & 1) * NKC + kc;
-            const uint4 b = codes_of(cur.kc[u >> 1].w[o >> 1], o & 1);
+            const uint4 b = operand_codes<BITS>(cur.kc[u >> 1].w, o);
             Du[u] = mfma_f16(qa, b, Du[u]);
           }
         }
@@ -563,7 +590,7 @@ attn_mfma_kernel(const AttnParams P) {
         const uint4 a = make_uint4(aw[0], aw[1], aw[2], aw[3]);
 #pragma unroll
         for (int nt = 0; nt < NNT; ++nt) {
-          const uint4 b = codes_of(cur.vc[ks].w[nt >> 1], nt & 1);
+          const uint4 b = operand_codes<BITS>(cur.vc[ks].w, nt);
           st.acc[nt] = mfma_f16(a, b, st.acc[nt]);
         }
       }
@@ -592,9 +619,8 @@ attn_mfma_kernel(const AttnParams P) {
     const float l_tot = row_sum(lsum);
     float zs = 0.f;
     {
-      const float f[4] = {0.125f, 0.5f, 2.f, 8.f};   // 2^-(3-2v)
 #pragma unroll
-      for (int v = 0; v < 4; ++v) zs += st.zacc[v] * f[v];
+      for (int v = 0; v < 4; ++v) zs += st.zacc[v] * __builtin_ldexpf(1.f, -pos_exp<BITS>(v));
     }
     zs = rows_sum(zs);
     if (q4 == 0) zs_lds[wave][up][g] = zs;
@@ -606,7 +632,7 @@ attn_mfma_kernel(const AttnParams P) {
       if (q4 == gc) {
 #pragma unroll
         for (int gg = 0; gg < 4; ++gg)
-          o_lds[wave][gg][16 * nt + n16] = st.acc[nt][gg] * 2097152.f + zs_lds[wave][gc][gg];
+          o_lds[wave][gg][16 * nt + n16] = st.acc[nt][gg] * CODE_SCALE<BITS> + zs_lds[wave][gc][gg];
       }
     }
   } else {
@@ -877,23 +903,28 @@ hipError_t launch_combine(const Shape& s, const float* ws, void* out, int splits
   return launch_status(__func__);
 }
 
-template <bool BF16, int D, int NWB>
+template <bool BF16, int D, int NWB, int BITS>
 static hipError_t launch_mfma_dg(const Shape& s, const AttnParams& P, dim3 grid, hipStream_t st) {
   switch (s.G) {
-    case 32: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 32, NWB>), grid, dim3(64 * NWB), 0, st, P); break;
-    case 64: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 64, NWB>), grid, dim3(64 * NWB), 0, st, P); break;
-    default: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 128, NWB>), grid, dim3(64 * NWB), 0, st, P); break;
+    case 32: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 32, NWB, BITS>), grid, dim3(64 * NWB), 0, st, P); break;
+    case 64: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 64, NWB, BITS>), grid, dim3(64 * NWB), 0, st, P); break;
+    default: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 128, NWB, BITS>), grid, dim3(64 * NWB), 0, st, P); break;
   }
   return launch_status(__func__);
 }
 
-template <bool BF16, int NWB>
+template <bool BF16, int NWB, int BITS>
 static hipError_t launch_mfma_d(const Shape& s, const AttnParams& P, dim3 grid, hipStream_t st) {
   switch (s.d) {
-    case 64: return launch_mfma_dg<BF16, 64, NWB>(s, P, grid, st);
-    case 96: return launch_mfma_dg<BF16, 96, NWB>(s, P, grid, st);
-    default: return launch_mfma_dg<BF16, 128, NWB>(s, P, grid, st);
+    case 64: return launch_mfma_dg<BF16, 64, NWB, BITS>(s, P, grid, st);
+    case 96: return launch_mfma_dg<BF16, 96, NWB, BITS>(s, P, grid, st);
+    default: return launch_mfma_dg<BF16, 128, NWB, BITS>(s, P, grid, st);
   }
+}
+
+template <int NWB, int BITS>
+static hipError_t launch_mfma_t(const Shape& s, const AttnParams& P, dim3 grid, hipStream_t st) {
+  return s.bf16 ? launch_mfma_d<true, NWB, BITS>(s, P, grid, st) : launch_mfma_d<false, NWB, BITS>(s, P, grid, st);
 }
 
 hipError_t launch_decode_attn_mfma(const Shape& s, const lq_cache& c, const void* q, float scale,
@@ -916,8 +947,8 @@ hipError_t launch_decode_attn_mfma(const Shape& s, const lq_cache& c, const void
   P.dynamic = dynamic;
   dim3 grid(plan.splits, s.B * s.Hkv * (s.gh / P.hb));
   if (plan.waves_per_block == 4)
-    return s.bf16 ? launch_mfma_d<true, 4>(s, P, grid, st) : launch_mfma_d<false, 4>(s, P, grid, st);
-  return s.bf16 ? launch_mfma_d<true, 8>(s, P, grid, st) : launch_mfma_d<false, 8>(s, P, grid, st);
+    return s.bits == 4 ? launch_mfma_t<4, 4>(s, P, grid, st) : launch_mfma_t<4, 2>(s, P, grid, st);
+  return s.bits == 4 ? launch_mfma_t<8, 4>(s, P, grid, st) : launch_mfma_t<8, 2>(s, P, grid, st);
 }
 
 }  // namespace lq

@@ -23,7 +23,7 @@ attn_ref_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_f
                 const uint32_t* __restrict__ v_codes, const uint16_t* __restrict__ k_scale,
                 const uint16_t* __restrict__ k_zero, const uint16_t* __restrict__ v_scale,
                 const uint16_t* __restrict__ v_zero, float* __restrict__ ws, int d, int G, int cap,
-                int qcap, int n_fp, int n_q, int gh, int splits, float scale_log2e) {
+                int qcap, int n_fp, int n_q, int gh, int splits, float scale_log2e, int bits) {
   __shared__ float sm_o[4][HB][128];
   __shared__ float sm_ml[4][HB][2];
   const int split = blockIdx.x;
@@ -48,7 +48,8 @@ attn_ref_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_f
   for (int g = 0; g < HB; ++g) { m[g] = -INFINITY; l[g] = 0.f; o[g][0] = o[g][1] = 0.f; }
 
   const int64_t fp_slice = (int64_t)bh * cap * d;
-  const int64_t code_slice = (int64_t)bh * (qcap >> 5) * 64 * nkc;
+  const int64_t code_slice = (int64_t)bh * (qcap >> 5) * 64 * nkc * (bits >> 1);
+  const uint32_t cmask = (1u << bits) - 1u;
   const int64_t kmeta_slice = (int64_t)bh * (qcap / G) * d;
   const int64_t vmeta_slice = (int64_t)bh * (qcap >> 5) * ngc * 32;
 
@@ -65,17 +66,21 @@ attn_ref_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_f
         const int s = t - n_fp;
         {  // key code, scale, zero
           const int o_ = ((s & 31) >> 4) * nkc + (c >> 5);
-          const int64_t w = (((int64_t)(s >> 5)) * 64 + 16 * ((c & 31) >> 3) + (s & 15)) * nkc + (o_ >> 1);
-          const int bit = 8 * (o_ & 1) + 2 * ((c & 7) >> 1) + 16 * (c & 1);
-          const float code = (float)((k_codes[code_slice + w] >> bit) & 3u);
+          const int64_t ln = ((int64_t)(s >> 5)) * 64 + 16 * ((c & 31) >> 3) + (s & 15);
+          const int64_t w = bits == 2 ? ln * nkc + (o_ >> 1) : ln * 2 * nkc + o_;
+          const int bit = bits == 2 ? 8 * (o_ & 1) + 2 * ((c & 7) >> 1) + 16 * (c & 1)
+                                    : 4 * ((c & 7) >> 1) + 16 * (c & 1);
+          const float code = (float)((k_codes[code_slice + w] >> bit) & cmask);
           const int64_t mi = kmeta_slice + (int64_t)(s / G) * d + c;
           kx[e] = fmaf(code, t2f<BF16>(k_scale[mi]), t2f<BF16>(k_zero[mi]));
         }
         {  // value code, scale, zero
           const int k = kperm(s & 31);
-          const int64_t w = (((int64_t)(s >> 5)) * 64 + 16 * (k >> 3) + (c & 15)) * nkc + ((c >> 4) >> 1);
-          const int bit = 8 * ((c >> 4) & 1) + 2 * ((k & 7) >> 1) + 16 * (k & 1);
-          const float code = (float)((v_codes[code_slice + w] >> bit) & 3u);
+          const int64_t ln = ((int64_t)(s >> 5)) * 64 + 16 * (k >> 3) + (c & 15);
+          const int64_t w = bits == 2 ? ln * nkc + ((c >> 4) >> 1) : ln * 2 * nkc + (c >> 4);
+          const int bit = bits == 2 ? 8 * ((c >> 4) & 1) + 2 * ((k & 7) >> 1) + 16 * (k & 1)
+                                    : 4 * ((k & 7) >> 1) + 16 * (k & 1);
+          const float code = (float)((v_codes[code_slice + w] >> bit) & cmask);
           const int64_t mi = vmeta_slice + v_meta_index(s, c / G, ngc);
           vx[e] = fmaf(code, t2f<BF16>(v_scale[mi]), t2f<BF16>(v_zero[mi]));
         }
@@ -126,7 +131,7 @@ static hipError_t launch_ref_t(const Shape& s, const lq_cache& c, const void* q,
                      (const uint16_t*)c.k_fp[c.cur], (const uint16_t*)c.v_fp[c.cur], c.k_codes,
                      c.v_codes, (const uint16_t*)c.k_scale, (const uint16_t*)c.k_zero,
                      (const uint16_t*)c.v_scale, (const uint16_t*)c.v_zero, (float*)ws, s.d, s.G,
-                     s.cap, s.qcap, c.n_fp, c.n_q, s.gh, splits, scale * 1.4426950408889634f);
+                     s.cap, s.qcap, c.n_fp, c.n_q, s.gh, splits, scale * 1.4426950408889634f, s.bits);
   return launch_status(__func__);
 }
 

@@ -8,28 +8,34 @@
 
 namespace lq {
 
-// One group of values: zero z = min, scale s = T((max - min) / 3) with the
+// One group of values: zero z = min, scale s = T((max - min) / STEPS) with the
 // difference and the quotient correctly rounded to fp32 (the fp64 quotient
 // rounded once more to fp32 equals the IEEE fp32 quotient, 53 >= 2*24 + 2).
-template <bool BF16>
+template <bool BF16, int BITS>
 __device__ __forceinline__ void group_params(float mn, float mx, float* z, float* s, uint16_t* zt,
                                              uint16_t* st) {
   if (mn == 0.f) mn = 0.f;  // -0 -> +0 (min/max do not order signed zeros)
   if (mx == 0.f) mx = 0.f;
   const float diff = mx - mn;
-  const float quo = (float)((double)diff / 3.0);
+  const float quo = (float)((double)diff / (double)((1 << BITS) - 1));
   *st = f2t<BF16>(quo);
   *s = t2f<BF16>(*st);
   *zt = f2t<BF16>(mn);  // exact: mn is an element of T
   *z = mn;
 }
 
-// round-half-up of (x - z)/s clamped to 0..3, by threshold compares on the exact
-// (fp64) difference.
+// round-half-up of (x - z)/s clamped to 0..2^BITS-1, by threshold compares on the
+// exact (fp64) difference; (k + 0.5) * s is exact in fp64.
+template <int BITS>
 __device__ __forceinline__ uint32_t code_of(float x, float z, float s) {
   const double dl = (double)x - (double)z;
   const double sd = (double)s;
-  const uint32_t c = (uint32_t)(dl >= 0.5 * sd) + (uint32_t)(dl >= 1.5 * sd) + (uint32_t)(dl >= 2.5 * sd);
+  // the thresholds grow with k, so the number of them that dl reaches is found by
+  // bisection: BITS compares instead of 2^BITS - 1
+  uint32_t c = 0;
+#pragma unroll
+  for (int step = 1 << (BITS - 1); step >= 1; step >>= 1)
+    if (dl >= ((double)(c + step) - 0.5) * sd) c += step;
   return s == 0.f ? 0u : c;
 }
 
@@ -92,7 +98,7 @@ struct PromptSource {
 
 // Quantize one key group (G rows) of slice bh into quantized slots q0 .. q0+G-1.
 // 256 threads; sm: G * (d + 2) uint16 of LDS, red: 8 * 128 floats.
-template <bool BF16, int d, int G, class Src>
+template <bool BF16, int d, int G, int BITS, class Src>
 __device__ __forceinline__ void quantize_group(
     uint16_t* sm, float* red, const Src& src, int bh, int q0, uint32_t* __restrict__ k_codes,
     uint32_t* __restrict__ v_codes, uint16_t* __restrict__ k_scale, uint16_t* __restrict__ k_zero,
@@ -100,7 +106,8 @@ __device__ __forceinline__ void quantize_group(
     int qcap, int Hkv) {
   const int tid = threadIdx.x;
   constexpr int nkc = d >> 5, ngc = (d + G - 1) / G, ld = d + 2;
-  const int64_t code_base = ((int64_t)bh * (qcap >> 5) + (q0 >> 5)) * 64 * nkc;
+  constexpr int WPL = nkc * (BITS / 2);   // code words per lane and 32-slot block
+  const int64_t code_base = ((int64_t)bh * (qcap >> 5) + (q0 >> 5)) * 64 * WPL;
 
   // ---------------- keys ----------------
   src.stage_keys(sm, ld);
@@ -129,30 +136,38 @@ __device__ __forceinline__ void quantize_group(
       }
       float z, sc;
       uint16_t zt, st;
-      group_params<BF16>(mn, mx, &z, &sc, &zt, &st);
+      group_params<BF16, BITS>(mn, mx, &z, &sc, &zt, &st);
       if (part == 0) {
         const int64_t mi = ((int64_t)bh * (qcap / G) + q0 / G) * d + c;
         k_scale[mi] = st;
         k_zero[mi] = zt;
       }
-      for (int e = e0; e < e0 + per; ++e) sm[e * ld + c] = (uint16_t)code_of(t2f<BF16>(sm[e * ld + c]), z, sc);
+      for (int e = e0; e < e0 + per; ++e) sm[e * ld + c] = (uint16_t)code_of<BITS>(t2f<BF16>(sm[e * ld + c]), z, sc);
     }
   }
   __syncthreads();
-  for (int idx = tid; idx < (G >> 5) * 64 * nkc; idx += 256) {
-    const int m = idx % nkc, lane = (idx / nkc) & 63, blk = idx / (nkc * 64);
+  for (int idx = tid; idx < (G >> 5) * 64 * WPL; idx += 256) {
+    const int m = idx % WPL, lane = (idx / WPL) & 63, blk = idx / (WPL * 64);
     const int r = lane & 15, qq = lane >> 4;
     uint32_t w = 0;
+    if constexpr (BITS == 2) {
 #pragma unroll
-    for (int jj = 0; jj < 8; ++jj) {
-      const int o = 2 * m + (jj >> 2);
-      const int uu = o / nkc, kc = o % nkc;
+      for (int jj = 0; jj < 8; ++jj) {
+        const int o = 2 * m + (jj >> 2);
+        const int uu = o / nkc, kc = o % nkc;
+        const int e = blk * 32 + 16 * uu + r;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+          const int c = 32 * kc + 8 * qq + 2 * (jj & 3) + half;
+          w |= (uint32_t)sm[e * ld + c] << (2 * jj + 16 * half);
+        }
+      }
+    } else {
+      const int uu = m / nkc, kc = m % nkc;   // one word per operand o = m
       const int e = blk * 32 + 16 * uu + r;
 #pragma unroll
-      for (int half = 0; half < 2; ++half) {
-        const int c = 32 * kc + 8 * qq + 2 * (jj & 3) + half;
-        w |= (uint32_t)sm[e * ld + c] << (2 * jj + 16 * half);
-      }
+      for (int i = 0; i < 8; ++i)
+        w |= (uint32_t)sm[e * ld + 32 * kc + 8 * qq + i] << (4 * (i >> 1) + 16 * (i & 1));
     }
     k_codes[code_base + idx] = w;
   }
@@ -182,28 +197,36 @@ __device__ __forceinline__ void quantize_group(
       }
       float z, sc;
       uint16_t zt, st;
-      group_params<BF16>(mn, mx, &z, &sc, &zt, &st);
+      group_params<BF16, BITS>(mn, mx, &z, &sc, &zt, &st);
       if (part == 0) {
         const int64_t mi = (int64_t)bh * (qcap >> 5) * ngc * 32 + v_meta_index(q0 + e, gc, ngc);
         v_scale[mi] = st;
         v_zero[mi] = zt;
       }
-      for (int c = c0; c < c1; ++c) sm[e * ld + c] = (uint16_t)code_of(t2f<BF16>(sm[e * ld + c]), z, sc);
+      for (int c = c0; c < c1; ++c) sm[e * ld + c] = (uint16_t)code_of<BITS>(t2f<BF16>(sm[e * ld + c]), z, sc);
     }
   }
   __syncthreads();
-  for (int idx = tid; idx < (G >> 5) * 64 * nkc; idx += 256) {
-    const int m = idx % nkc, lane = (idx / nkc) & 63, blk = idx / (nkc * 64);
+  for (int idx = tid; idx < (G >> 5) * 64 * WPL; idx += 256) {
+    const int m = idx % WPL, lane = (idx / WPL) & 63, blk = idx / (WPL * 64);
     const int n = lane & 15, qq = lane >> 4;
     uint32_t w = 0;
+    if constexpr (BITS == 2) {
 #pragma unroll
-    for (int jj = 0; jj < 8; ++jj) {
-      const int nt = 2 * m + (jj >> 2);
+      for (int jj = 0; jj < 8; ++jj) {
+        const int nt = 2 * m + (jj >> 2);
 #pragma unroll
-      for (int half = 0; half < 2; ++half) {
-        const int k = 8 * qq + 2 * (jj & 3) + half;
-        const int e = blk * 32 + kperm_inv(k);
-        w |= (uint32_t)sm[e * ld + 16 * nt + n] << (2 * jj + 16 * half);
+        for (int half = 0; half < 2; ++half) {
+          const int k = 8 * qq + 2 * (jj & 3) + half;
+          const int e = blk * 32 + kperm_inv(k);
+          w |= (uint32_t)sm[e * ld + 16 * nt + n] << (2 * jj + 16 * half);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {            // one word per channel tile nt = m
+        const int e = blk * 32 + kperm_inv(8 * qq + i);
+        w |= (uint32_t)sm[e * ld + 16 * m + n] << (4 * (i >> 1) + 16 * (i & 1));
       }
     }
     v_codes[code_base + idx] = w;
@@ -266,7 +289,7 @@ struct CompressParams {
 // write disjoint ones.  grid (W/G + 2W/32, B*Hkv), block 256: workgroups x < W/G
 // quantize one key group each, the others move 32 kept rows each.
 // Dynamic LDS: G * (d + 2) uint16.
-template <bool BF16, int D, int G>
+template <bool BF16, int D, int G, int BITS>
 __global__ void __launch_bounds__(256) compress_kernel(const CompressParams P) {
   extern __shared__ uint16_t sm[];  // [G][d + 2]; values first, then their codes in place
   __shared__ float red[8 * 128];    // partial minima [4][d] and maxima [4][d] of the key channels
@@ -275,7 +298,7 @@ __global__ void __launch_bounds__(256) compress_kernel(const CompressParams P) {
     const int j = blockIdx.x;
     const int64_t fp_slice = (int64_t)bh * P.cap * D;
     const FpSource<D, G> src{P.k_old + fp_slice, P.v_old + fp_slice, P.pos_old + (bh / P.Hkv) * P.cap, j};
-    quantize_group<BF16, D, G>(sm, red, src, bh, P.n_q + j * G, P.k_codes, P.v_codes, P.k_scale, P.k_zero,
+    quantize_group<BF16, D, G, BITS>(sm, red, src, bh, P.n_q + j * G, P.k_codes, P.v_codes, P.k_scale, P.k_zero,
                                P.v_scale, P.v_zero, P.pos_q, P.qcap, P.Hkv);
   } else {
     compact_rows(blockIdx.x - nq, bh, P.k_old, P.v_old, P.pos_old, P.k_new, P.v_new, P.pos_new, P.d,
@@ -300,7 +323,7 @@ struct PrefillParams {
   int d, G, W, cap, qcap, Hkv, L, E, n_fp;
 };
 
-template <bool BF16, int D, int G>
+template <bool BF16, int D, int G, int BITS>
 __global__ void __launch_bounds__(256) prefill_kernel(const PrefillParams P) {
   extern __shared__ uint16_t sm[];
   __shared__ float red[8 * 128];
@@ -313,7 +336,7 @@ __global__ void __launch_bounds__(256) prefill_kernel(const PrefillParams P) {
     if (tid < G) posl[tid] = evicted_position(ev, j * G + tid, P.W);
     __syncthreads();
     const PromptSource<D, G> src{P.k + prompt, P.v + prompt, posl};
-    quantize_group<BF16, D, G>(sm, red, src, bh, (ev - 1) * P.W + j * G, P.k_codes, P.v_codes, P.k_scale,
+    quantize_group<BF16, D, G, BITS>(sm, red, src, bh, (ev - 1) * P.W + j * G, P.k_codes, P.v_codes, P.k_scale,
                                P.k_zero, P.v_scale, P.v_zero, P.pos_q, P.qcap, P.Hkv);
     return;
   }
@@ -349,26 +372,30 @@ __global__ void __launch_bounds__(256) prefill_kernel(const PrefillParams P) {
     P.pos_fp[(bh / P.Hkv) * P.cap + nb * 32 + tid] = posl[tid];
 }
 
-// compile-time head dimension and group size: the index arithmetic of the staging,
+// compile-time head dimension, group size and bit width: the index arithmetic of the staging,
 // encoding and packing loops is then shifts and masks
 struct CompressLaunch {
-  template <bool BF16, int D, int G>
+  template <bool BF16, int D, int G, int BITS>
   static void go(dim3 grid, size_t lds, hipStream_t st, const CompressParams& P) {
-    hipLaunchKernelGGL((compress_kernel<BF16, D, G>), grid, dim3(256), lds, st, P);
+    hipLaunchKernelGGL((compress_kernel<BF16, D, G, BITS>), grid, dim3(256), lds, st, P);
   }
 };
 struct PrefillLaunch {
-  template <bool BF16, int D, int G>
+  template <bool BF16, int D, int G, int BITS>
   static void go(dim3 grid, size_t lds, hipStream_t st, const PrefillParams& P) {
-    hipLaunchKernelGGL((prefill_kernel<BF16, D, G>), grid, dim3(256), lds, st, P);
+    hipLaunchKernelGGL((prefill_kernel<BF16, D, G, BITS>), grid, dim3(256), lds, st, P);
   }
 };
 template <class L, bool BF16, int D, class Params>
 static void dispatch_g(const Shape& s, dim3 grid, size_t lds, hipStream_t st, const Params& P) {
-  switch (s.G) {
-    case 32: L::template go<BF16, D, 32>(grid, lds, st, P); break;
-    case 64: L::template go<BF16, D, 64>(grid, lds, st, P); break;
-    default: L::template go<BF16, D, 128>(grid, lds, st, P); break;
+  const int key = s.G * 8 + s.bits;
+  switch (key) {
+    case 32 * 8 + 2: L::template go<BF16, D, 32, 2>(grid, lds, st, P); break;
+    case 64 * 8 + 2: L::template go<BF16, D, 64, 2>(grid, lds, st, P); break;
+    case 128 * 8 + 2: L::template go<BF16, D, 128, 2>(grid, lds, st, P); break;
+    case 32 * 8 + 4: L::template go<BF16, D, 32, 4>(grid, lds, st, P); break;
+    case 64 * 8 + 4: L::template go<BF16, D, 64, 4>(grid, lds, st, P); break;
+    default: L::template go<BF16, D, 128, 4>(grid, lds, st, P); break;
   }
 }
 template <class L, bool BF16, class Params>

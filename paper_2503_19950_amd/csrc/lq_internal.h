@@ -10,6 +10,7 @@ namespace lq {
 struct Shape {
   int B, Hq, Hkv, d, W, G, cap, qcap, gh;  // gh = Hq/Hkv, cap = 3W
   int nkc, nnt, ngc;                       // d/32, d/16, ceil(d/G)
+  int bits;                                // 2 or 4
   bool bf16;
 };
 

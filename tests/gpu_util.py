@@ -37,7 +37,7 @@ def build_gpu(wl, seed_id, L, q_capacity=None, poison=False, b_list=None):
         while q_capacity % 64 or q_capacity % W:
             q_capacity += W
     cfg = binding.make_config(wl["B"], wl["Hq"], wl["Hkv"], wl["d"], wl["F"], wl["G"], wl["dtype"],
-                              q_capacity)
+                              q_capacity, wl.get("bits", 2))
     dc = binding.DeviceCache(cfg, poison=poison)
     step = 3 * W * 8
     for t0 in range(0, L, step):
@@ -48,7 +48,7 @@ def build_gpu(wl, seed_id, L, q_capacity=None, poison=False, b_list=None):
 
 
 def build_oracle(wl, seed_id, L, b, h):
-    c = SliceCache(wl["F"] // 2, wl["G"], wl["d"], wl["dtype"])
+    c = SliceCache(wl["F"] // 2, wl["G"], wl["d"], wl["dtype"], wl.get("bits", 2))
     step = 1 << 15
     for t0 in range(0, L, step):
         K, V = inputs.slice_kv(seed_id, b, h, t0, min(L, t0 + step), wl)
@@ -80,10 +80,11 @@ def check_state(dc, oc, wl, b, h):
         assert np.array_equal(got, inputs.to_bits16(rows, dt)), "fp rows " + which
     if n_q == 0:
         return
-    nw = n_q // 32 * 64 * nkc
+    bits = wl.get("bits", 2)
+    nw = n_q // 32 * 64 * nkc * (bits // 2)
     for which, buf, codes in (("k", dc.k_codes, oc.K_codes), ("v", dc.v_codes, oc.V_codes)):
-        words = _np(buf, np.uint32)[bh * (qcap // 32) * 64 * nkc:][:nw]
-        want = layout.pack_codes(codes, which)
+        words = _np(buf, np.uint32)[bh * (qcap // 32) * 64 * nkc * (bits // 2):][:nw]
+        want = layout.pack_codes(codes, which, bits=bits)
         assert np.array_equal(words, want), "packed codes " + which
     for buf, meta, name in ((dc.k_scale, oc.K_scale, "k_scale"), (dc.k_zero, oc.K_zero, "k_zero")):
         got = _np(buf, np.uint16)[bh * (qcap // G) * d:][:n_q // G * d]
@@ -98,9 +99,11 @@ def check_attention(dc, oc_by_slice, wl, q_np, scale=0.0, large_outputs=False):
     """Run logquant_decode_attn for the whole batch; compare the heads of the given
     (b, h) slices with the oracle.  Returns the largest abs error seen.
 
-    large_outputs: for inputs built to give outputs far above 1 the rounding of the
-    output to T alone exceeds the absolute tolerance; the bound then adds half an ulp
-    of the expected value."""
+    The bound is the max-abs tolerance TOL.  The output is delivered in T, and where
+    half an ulp of the expected value is itself more than half of TOL (|o| > 1.28 in
+    bf16, > 2.05 in fp16) no result in T can be held to TOL: there, and everywhere
+    when `large_outputs` is set (inputs built to give outputs far above 1), the bound
+    adds that half ulp."""
     dt = wl["dtype"]
     gh = wl["Hq"] // wl["Hkv"]
     out = dc.decode_attn(to_dev(q_np, dt), softmax_scale=scale)
@@ -112,12 +115,13 @@ def check_attention(dc, oc_by_slice, wl, q_np, scale=0.0, large_outputs=False):
     for (b, h), oc in oc_by_slice.items():
         want = attention.decode_attention(oc, q_np[b, h * gh:(h + 1) * gh], scale if scale > 0 else None)
         diff = np.abs(out[b, h * gh:(h + 1) * gh] - want)
-        err = diff.max()
-        worst = max(worst, float(err))
-        if large_outputs:
-            assert (diff <= TOL[dt] + HALF_ULP[dt] * np.abs(want)).all(), "attention (b=%d,h=%d)" % (b, h)
-        else:
-            assert err <= TOL[dt], "attention (b=%d,h=%d): max abs err %.3e > %.1e" % (b, h, err, TOL[dt])
+        worst = max(worst, float(diff.max()))
+        half_ulp = HALF_ULP[dt] * np.abs(want)
+        if not large_outputs:
+            half_ulp = np.where(half_ulp > TOL[dt] / 2, half_ulp, 0.0)
+        bad = diff > TOL[dt] + half_ulp
+        assert not bad.any(), "attention (b=%d,h=%d): abs err %.3e at |o| = %.3f, tolerance %.1e" % (
+            b, h, diff[bad].max(), np.abs(want)[bad].max(), TOL[dt])
     return worst
 
 
@@ -147,7 +151,7 @@ def build_gpu_sampled(wl, seed_id, L, distinct, q_capacity=None):
         while q_capacity % 64:
             q_capacity += W
     cfg = binding.make_config(wl["B"], wl["Hq"], wl["Hkv"], wl["d"], wl["F"], wl["G"], wl["dtype"],
-                              q_capacity)
+                              q_capacity, wl.get("bits", 2))
     dc = binding.DeviceCache(cfg)
     step = 3 * W * 8
     for t0 in range(0, L, step):
@@ -166,7 +170,7 @@ def new_cache(wl, L, q_capacity=None, poison=False):
         while q_capacity % 64 or q_capacity % W:
             q_capacity += W
     cfg = binding.make_config(wl["B"], wl["Hq"], wl["Hkv"], wl["d"], wl["F"], wl["G"], wl["dtype"],
-                              q_capacity)
+                              q_capacity, wl.get("bits", 2))
     return binding.DeviceCache(cfg, poison=poison)
 
 
@@ -191,8 +195,9 @@ def live_buffers(dc, wl):
     for which, buf in (("k", dc.k_fp[cur]), ("v", dc.v_fp[cur])):
         flat = _np(buf, np.uint16).reshape(BH, cap * d)
         out["fp_" + which] = np.stack([layout.gather_fp(flat[i], which, n_fp, d) for i in range(BH)])
-    out["k_codes"] = _np(dc.k_codes, np.uint32).reshape(BH, -1)[:, :n_q // 32 * 64 * nkc]
-    out["v_codes"] = _np(dc.v_codes, np.uint32).reshape(BH, -1)[:, :n_q // 32 * 64 * nkc]
+    wpl = nkc * (wl.get("bits", 2) // 2)
+    out["k_codes"] = _np(dc.k_codes, np.uint32).reshape(BH, -1)[:, :n_q // 32 * 64 * wpl]
+    out["v_codes"] = _np(dc.v_codes, np.uint32).reshape(BH, -1)[:, :n_q // 32 * 64 * wpl]
     out["k_scale"] = _np(dc.k_scale, np.uint16).reshape(BH, -1)[:, :n_q // G * d]
     out["k_zero"] = _np(dc.k_zero, np.uint16).reshape(BH, -1)[:, :n_q // G * d]
     out["v_scale"] = _np(dc.v_scale, np.uint16).reshape(BH, -1)[:, :n_q // 32 * ngc * 32]

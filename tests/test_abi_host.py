@@ -39,12 +39,15 @@ def test_sizes_match_the_documented_layouts():
     assert s.k_meta == bh * (qc // 32) * d * 2 and s.v_meta == bh * qc * 4 * 2
     assert s.pos_fp == cap * 4 and s.pos_q == qc * 4
     assert s.workspace == B.logquant_workspace_bytes(_cfg()) > 0
+    s4 = B.logquant_sizes(_cfg(bits=4))
+    assert s4.k_codes == s4.v_codes == bh * qc * d // 2 and s4.k_meta == s.k_meta and s4.k_fp == s.k_fp
     s = B.logquant_sizes(_cfg(d=96, group=64, Hq=8, Hkv=8, fp_budget=384, q_capacity=384 * 2))
     assert s.v_meta == 8 * 768 * 2 * 2        # ceil(96/64) = 2 channel groups
 
 
 @pytest.mark.parametrize("kw,status", [
-    (dict(bits=4), B.LQ_ERR_UNSUPPORTED),
+    (dict(bits=3), B.LQ_ERR_UNSUPPORTED),
+    (dict(bits=8), B.LQ_ERR_UNSUPPORTED),
     (dict(d=80), B.LQ_ERR_UNSUPPORTED),
     (dict(group=16), B.LQ_ERR_UNSUPPORTED),
     (dict(fp_budget=84, q_capacity=42 * 64), B.LQ_ERR_UNSUPPORTED),   # the paper's W = 42: G does not divide W
@@ -135,6 +138,8 @@ def test_plan_reports_the_algorithmic_bytes():
     cfg5 = _cfg(B=16, Hq=32, Hkv=32, d=96, fp_budget=384, group=64, dtype="bf16", q_capacity=32256 + 192 * 2)
     assert B.logquant_decode_plan(cfg5, 512, 32256).bytes_read == 1124597760
     assert p.blocks >= 1 and p.splits >= 1
+    # 4-bit codes: d/2 bytes per slot for keys and for values
+    assert B.logquant_decode_plan(_cfg(bits=4), 128, 384).bytes_read == 8 * (128 * 512 + 384 * (128 + 32))
 
 
 def test_status_strings():

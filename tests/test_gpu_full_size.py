@@ -95,3 +95,12 @@ def test_workload_5_mha_d96_l32768():
     dc = U.build_gpu_sampled(wl, 5, wl["L"], slices)
     assert (dc.c.n_fp, dc.c.n_q) == (512, 32256)
     _check(dc, wl, 5, wl["L"], slices)
+
+
+def test_workload_3_shape_with_4_bit_codes():
+    """The 4-bit variant (Sec. 3.2.1, Table 3) at workload 3's size: state built by
+    logquant_prefill, one slice checked completely against the oracle."""
+    wl = dict(inputs.WORKLOADS[3], bits=4)
+    dc = U.build_gpu_prefill(wl, 3, wl["L"])
+    assert (dc.c.n_fp, dc.c.n_q) == (512, 130560)
+    _check(dc, wl, 3, wl["L"], [(0, 5)])

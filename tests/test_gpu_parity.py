@@ -26,6 +26,14 @@ SMALL = [
     ("single_token", U.make_wl(B=1, Hq=4, Hkv=1, d=128, G=32, F=64), 1),
     ("exactly_at_event", U.make_wl(B=1, Hq=4, Hkv=1, d=128, G=32, F=64), 96),
     ("one_before_event", U.make_wl(B=1, Hq=4, Hkv=1, d=128, G=32, F=64), 95),
+    # the 4-bit variant (Sec. 3.2.1, Table 3)
+    ("bits4_cfg1", dict(inputs.WORKLOADS[1], bits=4), 512),
+    ("bits4_d128_g64_bf16_sinks", U.make_wl(B=1, Hq=8, Hkv=2, d=128, G=64, F=128, dtype="bf16", sinks=4,
+                                            bits=4), 1000),
+    ("bits4_mha_d96_g64_bf16_midwindow", U.make_wl(B=2, Hq=4, Hkv=4, d=96, G=64, F=128, dtype="bf16",
+                                                   dist="laplace", bits=4), 700),
+    ("bits4_d64_gqa2_partial_tile", U.make_wl(B=2, Hq=4, Hkv=2, d=64, G=32, F=64, bits=4), 365),
+    ("bits4_d128_g128_gqa8", U.make_wl(B=1, Hq=8, Hkv=1, d=128, G=128, F=256, bits=4), 900),
 ]
 
 

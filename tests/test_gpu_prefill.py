@@ -24,6 +24,8 @@ CASES = [
     ("d96_g64_ragged_value_group", U.make_wl(B=1, Hq=4, Hkv=4, d=96, G=64, F=128, dtype="bf16"), 700),
     ("d128_g128", U.make_wl(B=1, Hq=8, Hkv=1, d=128, G=128, F=256), 900),
     ("d128_g64_bf16_sinks", U.make_wl(B=1, Hq=8, Hkv=2, d=128, G=64, F=128, dtype="bf16", sinks=4), 1000),
+    ("bits4_w32_many_events", U.make_wl(B=1, Hq=4, Hkv=2, d=128, G=32, F=64, bits=4), 32 * 23 + 9),
+    ("bits4_d96_g64_bf16", U.make_wl(B=1, Hq=4, Hkv=4, d=96, G=64, F=128, dtype="bf16", bits=4), 700),
 ]
 
 
