@@ -1,39 +1,40 @@
 // Fused decode attention for gfx950 (Eq. 2 with Eq. 6's 1/sqrt(d), one softmax over
-// the original-precision rows and the 2-bit rows, Sec. 2.4).  The 2-bit rows are
-// never dequantized in memory:
+// the original-precision rows and the quantized rows, Sec. 2.4).  The quantized rows
+// (2-bit codes, or 4-bit: Sec. 3.2.1) are never dequantized in memory:
 //
 //   logits   q.k_hat_t = sum_c q_c z_c + sum_c (q_c s_c) code_tc
 //            -> per key group (G tokens) the products q_c s_c are formed once, split
 //               into an fp16 head and an fp16 tail (together exact for 11-bit or
-//               8-bit factors) and become the B operands of two 16x16x32 matrix
-//               instructions whose A operand is the code tile; sum_c q_c z_c is a
-//               per-group bias.  (A single fp16 rounding of q_c s_c is not enough:
-//               with outlier channels its error alone moves the logits by ~1e-2.)
+//               8-bit factors) and become two rows of the A operand of a 16x16x32
+//               matrix instruction: row 4*head + piece (pieces 2 and 3 are zero).
+//               The code tile is the B operand, 16 tokens per instruction.  Lane
+//               (row group q4, column n16) of the result then holds, for head q4 and
+//               token n16, head and tail in two registers: one add gives the logit.
+//               sum_c q_c z_c is a per-group bias.  (A single fp16 rounding of
+//               q_c s_c is not enough: with outlier channels its error alone moves
+//               the logits by ~1e-2.)
 //   output   sum_t p_t v_hat_tc = sum_t p_t vz_t + sum_t (p_t vs_t) code_tc
-//            -> p_t vs_t (one per token and channel group) is the A operand, the
-//               code tile the B operand; sum_t p_t vz_t is kept per channel group.
+//            -> p_t vs_t (row 4*channel group + head) is the A operand, the code
+//               tile the B operand; sum_t p_t vz_t is kept per channel group.  The
+//               probabilities go from the softmax lanes (head x token) to the lanes
+//               of the output step (token octets) through LDS as fp16.
 //
 // Codes as operands.  An fp16 lane whose only set bits are mantissa bits 2v, 2v+1 is
 // the subnormal number code * 2^(2v-24); gfx950's matrix cores take subnormal
-// operands exactly.  The packed layout puts the eight codes a lane feeds to one
-// matrix instruction into one byte of the low and one byte of the high half of a
-// 32-bit word, so four ANDs (plus one shift by 8 for the odd operand of a word)
+// operands exactly.  The packed layout puts the eight 2-bit codes a lane feeds to
+// one matrix instruction into one byte of the low and one byte of the high half of
+// a 32-bit word, so four ANDs (plus one shift by 8 for the odd operand of a word)
 // produce the four operand registers: 9 VALU instructions per 16 codes, no
 // integer-to-float conversion.  The factor 2^(2v) that depends on the position v
 // of a code inside its byte is cancelled in the other operand: q is pre-multiplied
 // by 2^(3-2v) per channel, and the probabilities by the same factor per token slot
-// (folded into the exponent of exp2, so it costs nothing).
+// (folded into the exponent of exp2, so it costs nothing).  4-bit codes work the
+// same way with two nibble positions (see codes4).
 //
-// The up to four query heads that share a kv head occupy four of the 16 columns of
-// the logits tile; the other twelve columns repeat them for three more 16-token
-// tiles, so one accumulator quad per lane ends up holding logits of 64 tokens x 4
-// heads with every lane busy in the softmax.
-//
-// Work split: a workgroup has eight independent wavefronts; the wavefronts of all
-// workgroups of one (batch row, kv head) are numbered 0..NW-1, the first `nwf` walk
-// the fp rows in units of 32, the others walk the quantized rows in tiles of 64:
-// slot w owns every NWQ-th tile starting at w (all wavefronts sweep memory side by
-// side), and the slots of one workgroup are pooled and drawn dynamically.
+// Work split: a workgroup has eight (or four) independent wavefronts; the
+// wavefronts of all workgroups of one (batch row, kv head) are numbered 0..NW-1,
+// the first `nwf` walk the fp rows in units of 32, the others walk the quantized
+// rows in tiles of 64 (schedule: see "Tile schedule" below).
 // Partial (max, sum, output) triples are merged in LDS per workgroup and written
 // to the workspace.  Every workgroup then takes a ticket from a counter of its
 // (batch row, kv head, head group); the one that draws the last ticket merges all
