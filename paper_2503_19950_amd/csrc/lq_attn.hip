@@ -17,7 +17,7 @@ static int env_int(const char* name, int dflt) {
   return v && *v ? atoi(v) : dflt;
 }
 
-// Launch shape: wavefronts per workgroup (8 or 4), context splits per (b, kv head,
+// Launch shape: wavefronts per workgroup (12, 8 or 4), context splits per (b, kv head,
 // head group), and the share of wavefronts that walks the fp rows.  Work is counted
 // in units of one 64-slot quantized tile; a 32-row fp unit weighs its bytes relative
 // to that.  A compute unit holds eight wavefronts of this kernel, i.e. one
@@ -40,7 +40,7 @@ void plan_decode(const Shape& s, int n_fp, int n_q, lq_plan* plan) {
   int best_wpb = 8, best_splits = 1;
   double best = 1e300;
   for (int wpb = 8; wpb >= 4; wpb -= 4) {
-    if (force_wpb && wpb != force_wpb) continue;
+    if (force_wpb && force_wpb != 12 && wpb != force_wpb) continue;
     const int slots = cus * (8 / wpb);
     int smax = (int)ceil(units / wpb);            // at least one unit per wavefront
     if (smax > max_splits(s)) smax = max_splits(s);
@@ -52,6 +52,13 @@ void plan_decode(const Shape& s, int n_fp, int n_q, lq_plan* plan) {
       if (t < best - 1e-9) { best = t; best_wpb = wpb; best_splits = sp; }
     }
   }
+  // Twelve wavefronts per workgroup (three per SIMD) pay off for long contexts on few
+  // groups: measured on 131072 tokens x 8 kv heads 25.7 against 27.3 us, but slower
+  // than 8 with fewer than ~6 tiles per wavefront and slower than 4 when every
+  // compute unit holds two workgroups anyway.  Only built for 2-bit codes (the 4-bit
+  // tile does not fit 168 registers).
+  if (s.bits == 2 && (force_wpb == 12 || (!force_wpb && best_wpb == 8 && units / (best_splits * 8.0) >= 6.0)))
+    best_wpb = 12;
   const int splits = best_splits, WPB = best_wpb;
   const int NW = WPB * splits;
   int nwf = (int)lround(NW * (r * TF) / units);

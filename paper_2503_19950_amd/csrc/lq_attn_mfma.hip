@@ -324,10 +324,12 @@ __device__ __forceinline__ void online_softmax_rows(State<NNT>& st, const float*
   }
 }
 
-// NWB: wavefronts per workgroup (8, or 4 when there are enough (b, kv head) groups to
-// put two workgroups on every compute unit).
+// NWB: wavefronts per workgroup: 8; 4 when there are enough (b, kv head) groups to put
+// two workgroups on every compute unit; 12 (three wavefronts per SIMD, at most 168
+// registers) for long contexts, where the extra wavefront hides more than the tighter
+// register budget costs.
 template <bool BF16, int D, int G, int NWB, int BITS>
-__global__ void __launch_bounds__(64 * NWB, 2)
+__global__ void __launch_bounds__(64 * NWB, NWB == 12 ? 3 : 2)
 attn_mfma_kernel(const AttnParams P) {
   constexpr int NKC = D / 32, NNT = D / 16, NGC = (D + G - 1) / G;
   constexpr int WPL = NKC * (BITS / 2);           // code words per lane and 32-slot block
@@ -400,28 +402,30 @@ attn_mfma_kernel(const AttnParams P) {
       uint4 vs[2], vz[2];
       uint4 ks8[NGRP], kz8[NGRP];
     };
-    auto load_tile = [&](int t) {
-      Tile T;
-      const char* kcp = kcb + (int64_t)t * (2 * 64 * WPL * 4);
-      const char* vcp = vcb + (int64_t)t * (2 * 64 * WPL * 4);
-      const char* vsp = vsb + (int64_t)t * (2 * NGC * 32 * 2);
-      const char* vzp = vzb + (int64_t)t * (2 * NGC * 32 * 2);
-#pragma unroll
-      for (int b2 = 0; b2 < 2; ++b2) {
-        T.kc[b2] = *reinterpret_cast<const Words<WPL>*>(kcp + b2 * (64 * WPL * 4) + code_off);
-        T.vc[b2] = *reinterpret_cast<const Words<WPL>*>(vcp + b2 * (64 * WPL * 4) + code_off);
-        T.vs[b2] = *reinterpret_cast<const uint4*>(vsp + b2 * (NGC * 32 * 2) + vm_off);
-        T.vz[b2] = *reinterpret_cast<const uint4*>(vzp + b2 * (NGC * 32 * 2) + vm_off);
-      }
+    // A tile's registers are refilled piecewise with the next tile's data as soon as
+    // their content has been consumed (key scales right after the q*s preparation,
+    // key codes after the logits, value codes and scales after each output step), so
+    // only one tile's worth of registers is live and every piece still has most of a
+    // tile's processing time to arrive.
+    auto load_kmeta = [&](Tile& T, int t) {
 #pragma unroll
       for (int e = 0; e < NGRP; ++e) {
         const int grp = G <= 64 ? t * NGRP + e : t / (G / 64);
         T.ks8[e] = *reinterpret_cast<const uint4*>(ksb + (int64_t)grp * (D * 2) + km_off);
         T.kz8[e] = *reinterpret_cast<const uint4*>(kzb + (int64_t)grp * (D * 2) + km_off);
       }
-      return T;
     };
-
+    auto load_kcodes = [&](Tile& T, int t) {
+      const char* kcp = kcb + (int64_t)t * (2 * 64 * WPL * 4);
+#pragma unroll
+      for (int b2 = 0; b2 < 2; ++b2)
+        T.kc[b2] = *reinterpret_cast<const Words<WPL>*>(kcp + b2 * (64 * WPL * 4) + code_off);
+    };
+    auto load_v = [&](Tile& T, int t, int b2) {
+      T.vc[b2] = *reinterpret_cast<const Words<WPL>*>(vcb + (int64_t)t * (2 * 64 * WPL * 4) + b2 * (64 * WPL * 4) + code_off);
+      T.vs[b2] = *reinterpret_cast<const uint4*>(vsb + (int64_t)t * (2 * NGC * 32 * 2) + b2 * (NGC * 32 * 2) + vm_off);
+      T.vz[b2] = *reinterpret_cast<const uint4*>(vzb + (int64_t)t * (2 * NGC * 32 * 2) + b2 * (NGC * 32 * 2) + vm_off);
+    };
 
     // Tile schedule.  The first two tiles of a wavefront are fixed (wq, wq + NWQ) and
     // the loads of the first go out before anything else touches memory.  The later
@@ -454,7 +458,12 @@ attn_mfma_kernel(const AttnParams P) {
     };
     int ta = wq, tb = wq + NWQ;
     Tile A;
-    if (ta < TQ) A = load_tile(ta);
+    if (ta < TQ) {
+      load_kmeta(A, ta);
+      load_kcodes(A, ta);
+      load_v(A, ta, 0);
+      load_v(A, ta, 1);
+    }
 
     // q of (head q4, channels 8*c8..+7): raw pairs for the bias dot products, and
     // fp16 pairs pre-multiplied by 2^(3-2v) (v = pair index) for the q*s operands
@@ -495,7 +504,7 @@ attn_mfma_kernel(const AttnParams P) {
       if (lane < 32) { p_lds[wave][0][4][lane] = 0; p_lds[wave][1][4][lane] = 0; }
     }
 
-    auto process = [&](const Tile& cur, int t) {
+    auto process = [&](Tile& cur, int t, int tn) {   // tn: the tile to refill the registers with
       // ---- q*s (fp16 head and tail) and bias = sum_c q_c z_c for each key group
       float bo[4];
       {
@@ -521,6 +530,7 @@ attn_mfma_kernel(const AttnParams P) {
           }
           bias[e] = row_sum(bp) * P.c;
         }
+        load_kmeta(cur, tn);
 #pragma unroll
         for (int u = 0; u < 4; ++u) bo[u] = bias[(u * NGRP) >> 2] + offs[u];
       }
@@ -543,6 +553,8 @@ attn_mfma_kernel(const AttnParams P) {
           }
         }
       }
+
+      load_kcodes(cur, tn);
 
       // this lane: head q4, token 16*u + n16 of the tile; head and tail rows are j = 0, 1
       float s[4], p[4];
@@ -594,23 +606,19 @@ attn_mfma_kernel(const AttnParams P) {
           const uint4 b = operand_codes<BITS>(cur.vc[ks].w, nt);
           st.acc[nt] = mfma_f16(a, b, st.acc[nt]);
         }
+        load_v(cur, tn, ks);
       }
       wave_lds_sync();   // p_lds and qs_lds are rewritten by the next tile
     };
 
     if (ta < TQ) {
-      int kd = draw();
       while (true) {
-        Tile B = load_tile(tb < TQ ? tb : ta);
-        process(A, ta);
-        if (tb >= TQ) break;
-        ta = drawn_tile(kd);
-        kd = draw();
-        A = load_tile(ta < TQ ? ta : tb);
-        process(B, tb);
-        if (ta >= TQ) break;
+        const bool more = tb < TQ;
+        const int kd = draw();                 // for the tile after tb
+        process(A, ta, more ? tb : ta);
+        if (!more) break;
+        ta = tb;
         tb = drawn_tile(kd);
-        kd = draw();
       }
     }
     // canonical partial of this wavefront: o[g][c], m[g], l[g]
@@ -758,6 +766,7 @@ attn_mfma_kernel(const AttnParams P) {
   __syncthreads();
   if (!is_last) return;
   static_assert(NWB * 4 * D >= 4 * 256, "o_lds too small for the merge weights");
+  static_assert(NWB >= 4, "one wavefront per head merges the splits");
   float* w_lds = &o_lds[0][0][0];              // [4][256] weights, o_lds is free again
   // Wavefront w merges head w.  The partials are read past the caches (device-
   // coherent loads), 16 bytes per lane so that the address unit sees few, wide
@@ -947,6 +956,7 @@ hipError_t launch_decode_attn_mfma(const Shape& s, const lq_cache& c, const void
   static const int dynamic = [] { const char* v = getenv("LOGQUANT_ATTN_DYNAMIC"); return v && *v ? atoi(v) : 1; }();
   P.dynamic = dynamic;
   dim3 grid(plan.splits, s.B * s.Hkv * (s.gh / P.hb));
+  if (plan.waves_per_block == 12 && s.bits == 2) return launch_mfma_t<12, 2>(s, P, grid, st);
   if (plan.waves_per_block == 4)
     return s.bits == 4 ? launch_mfma_t<4, 4>(s, P, grid, st) : launch_mfma_t<4, 2>(s, P, grid, st);
   return s.bits == 4 ? launch_mfma_t<8, 4>(s, P, grid, st) : launch_mfma_t<8, 2>(s, P, grid, st);
