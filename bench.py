@@ -29,6 +29,8 @@ def parse():
     ap.add_argument("--copies", type=int, default=0, help="cache copies to rotate over (0 = auto)")
     ap.add_argument("--bits", type=int, default=2, choices=(2, 4),
                     help="code width; 2 is BASELINE.json's setting, 4 the paper's higher-precision variant")
+    ap.add_argument("--unfused", action="store_true",
+                    help="time the step as separate append and attention launches instead of logquant_decode_step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 256 MiB device copy a few times (reference for HBM counters)")
@@ -125,8 +127,11 @@ def main():
     stream = torch.cuda.current_stream()
     sh = stream.cuda_stream
 
+    fused = not a.unfused
+
     def run(n, record):
-        """n steps; returns per-kernel event pairs when record is True."""
+        """n steps; returns per-kernel event pairs when record is True (then with the
+        separate append / compress / attention calls, so that each can be bracketed)."""
         ev = []
         n_compress = 0
         visits = [0] * len(caches)
@@ -135,6 +140,11 @@ def main():
             dc = caches[i]
             j = visits[i]
             visits[i] += 1
+            if fused and not record and dc.c.n_fp + 1 < 3 * W:
+                # append and attention in one launch (logquant_decode_step)
+                st = binding.logquant_decode_step(cfg, dc.c, newK[j], newV[j], qs[s], 0.0, out, dc.workspace, sh)
+                assert st == 0, binding.logquant_status_string(st)
+                continue
             st = binding.logquant_append(cfg, dc.c, newK[j], newV[j], 1, sh)
             assert st == 0, binding.logquant_status_string(st)
             if dc.c.n_fp == 3 * W:
@@ -218,7 +228,7 @@ def main():
         "config": {"workload": wl["name"], "B": wl["B"], "Hq": wl["Hq"], "Hkv": wl["Hkv"],
                    "d": wl["d"], "L": L, "group": wl["G"], "fp_budget": wl["F"], "bits": wl["bits"],
                    "cache_copies_rotated": len(caches), "compress_events_in_timed_region": n_compress,
-                   "attn_blocks": plan.blocks, "attn_splits": plan.splits},
+                   "fused_append": not a.unfused, "attn_blocks": plan.blocks, "attn_splits": plan.splits},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,
                      "kernel": "decode attention", "us_per_launch": attn_us,

@@ -197,6 +197,17 @@ lq_status logquant_decode_attn(const lq_config *cfg, const lq_cache *cache, cons
                                float softmax_scale, void *out, void *workspace,
                                void *stream);
 
+/* One decode step in one launch: logquant_append of one new token per sequence
+ * (Algorithm 1, the append branch) followed by logquant_decode_attn over the cache
+ * including that token (Eq. 2; Sec. 2.4), with the same results as the two calls.
+ *   k_new, v_new : DEVICE [B][Hkv][1][d] T      q, out, workspace: as for decode_attn.
+ * Requires n_fp + 1 < 3W (else LQ_ERR_STATE): at the step that fills the window the
+ * caller appends, runs logquant_compress and attends with the separate calls.
+ * On success n_fp += 1. */
+lq_status logquant_decode_step(const lq_config *cfg, lq_cache *cache, const void *k_new,
+                               const void *v_new, const void *q, float softmax_scale, void *out,
+                               void *workspace, void *stream);
+
 /* Launch shape logquant_decode_attn would use for these counts (HOST out), so a
  * harness can report bytes per launch; pure host arithmetic. */
 typedef struct {

@@ -46,7 +46,8 @@ class lq_plan(C.Structure):
 
 
 EXPORTS = ("logquant_sizes", "logquant_workspace_bytes", "logquant_workspace_init", "logquant_append", "logquant_compress",
-           "logquant_prefill", "logquant_prefill_positions", "logquant_decode_attn", "logquant_decode_plan",
+           "logquant_prefill", "logquant_prefill_positions", "logquant_decode_attn", "logquant_decode_step",
+           "logquant_decode_plan",
            "logquant_status_string")
 
 if not os.path.exists(LIB_PATH):
@@ -74,6 +75,9 @@ _lib.logquant_prefill_positions.restype = C.c_int
 _lib.logquant_decode_attn.argtypes = [C.POINTER(lq_config), C.POINTER(lq_cache), C.c_void_p, C.c_float,
                                       C.c_void_p, C.c_void_p, C.c_void_p]
 _lib.logquant_decode_attn.restype = C.c_int
+_lib.logquant_decode_step.argtypes = [C.POINTER(lq_config), C.POINTER(lq_cache), C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]
+_lib.logquant_decode_step.restype = C.c_int
 _lib.logquant_decode_plan.argtypes = [C.POINTER(lq_config), C.c_int32, C.c_int32, C.POINTER(lq_plan)]
 _lib.logquant_decode_plan.restype = C.c_int
 _lib.logquant_status_string.argtypes = [C.c_int]
@@ -146,6 +150,11 @@ def logquant_prefill_positions(W, L):
 def logquant_decode_attn(cfg, cache, q, softmax_scale, out, workspace, stream=0):
     return _lib.logquant_decode_attn(_p(cfg), _p(cache), _ptr(q), float(softmax_scale), _ptr(out),
                                      _ptr(workspace), stream)
+
+
+def logquant_decode_step(cfg, cache, k_new, v_new, q, softmax_scale, out, workspace, stream=0):
+    return _lib.logquant_decode_step(_p(cfg), _p(cache), _ptr(k_new), _ptr(v_new), _ptr(q), float(softmax_scale),
+                                     _ptr(out), _ptr(workspace), stream)
 
 
 def logquant_decode_plan(cfg, n_fp, n_q):
@@ -257,6 +266,15 @@ class DeviceCache:
                 self.compress()
                 ev += 1
         return ev
+
+    def decode_step(self, k_new, v_new, q, out=None, softmax_scale=0.0):
+        """Append one token ([B][Hkv][1][d]) and attend, in one launch."""
+        if out is None:
+            out = self.torch.empty_like(q)
+        assert k_new.is_contiguous() and v_new.is_contiguous()
+        self._check(logquant_decode_step(self.cfg, self.c, k_new, v_new, q, softmax_scale, out, self.workspace,
+                                         self._stream()), "logquant_decode_step")
+        return out
 
     def decode_attn(self, q, out=None, softmax_scale=0.0):
         if out is None:

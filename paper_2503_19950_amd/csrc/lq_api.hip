@@ -212,6 +212,29 @@ lq_status logquant_decode_attn(const lq_config* cfg, const lq_cache* cache, cons
   return LQ_OK;
 }
 
+lq_status logquant_decode_step(const lq_config* cfg, lq_cache* cache, const void* k_new,
+                               const void* v_new, const void* q, float softmax_scale, void* out,
+                               void* workspace, void* stream) {
+  if (!cfg || !cache || !k_new || !v_new || !q || !out || !workspace) return LQ_ERR_NULL;
+  Shape s;
+  lq_status st = make_shape(cfg, &s);
+  if (st != LQ_OK) return st;
+  if (!cache_ptrs_ok(cache)) return LQ_ERR_NULL;
+  if ((st = cache_state_ok(s, cache)) != LQ_OK) return st;
+  if (cache->n_fp + 1 >= s.cap) return LQ_ERR_STATE;   // the window would be full: append, compress, attend
+  lq_cache after = *cache;
+  after.n_fp += 1;
+  lq_plan plan;
+  plan_decode(s, after.n_fp, after.n_q, &plan);
+  if (!(softmax_scale > 0.f)) softmax_scale = 1.0f / sqrtf((float)s.d);
+  clear_stale_error();
+  if (launch_decode_step(s, after, k_new, v_new, q, softmax_scale, out, workspace, plan,
+                         (hipStream_t)stream) != hipSuccess)
+    return LQ_ERR_HIP;
+  cache->n_fp = after.n_fp;
+  return LQ_OK;
+}
+
 const char* logquant_status_string(lq_status s) {
   switch (s) {
     case LQ_OK: return "ok";

@@ -10,7 +10,8 @@ namespace lq {
 hipError_t launch_decode_attn_ref(const Shape& s, const lq_cache& c, const void* q, float scale,
                                   void* out, void* ws, int splits, hipStream_t st);
 hipError_t launch_decode_attn_mfma(const Shape& s, const lq_cache& c, const void* q, float scale,
-                                   void* out, void* ws, const lq_plan& plan, hipStream_t st);
+                                   void* out, void* ws, const lq_plan& plan, hipStream_t st,
+                                   const void* k_new, const void* v_new);
 
 static int env_int(const char* name, int dflt) {
   const char* v = getenv(name);
@@ -77,12 +78,31 @@ void plan_decode(const Shape& s, int n_fp, int n_q, lq_plan* plan) {
   plan->bytes_read = cache_bytes_read(s, n_fp, n_q);
 }
 
+// LOGQUANT_ATTN_PLAIN=1 selects the plain one-token-at-a-time kernel (cross-check).
+static bool plain_attention() {
+  static const int plain = env_int("LOGQUANT_ATTN_PLAIN", 0);
+  return plain != 0;
+}
+
 hipError_t launch_decode_attn(const Shape& s, const lq_cache& c, const void* q, float scale,
                               void* out, void* ws, const lq_plan& plan, hipStream_t st) {
-  // LOGQUANT_ATTN_PLAIN=1 selects the plain one-token-at-a-time kernel (cross-check).
-  static const int plain = env_int("LOGQUANT_ATTN_PLAIN", 0);
-  if (plain) return launch_decode_attn_ref(s, c, q, scale, out, ws, plan.splits, st);
-  return launch_decode_attn_mfma(s, c, q, scale, out, ws, plan, st);
+  if (plain_attention()) return launch_decode_attn_ref(s, c, q, scale, out, ws, plan.splits, st);
+  return launch_decode_attn_mfma(s, c, q, scale, out, ws, plan, st, nullptr, nullptr);
+}
+
+// `c` already counts the new row (n_fp includes it); the row itself is still only in
+// k_new / v_new.
+hipError_t launch_decode_step(const Shape& s, const lq_cache& c, const void* k_new, const void* v_new,
+                              const void* q, float scale, void* out, void* ws, const lq_plan& plan,
+                              hipStream_t st) {
+  if (plain_attention()) {
+    lq_cache before = c;
+    before.n_fp -= 1;
+    hipError_t e = launch_append(s, before, k_new, v_new, 1, st);
+    if (e != hipSuccess) return e;
+    return launch_decode_attn_ref(s, c, q, scale, out, ws, plan.splits, st);
+  }
+  return launch_decode_attn_mfma(s, c, q, scale, out, ws, plan, st, k_new, v_new);
 }
 
 }  // namespace lq

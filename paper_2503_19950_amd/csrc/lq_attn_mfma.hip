@@ -69,6 +69,14 @@ struct AttnParams {
   float* ws;          // partials
   int* counters;      // CTR_LINES lines per group (ticket, tile pools), zero between launches
   uint16_t* out;
+  // fused append (null k_new: none): the new row of every (b, kv head), [B][Hkv][d],
+  // becomes fp slot n_fp - 1 (n_fp already counts it)
+  const uint16_t* k_new;
+  const uint16_t* v_new;
+  uint16_t* k_fp_w;
+  uint16_t* v_fp_w;
+  int32_t* pos_fp;
+  int Hkv;
   int cap, qcap, n_fp, n_q, gh, hb, splits, nwf;
   int dynamic;        // 0: static tile schedule only
   float c;  // softmax scale * log2(e)
@@ -667,6 +675,42 @@ attn_mfma_kernel(const AttnParams P) {
       for (int nt = 0; nt < NNT; ++nt)
         va[nt] = *reinterpret_cast<const uint4*>(vb + ((int64_t)unit * NNT + nt) * 512);
 
+      if (P.k_new && unit == (P.n_fp - 1) >> 5) {
+        // Fused append.  This wavefront is the only reader of the unit that receives
+        // the new row: it takes the row from the caller's buffers instead of the cache
+        // (whatever the loads above found in that slot is replaced) and stores it into
+        // the cache for the steps to come (once per (b, kv head): head group 0).
+        const int sx = (P.n_fp - 1) & 31, uu_ = sx >> 4;
+        const uint16_t* kn = P.k_new + (int64_t)bh * D;
+        const uint16_t* vn = P.v_new + (int64_t)bh * D;
+        if (n16 == (sx & 15)) {
+#pragma unroll
+          for (int kc = 0; kc < NKC; ++kc) {
+            const uint4 x = *reinterpret_cast<const uint4*>(kn + 32 * kc + 8 * q4);
+            if (uu_ == 0) ka[0][kc] = x; else ka[1][kc] = x;
+            if (hsub == 0)
+              *reinterpret_cast<uint4*>(P.k_fp_w + fp_slice + lane * 8 + ((int64_t)(2 * unit + uu_) * NKC + kc) * 512) = x;
+          }
+        }
+        const int kx = kperm(sx);      // element kx & 7 of the lanes of token octet kx >> 3
+        if (q4 == (kx >> 3)) {
+          const int sh = 16 * (kx & 1), wi = (kx & 7) >> 1;
+#pragma unroll
+          for (int nt = 0; nt < NNT; ++nt) {
+            const uint32_t e = vn[16 * nt + n16];
+            uint32_t w[4] = {va[nt].x, va[nt].y, va[nt].z, va[nt].w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              if (i == wi) w[i] = (w[i] & ~(0xFFFFu << sh)) | (e << sh);
+            va[nt] = make_uint4(w[0], w[1], w[2], w[3]);
+            if (hsub == 0)
+              P.v_fp_w[fp_slice + (((int64_t)unit * NNT + nt) * 64 + lane) * 8 + (kx & 7)] = (uint16_t)e;
+          }
+        }
+        if (hsub == 0 && bh % P.Hkv == 0 && lane == 0)
+          P.pos_fp[(bh / P.Hkv) * P.cap + P.n_fp - 1] = P.n_fp - 1 + P.n_q;
+      }
+
       floatx4 Du[2] = {floatx4{0.f, 0.f, 0.f, 0.f}, floatx4{0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
       for (int kc = 0; kc < NKC; ++kc) {
@@ -938,8 +982,12 @@ static hipError_t launch_mfma_t(const Shape& s, const AttnParams& P, dim3 grid, 
 }
 
 hipError_t launch_decode_attn_mfma(const Shape& s, const lq_cache& c, const void* q, float scale,
-                                   void* out, void* ws, const lq_plan& plan, hipStream_t st) {
+                                   void* out, void* ws, const lq_plan& plan, hipStream_t st,
+                                   const void* k_new, const void* v_new) {
   AttnParams P;
+  P.k_new = (const uint16_t*)k_new; P.v_new = (const uint16_t*)v_new;
+  P.k_fp_w = (uint16_t*)c.k_fp[c.cur]; P.v_fp_w = (uint16_t*)c.v_fp[c.cur];
+  P.pos_fp = c.pos_fp[c.cur]; P.Hkv = s.Hkv;
   P.q = (const uint16_t*)q;
   P.k_fp = (const uint16_t*)c.k_fp[c.cur];
   P.v_fp = (const uint16_t*)c.v_fp[c.cur];

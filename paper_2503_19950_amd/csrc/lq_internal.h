@@ -47,6 +47,9 @@ hipError_t launch_prefill(const Shape& s, const lq_cache& c, const void* k, cons
                           int n_fp, hipStream_t st);
 hipError_t launch_decode_attn(const Shape& s, const lq_cache& c, const void* q, float scale,
                               void* out, void* ws, const lq_plan& plan, hipStream_t st);
+hipError_t launch_decode_step(const Shape& s, const lq_cache& c, const void* k_new, const void* v_new,
+                              const void* q, float scale, void* out, void* ws, const lq_plan& plan,
+                              hipStream_t st);
 void plan_decode(const Shape& s, int n_fp, int n_q, lq_plan* plan);
 
 }  // namespace lq

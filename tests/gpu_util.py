@@ -114,15 +114,21 @@ def check_attention(dc, oc_by_slice, wl, q_np, scale=0.0, large_outputs=False):
     worst = 0.0
     for (b, h), oc in oc_by_slice.items():
         want = attention.decode_attention(oc, q_np[b, h * gh:(h + 1) * gh], scale if scale > 0 else None)
-        diff = np.abs(out[b, h * gh:(h + 1) * gh] - want)
-        worst = max(worst, float(diff.max()))
-        half_ulp = HALF_ULP[dt] * np.abs(want)
-        if not large_outputs:
-            half_ulp = np.where(half_ulp > TOL[dt] / 2, half_ulp, 0.0)
-        bad = diff > TOL[dt] + half_ulp
-        assert not bad.any(), "attention (b=%d,h=%d): abs err %.3e at |o| = %.3f, tolerance %.1e" % (
-            b, h, diff[bad].max(), np.abs(want)[bad].max(), TOL[dt])
+        worst = max(worst, assert_outputs_close(out[b, h * gh:(h + 1) * gh], want, dt,
+                                                "attention (b=%d,h=%d)" % (b, h), large_outputs))
     return worst
+
+
+def assert_outputs_close(got, want, dt, where, large_outputs=False):
+    """The output bound described in check_attention; returns the largest abs error."""
+    diff = np.abs(got - want)
+    half_ulp = HALF_ULP[dt] * np.abs(want)
+    if not large_outputs:
+        half_ulp = np.where(half_ulp > TOL[dt] / 2, half_ulp, 0.0)
+    bad = diff > TOL[dt] + half_ulp
+    assert not bad.any(), "%s: abs err %.3e at |o| = %.3f, tolerance %.1e" % (
+        where, diff[bad].max(), np.abs(want)[bad].max(), TOL[dt])
+    return float(diff.max())
 
 
 def batch_kv_sampled(seed_id, t0, t1, wl, distinct):

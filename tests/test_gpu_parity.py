@@ -103,3 +103,57 @@ def test_error_codes_with_live_device_buffers():
     dc.append(k[:, :, 88:120].contiguous(), v[:, :, 88:120].contiguous())
     assert dc.c.n_fp == 96
     assert B.logquant_compress(dc.cfg, dc.c) == B.LQ_ERR_CAPACITY       # quantized region is full
+
+
+@pytest.mark.parametrize("name,wl,L0,steps", [
+    ("gqa4_f16", U.make_wl(B=2, Hq=8, Hkv=2, d=128, G=32, F=64), 130, 40),          # crosses events (W = 32)
+    ("mha_d96_bf16", U.make_wl(B=2, Hq=4, Hkv=4, d=96, G=64, F=128, dtype="bf16"), 300, 20),
+    ("gqa8_two_head_groups", U.make_wl(B=1, Hq=8, Hkv=1, d=128, G=32, F=64), 5, 70),
+    ("from_empty_bits4", U.make_wl(B=1, Hq=4, Hkv=2, d=64, G=32, F=64, bits=4), 0, 40),
+])
+def test_fused_decode_step_equals_append_then_attend(name, wl, L0, steps):
+    """logquant_decode_step against logquant_append + logquant_decode_attn on a twin cache:
+    same outputs (to tolerance, and against the oracle) and bit-identical cache state
+    after every step; at the step that fills the window both use the separate calls."""
+    import torch
+    seed_id = 400 + len(name)
+    dt = wl["dtype"]
+    K, V = inputs.batch_kv(seed_id, 0, L0 + steps, wl)
+    Kd, Vd = U.to_dev(K, dt), U.to_dev(V, dt)
+    qcap = 64 * ((L0 + steps) // 64 + 2)
+    a, b = U.new_cache(wl, 0, q_capacity=qcap), U.new_cache(wl, 0, q_capacity=qcap)
+    if L0:
+        a.prefill(Kd[:, :, :L0].contiguous(), Vd[:, :, :L0].contiguous())
+        b.prefill(Kd[:, :, :L0].contiguous(), Vd[:, :, :L0].contiguous())
+    cap = 3 * (wl["F"] // 2)
+    ocs = {(bb, h): U.build_oracle(wl, seed_id, L0, bb, h) for bb in range(wl["B"]) for h in range(wl["Hkv"])}
+    gh = wl["Hq"] // wl["Hkv"]
+    for j in range(steps):
+        t = L0 + j
+        kn, vn = Kd[:, :, t:t + 1].contiguous(), Vd[:, :, t:t + 1].contiguous()
+        q_np = inputs.queries(seed_id, j, wl)
+        q = U.to_dev(q_np, dt)
+        b.append(kn, vn)
+        if b.c.n_fp == cap:
+            b.compress()
+        out_b = b.decode_attn(q)
+        if a.c.n_fp + 1 < cap:
+            out_a = a.decode_step(kn, vn, q)
+        else:
+            a.append(kn, vn)
+            a.compress()
+            out_a = a.decode_attn(q)
+        torch.cuda.synchronize()
+        assert a.counts() == b.counts()
+        assert (out_a.float() - out_b.float()).abs().max().item() <= 2 * U.HALF_ULP[dt] * max(1.0, out_b.float().abs().max().item())
+        for (bb, h), oc in ocs.items():
+            oc.append(K[bb, h, t], V[bb, h, t])
+        if j % 13 == 0 or j == steps - 1:
+            sa, sb = U.live_buffers(a, wl), U.live_buffers(b, wl)
+            for key in sa:
+                assert np.array_equal(sa[key], sb[key]), (key, j)
+            from oracle import attention
+            o = out_a.float().cpu().numpy()
+            for (bb, h), oc in ocs.items():
+                want = attention.decode_attention(oc, q_np[bb, h * gh:(h + 1) * gh], None)
+                U.assert_outputs_close(o[bb, h * gh:(h + 1) * gh], want, dt, "step %d (b=%d,h=%d)" % (j, bb, h))
