@@ -142,6 +142,44 @@ def test_plan_reports_the_algorithmic_bytes():
     assert B.logquant_decode_plan(_cfg(bits=4), 128, 384).bytes_read == 8 * (128 * 512 + 384 * (128 + 32))
 
 
+def test_decode_step_errors_without_a_gpu():
+    cfg = _cfg()                               # W = 64: capacity 192 fp rows
+    cache = B.lq_cache()
+    assert B.logquant_decode_step(cfg, cache, 4096, 4096, 4096, 0.0, 4096, 4096) == B.LQ_ERR_NULL
+    for name, _ in B.lq_cache._fields_[3:10]:
+        setattr(cache, name, 4096)
+    for i in range(2):
+        cache.k_fp[i] = cache.v_fp[i] = cache.pos_fp[i] = 4096
+    assert B.logquant_decode_step(cfg, cache, None, 4096, 4096, 0.0, 4096, 4096) == B.LQ_ERR_NULL
+    cache.n_fp = 191                           # the append would fill the window: separate calls needed
+    assert B.logquant_decode_step(cfg, cache, 4096, 4096, 4096, 0.0, 4096, 4096) == B.LQ_ERR_STATE
+    assert cache.n_fp == 191
+
+
+def test_launch_plans_of_the_five_workloads():
+    """Workgroup shape and split count the planner picks: every compute unit gets work,
+    the chip is filled in one round, and the fp share gets at least one wavefront."""
+    shapes = {
+        1: (dict(), 128, 384),
+        2: (dict(B=8, fp_budget=256, q_capacity=8192), 256, 7936),
+        3: (dict(fp_budget=512, group=64, dtype="bf16", q_capacity=131072), 512, 130560),
+        4: (dict(B=64, fp_budget=256, q_capacity=4352), 256, 3840),
+        5: (dict(B=16, Hq=32, Hkv=32, d=96, fp_budget=384, group=64, dtype="bf16", q_capacity=32256 + 384), 512, 32256),
+    }
+    for w, (kw, n_fp, n_q) in shapes.items():
+        p = B.logquant_decode_plan(_cfg(**kw), n_fp, n_q)
+        assert p.waves_per_block in (4, 8, 12) and p.splits >= 1 and 1 <= p.fp_waves < p.splits * p.waves_per_block
+        if w >= 2:
+            assert 256 <= p.blocks <= 512, (w, p.blocks)
+            assert p.blocks * p.waves_per_block <= 256 * 12
+    p3 = B.logquant_decode_plan(_cfg(**shapes[3][0]), 512, 130560)
+    assert (p3.waves_per_block, p3.splits) == (12, 32)
+    p4 = B.logquant_decode_plan(_cfg(**shapes[4][0]), 256, 3840)
+    assert (p4.waves_per_block, p4.splits) == (4, 1)
+    # 4-bit codes are not built for 12-wavefront workgroups
+    assert B.logquant_decode_plan(_cfg(bits=4, **shapes[3][0]), 512, 130560).waves_per_block == 8
+
+
 def test_status_strings():
     assert B.logquant_status_string(0) == "ok"
     assert "capacity" in B.logquant_status_string(B.LQ_ERR_CAPACITY)
