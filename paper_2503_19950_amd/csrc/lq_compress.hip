@@ -24,19 +24,44 @@ __device__ __forceinline__ void group_params(float mn, float mx, float* z, float
   *z = mn;
 }
 
-// round-half-up of (x - z)/s clamped to 0..2^BITS-1, by threshold compares on the
-// exact (fp64) difference; (k + 0.5) * s is exact in fp64.
+// Encoder of one group: round-half-up of (x - z)/s clamped to 0..2^BITS-1, by
+// threshold compares on the exact (fp64) difference; (k + 0.5) * s is exact in fp64.
+// The thresholds grow with k, so the number of them that x - z reaches is found by
+// bisection (BITS compares instead of 2^BITS - 1); with 2 bits the three thresholds
+// are formed once per group.
 template <int BITS>
-__device__ __forceinline__ uint32_t code_of(float x, float z, float s) {
-  const double dl = (double)x - (double)z;
-  const double sd = (double)s;
-  // the thresholds grow with k, so the number of them that dl reaches is found by
-  // bisection: BITS compares instead of 2^BITS - 1
-  uint32_t c = 0;
+struct Encoder {
+  double z, sd, t0, t1, t2;
+  bool flat;
+  __device__ __forceinline__ Encoder(float zf, float s) {
+    z = (double)zf; sd = (double)s; flat = s == 0.f;
+    t0 = 0.5 * sd; t1 = 1.5 * sd; t2 = 2.5 * sd;
+  }
+  __device__ __forceinline__ uint32_t operator()(float x) const {
+    const double dl = (double)x - z;
+    uint32_t c;
+    if constexpr (BITS == 2) {
+      const uint32_t hi = dl >= t1;
+      c = 2 * hi + (uint32_t)(dl >= (hi ? t2 : t0));
+    } else {
+      c = 0;
 #pragma unroll
-  for (int step = 1 << (BITS - 1); step >= 1; step >>= 1)
-    if (dl >= ((double)(c + step) - 0.5) * sd) c += step;
-  return s == 0.f ? 0u : c;
+      for (int step = 1 << (BITS - 1); step >= 1; step >>= 1)
+        if (dl >= ((double)(c + step) - 0.5) * sd) c += step;
+    }
+    return flat ? 0u : c;
+  }
+};
+
+// Eight codes (one byte each, in x: elements 0..3, y: elements 4..7) -> the operand
+// order of the packed layouts: element i at bit BITS*(i>>1) + 16*(i&1).
+template <int BITS>
+__device__ __forceinline__ uint32_t pack8(uint32_t x, uint32_t y) {
+  constexpr uint32_t M = (1u << BITS) - 1u;
+  uint32_t w = (x & M) | (((x >> 8) & M) << 16) | (((x >> 16) & M) << BITS) | (((x >> 24) & M) << (16 + BITS));
+  w |= ((y & M) << (2 * BITS)) | (((y >> 8) & M) << (16 + 2 * BITS)) | (((y >> 16) & M) << (3 * BITS)) |
+       (((y >> 24) & M) << (16 + 3 * BITS));
+  return w;
 }
 
 // Where the G rows of one key group come from.
@@ -97,17 +122,25 @@ struct PromptSource {
 };
 
 // Quantize one key group (G rows) of slice bh into quantized slots q0 .. q0+G-1.
-// 256 threads; sm: G * (d + 2) uint16 of LDS, red: 8 * 128 floats.
+// 256 threads.  LDS: sm = G * (d + 4) uint16 (the staged rows), cb = QG_CODE_BYTES
+// bytes (the codes, one byte each: keys [token][d + 4], values transposed
+// [channel][G + 4], so that the eight codes of a packed operand are two aligned
+// 32-bit reads), red = 8 * 128 floats.
+template <int d, int G>
+constexpr int QG_CODE_BYTES = (G * (d + 4) > d * (G + 4) ? G * (d + 4) : d * (G + 4));
+
 template <bool BF16, int d, int G, int BITS, class Src>
 __device__ __forceinline__ void quantize_group(
-    uint16_t* sm, float* red, const Src& src, int bh, int q0, uint32_t* __restrict__ k_codes,
+    uint16_t* sm, uint8_t* cb, float* red, const Src& src, int bh, int q0, uint32_t* __restrict__ k_codes,
     uint32_t* __restrict__ v_codes, uint16_t* __restrict__ k_scale, uint16_t* __restrict__ k_zero,
     uint16_t* __restrict__ v_scale, uint16_t* __restrict__ v_zero, int32_t* __restrict__ pos_q,
     int qcap, int Hkv) {
   const int tid = threadIdx.x;
-  constexpr int nkc = d >> 5, ngc = (d + G - 1) / G, ld = d + 2;
+  constexpr int nkc = d >> 5, ngc = (d + G - 1) / G, ld = d + 4;
   constexpr int WPL = nkc * (BITS / 2);   // code words per lane and 32-slot block
+  constexpr int KP = d + 4, VP = G + 4;   // byte pitches of the code arrays
   const int64_t code_base = ((int64_t)bh * (qcap >> 5) + (q0 >> 5)) * 64 * WPL;
+  const uint32_t* cw = reinterpret_cast<const uint32_t*>(cb);
 
   // ---------------- keys ----------------
   src.stage_keys(sm, ld);
@@ -115,9 +148,9 @@ __device__ __forceinline__ void quantize_group(
   // per channel: 256 / d threads each scan a share of the G tokens, exchange their
   // partial minima and maxima, and then encode their own share
   {
-    constexpr int parts = 256 / d, per = G / parts;
+    constexpr int parts = 256 / d, per = G / parts;   // d in {64, 96, 128}: parts in {4, 2, 2} divide G
     const int c = tid % d, part = tid / d;
-    const int e0 = part * per;   // d in {64, 96, 128}: parts in {4, 2, 2} divide G
+    const int e0 = part * per;
     float mn = INFINITY, mx = -INFINITY;
     if (part < parts) {
       for (int e = e0; e < e0 + per; ++e) {
@@ -142,32 +175,29 @@ __device__ __forceinline__ void quantize_group(
         k_scale[mi] = st;
         k_zero[mi] = zt;
       }
-      for (int e = e0; e < e0 + per; ++e) sm[e * ld + c] = (uint16_t)code_of<BITS>(t2f<BF16>(sm[e * ld + c]), z, sc);
+      const Encoder<BITS> enc(z, sc);
+      for (int e = e0; e < e0 + per; ++e) cb[e * KP + c] = (uint8_t)enc(t2f<BF16>(sm[e * ld + c]));
     }
   }
   __syncthreads();
+  // one word per (32-slot block, lane (qq, r), m): the operand(s) of token 16*uu + r,
+  // channels 32*kc + 8*qq .. +7
   for (int idx = tid; idx < (G >> 5) * 64 * WPL; idx += 256) {
     const int m = idx % WPL, lane = (idx / WPL) & 63, blk = idx / (WPL * 64);
     const int r = lane & 15, qq = lane >> 4;
-    uint32_t w = 0;
+    uint32_t w;
     if constexpr (BITS == 2) {
+      w = 0;
 #pragma unroll
-      for (int jj = 0; jj < 8; ++jj) {
-        const int o = 2 * m + (jj >> 2);
-        const int uu = o / nkc, kc = o % nkc;
-        const int e = blk * 32 + 16 * uu + r;
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-          const int c = 32 * kc + 8 * qq + 2 * (jj & 3) + half;
-          w |= (uint32_t)sm[e * ld + c] << (2 * jj + 16 * half);
-        }
+      for (int h = 0; h < 2; ++h) {
+        const int o = 2 * m + h, uu = o / nkc, kc = o % nkc;
+        const int at = ((blk * 32 + 16 * uu + r) * KP + 32 * kc + 8 * qq) >> 2;
+        w |= pack8<2>(cw[at], cw[at + 1]) << (8 * h);
       }
     } else {
-      const int uu = m / nkc, kc = m % nkc;   // one word per operand o = m
-      const int e = blk * 32 + 16 * uu + r;
-#pragma unroll
-      for (int i = 0; i < 8; ++i)
-        w |= (uint32_t)sm[e * ld + 32 * kc + 8 * qq + i] << (4 * (i >> 1) + 16 * (i & 1));
+      const int uu = m / nkc, kc = m % nkc;
+      const int at = ((blk * 32 + 16 * uu + r) * KP + 32 * kc + 8 * qq) >> 2;
+      w = pack8<4>(cw[at], cw[at + 1]);
     }
     k_codes[code_base + idx] = w;
   }
@@ -180,16 +210,20 @@ __device__ __forceinline__ void quantize_group(
   // shares of one group sit in neighbouring lanes and are combined by lane shuffles
   {
     constexpr int vp = 2 * G * ngc > 256 ? 1 : 4 * G * ngc > 256 ? 2 : 8 * G * ngc > 256 ? 4 : 8;
+    constexpr int PER = ((G < d ? G : d) + vp - 1) / vp;    // channels per thread in a full group
     for (int idx = tid; idx < G * ngc * vp; idx += 256) {   // a multiple of vp; all lanes of a group take the same trips
       const int part = idx % vp, e = (idx / vp) % G, gc = idx / (vp * G);
       const int lo = gc * G, hi = min(lo + G, d);
-      const int per = (hi - lo + vp - 1) / vp;
-      const int c0 = lo + part * per, c1 = min(c0 + per, hi);
+      const int per = (hi - lo + vp - 1) / vp;              // fewer in the ragged last group
+      const int c0 = lo + part * per, n = min(per, hi - c0);
+      const uint16_t* row = sm + e * ld + c0;
+      uint8_t* col = cb + c0 * VP + e;
       float mn = INFINITY, mx = -INFINITY;
-      for (int c = c0; c < c1; ++c) {
-        const float x = t2f<BF16>(sm[e * ld + c]);
-        mn = fminf(mn, x);
-        mx = fmaxf(mx, x);
+#pragma unroll
+      for (int i = 0; i < PER; ++i) {
+        const float x = t2f<BF16>(row[i < n ? i : 0]);
+        mn = fminf(mn, i < n ? x : mn);
+        mx = fmaxf(mx, i < n ? x : mx);
       }
       for (int o = 1; o < vp; o <<= 1) {
         mn = fminf(mn, __shfl_xor(mn, o));
@@ -203,31 +237,29 @@ __device__ __forceinline__ void quantize_group(
         v_scale[mi] = st;
         v_zero[mi] = zt;
       }
-      for (int c = c0; c < c1; ++c) sm[e * ld + c] = (uint16_t)code_of<BITS>(t2f<BF16>(sm[e * ld + c]), z, sc);
+      const Encoder<BITS> enc(z, sc);
+#pragma unroll
+      for (int i = 0; i < PER; ++i)
+        if (i < n) col[i * VP] = (uint8_t)enc(t2f<BF16>(row[i]));
     }
   }
   __syncthreads();
+  // one word per (32-slot block, lane (qq, n), m): the operand(s) of channel 16*nt + n,
+  // tokens kperm_inv(8*qq + i), i = 0..7: local slots 4*qq .. +3 and 16 + 4*qq .. +3
   for (int idx = tid; idx < (G >> 5) * 64 * WPL; idx += 256) {
     const int m = idx % WPL, lane = (idx / WPL) & 63, blk = idx / (WPL * 64);
     const int n = lane & 15, qq = lane >> 4;
-    uint32_t w = 0;
+    uint32_t w;
     if constexpr (BITS == 2) {
+      w = 0;
 #pragma unroll
-      for (int jj = 0; jj < 8; ++jj) {
-        const int nt = 2 * m + (jj >> 2);
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-          const int k = 8 * qq + 2 * (jj & 3) + half;
-          const int e = blk * 32 + kperm_inv(k);
-          w |= (uint32_t)sm[e * ld + 16 * nt + n] << (2 * jj + 16 * half);
-        }
+      for (int h = 0; h < 2; ++h) {
+        const int at = ((16 * (2 * m + h) + n) * VP + blk * 32 + 4 * qq) >> 2;
+        w |= pack8<2>(cw[at], cw[at + 4]) << (8 * h);
       }
     } else {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {            // one word per channel tile nt = m
-        const int e = blk * 32 + kperm_inv(8 * qq + i);
-        w |= (uint32_t)sm[e * ld + 16 * m + n] << (4 * (i >> 1) + 16 * (i & 1));
-      }
+      const int at = ((16 * m + n) * VP + blk * 32 + 4 * qq) >> 2;
+      w = pack8<4>(cw[at], cw[at + 4]);
     }
     v_codes[code_base + idx] = w;
   }
@@ -288,17 +320,18 @@ struct CompressParams {
 // One launch does both halves of the filtering branch; they read the same buffer and
 // write disjoint ones.  grid (W/G + 2W/32, B*Hkv), block 256: workgroups x < W/G
 // quantize one key group each, the others move 32 kept rows each.
-// Dynamic LDS: G * (d + 2) uint16.
+// Dynamic LDS: G * (d + 4) uint16.
 template <bool BF16, int D, int G, int BITS>
 __global__ void __launch_bounds__(256) compress_kernel(const CompressParams P) {
-  extern __shared__ uint16_t sm[];  // [G][d + 2]; values first, then their codes in place
+  extern __shared__ uint16_t sm[];  // [G][d + 4]: the staged rows
   __shared__ float red[8 * 128];    // partial minima [4][d] and maxima [4][d] of the key channels
+  __shared__ __attribute__((aligned(16))) uint8_t cb[QG_CODE_BYTES<D, G>];
   const int nq = P.W / G, bh = blockIdx.y;
   if ((int)blockIdx.x < nq) {
     const int j = blockIdx.x;
     const int64_t fp_slice = (int64_t)bh * P.cap * D;
     const FpSource<D, G> src{P.k_old + fp_slice, P.v_old + fp_slice, P.pos_old + (bh / P.Hkv) * P.cap, j};
-    quantize_group<BF16, D, G, BITS>(sm, red, src, bh, P.n_q + j * G, P.k_codes, P.v_codes, P.k_scale, P.k_zero,
+    quantize_group<BF16, D, G, BITS>(sm, cb, red, src, bh, P.n_q + j * G, P.k_codes, P.v_codes, P.k_scale, P.k_zero,
                                P.v_scale, P.v_zero, P.pos_q, P.qcap, P.Hkv);
   } else {
     compact_rows(blockIdx.x - nq, bh, P.k_old, P.v_old, P.pos_old, P.k_new, P.v_new, P.pos_new, P.d,
@@ -327,6 +360,7 @@ template <bool BF16, int D, int G, int BITS>
 __global__ void __launch_bounds__(256) prefill_kernel(const PrefillParams P) {
   extern __shared__ uint16_t sm[];
   __shared__ float red[8 * 128];
+  __shared__ __attribute__((aligned(16))) uint8_t cb[QG_CODE_BYTES<D, G>];
   __shared__ int posl[128];
   const int tid = threadIdx.x, bh = blockIdx.y;
   const int per_event = P.W / G, nqb = P.E * per_event;
@@ -336,7 +370,7 @@ __global__ void __launch_bounds__(256) prefill_kernel(const PrefillParams P) {
     if (tid < G) posl[tid] = evicted_position(ev, j * G + tid, P.W);
     __syncthreads();
     const PromptSource<D, G> src{P.k + prompt, P.v + prompt, posl};
-    quantize_group<BF16, D, G, BITS>(sm, red, src, bh, (ev - 1) * P.W + j * G, P.k_codes, P.v_codes, P.k_scale,
+    quantize_group<BF16, D, G, BITS>(sm, cb, red, src, bh, (ev - 1) * P.W + j * G, P.k_codes, P.v_codes, P.k_scale,
                                P.k_zero, P.v_scale, P.v_zero, P.pos_q, P.qcap, P.Hkv);
     return;
   }
@@ -422,7 +456,7 @@ hipError_t launch_compress(const Shape& s, const lq_cache& c, hipStream_t st) {
   P.v_scale = (uint16_t*)c.v_scale; P.v_zero = (uint16_t*)c.v_zero;
   P.pos_q = c.pos_q;
   P.d = s.d; P.G = s.G; P.W = s.W; P.cap = s.cap; P.qcap = s.qcap; P.n_q = c.n_q; P.Hkv = s.Hkv;
-  const size_t lds = (size_t)s.G * (s.d + 2) * sizeof(uint16_t);
+  const size_t lds = (size_t)s.G * (s.d + 4) * sizeof(uint16_t);
   dim3 grid(s.W / s.G + 2 * s.W / 32, s.B * s.Hkv);
   dispatch_dg<CompressLaunch>(s, grid, lds, st, P);
   return launch_status(__func__);
@@ -439,7 +473,7 @@ hipError_t launch_prefill(const Shape& s, const lq_cache& c, const void* k, cons
   P.pos_q = c.pos_q;
   P.d = s.d; P.G = s.G; P.W = s.W; P.cap = s.cap; P.qcap = s.qcap; P.Hkv = s.Hkv;
   P.L = L; P.E = E; P.n_fp = n_fp;
-  const size_t lds = (size_t)s.G * (s.d + 2) * sizeof(uint16_t);
+  const size_t lds = (size_t)s.G * (s.d + 4) * sizeof(uint16_t);
   dim3 grid(E * (s.W / s.G) + (n_fp + 31) / 32, s.B * s.Hkv);
   dispatch_dg<PrefillLaunch>(s, grid, lds, st, P);
   return launch_status(__func__);
