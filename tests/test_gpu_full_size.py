@@ -46,8 +46,24 @@ def test_workload_3_long_context_l131072():
     wl = dict(inputs.WORKLOADS[3])
     dc = U.build_gpu(wl, 3, wl["L"])
     assert (dc.c.n_fp, dc.c.n_q) == (512, 130560)
-    _check(dc, wl, 3, wl["L"], [(0, 0), (0, 6)])
+    ocs = _check(dc, wl, 3, wl["L"], [(0, 0), (0, 6)])
     _check_prefill(dc, wl, 3, wl["L"])
+    # one more token through the fused step the benchmark times (append + attention in one launch)
+    L = wl["L"]
+    K, V = inputs.batch_kv(3, L, L + 1, wl)
+    q = inputs.queries(3, 1, wl)
+    out = dc.decode_step(U.to_dev(K, "bf16"), U.to_dev(V, "bf16"), U.to_dev(q, "bf16"))
+    import torch
+    from oracle import attention
+    torch.cuda.synchronize()
+    out = out.float().cpu().numpy()
+    gh = wl["Hq"] // wl["Hkv"]
+    for (b, h), oc in ocs.items():
+        oc.append(K[b, h, 0], V[b, h, 0])
+        U.check_state(dc, oc, wl, b, h)
+        want = attention.decode_attention(oc, q[b, h * gh:(h + 1) * gh], None)
+        U.assert_outputs_close(out[b, h * gh:(h + 1) * gh], want, "bf16", "fused step (b=%d,h=%d)" % (b, h))
+    print("  fused decode step: state bit-exact, outputs within tolerance", flush=True)
 
 
 def test_workload_4_batch64_128_decode_steps():
