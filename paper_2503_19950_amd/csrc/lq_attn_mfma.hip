@@ -785,10 +785,15 @@ attn_mfma_kernel(const AttnParams P) {
       acc += a * o_lds[w][gg][c];
       L += a * ml_lds[w][gg][1];
     }
+    if (P.splits == 1) {   // nothing to merge across workgroups: this is the result
+      P.out[((int64_t)bh * P.gh + hsub * P.hb + gg) * D + c] = f2t<BF16>(acc / L);
+      continue;
+    }
     const int64_t base = part_base + gg * (D + 4);
     st_dev(P.ws + base + c, acc);
     if (c == 0) { st_dev(P.ws + base + D, M); st_dev(P.ws + base + D + 1, L); }
   }
+  if (P.splits == 1) return;
 
   // ---- ticket: the last workgroup of this (b, kv head, head group) merges the splits.
   // The barrier waits for this workgroup's stores to be acknowledged before thread 0
