@@ -348,7 +348,7 @@ attn_mfma_kernel(const AttnParams P) {
   constexpr int QS_ROW = D + 8;
   static_assert((QS_ROW * 2 / 16) % 2 == 1, "q*s row pitch");
   __shared__ __attribute__((aligned(16))) uint16_t qs_lds[NWB][NGRP][9][QS_ROW];   // rows 4*piece+head, row 8 = zeros
-  __shared__ __attribute__((aligned(16))) uint16_t p_lds[NWB][2][5][32];            // [wave][32-token step][head, 4 = zeros][token]
+  __shared__ __attribute__((aligned(16))) uint16_t p_lds[NWB][2][9][32];            // [wave][32-token step][row][token]: rows 0-3 p of head, 4 zeros, 5-8 p's fp16 rounding residual
   __shared__ float o_lds[NWB][4][D];
   __shared__ float ml_lds[NWB][4][2];
   __shared__ float zs_lds[NWB][4][4];
@@ -393,7 +393,15 @@ attn_mfma_kernel(const AttnParams P) {
     const char* kzb = (const char*)(P.k_zero + (int64_t)bh * (P.qcap / G) * D);
     const char* vsb = (const char*)(P.v_scale + (int64_t)bh * (P.qcap >> 5) * NGC * 32);
     const char* vzb = (const char*)(P.v_zero + (int64_t)bh * (P.qcap >> 5) * NGC * 32);
-    const int upc = up < NGC ? up : 0;
+    // Rows of the probability operand of the output step: row 4*up + g.  With at most
+    // two channel groups there are rows to spare, and the probabilities enter in two
+    // pieces: p rounded to fp16, and the residual of that rounding (rows up = piece *
+    // NGC + channel group), so that only the rounding of the product p * vs remains.
+    // With three or four groups there is one piece (up = channel group).
+    constexpr int VPIECES = NGC <= 2 ? 2 : 1;
+    const bool row_live = up < VPIECES * NGC;
+    const int upc = row_live ? up % NGC : 0;          // channel group of this lane's row
+    const bool tail_row = VPIECES == 2 && up >= NGC;  // this lane feeds the residual piece
     const uint32_t code_off = lane * WPL * 4;                 // byte offsets of this lane
     const uint32_t vm_off = (upc * 32 + 8 * q4) * 2;
     // Lane roles.  Logits and softmax: lane row q4 is query head q4, lane column n16
@@ -415,24 +423,55 @@ attn_mfma_kernel(const AttnParams P) {
     // key codes after the logits, value codes and scales after each output step), so
     // only one tile's worth of registers is live and every piece still has most of a
     // tile's processing time to arrive.
+    // The tile loads are buffer loads: one descriptor per array over this slice, the
+    // lane's offset in a register, the tile's offset in a scalar register, so that the
+    // per-tile address arithmetic runs on the scalar unit (and a load past the slice
+    // would return zeros instead of faulting).
+    const uint32_t code_bytes = (uint32_t)(P.qcap >> 5) * 64 * WPL * 4;
+    const auto rs_kc = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(kcb), 0, code_bytes, 0x00020000);
+    const auto rs_vc = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(vcb), 0, code_bytes, 0x00020000);
+    const uint32_t kmeta_bytes = (uint32_t)(P.qcap / G) * D * 2, vmeta_bytes = (uint32_t)(P.qcap >> 5) * NGC * 32 * 2;
+    const auto rs_ks = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(ksb), 0, kmeta_bytes, 0x00020000);
+    const auto rs_kz = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(kzb), 0, kmeta_bytes, 0x00020000);
+    const auto rs_vs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(vsb), 0, vmeta_bytes, 0x00020000);
+    const auto rs_vz = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(vzb), 0, vmeta_bytes, 0x00020000);
+    auto load16 = [&](__amdgpu_buffer_rsrc_t rs, uint32_t voff, uint32_t soff) {
+      const auto v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)voff, (int)soff, 0);
+      return make_uint4(v[0], v[1], v[2], v[3]);
+    };
+    auto load_words = [&](__amdgpu_buffer_rsrc_t rs, uint32_t voff, uint32_t soff) {
+      Words<WPL> r;
+#pragma unroll
+      for (int i = 0; i + 4 <= WPL; i += 4) {
+        const auto v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)voff + 4 * i, (int)soff, 0);
+        r.w[i] = v[0]; r.w[i + 1] = v[1]; r.w[i + 2] = v[2]; r.w[i + 3] = v[3];
+      }
+      if constexpr (WPL % 4 == 3) {
+        const auto v = __builtin_amdgcn_raw_buffer_load_b96(rs, (int)voff + 4 * (WPL - 3), (int)soff, 0);
+        r.w[WPL - 3] = v[0]; r.w[WPL - 2] = v[1]; r.w[WPL - 1] = v[2];
+      } else if constexpr (WPL % 4 == 2) {
+        const auto v = __builtin_amdgcn_raw_buffer_load_b64(rs, (int)voff + 4 * (WPL - 2), (int)soff, 0);
+        r.w[WPL - 2] = v[0]; r.w[WPL - 1] = v[1];
+      }
+      return r;
+    };
     auto load_kmeta = [&](Tile& T, int t) {
 #pragma unroll
       for (int e = 0; e < NGRP; ++e) {
         const int grp = G <= 64 ? t * NGRP + e : t / (G / 64);
-        T.ks8[e] = *reinterpret_cast<const uint4*>(ksb + (int64_t)grp * (D * 2) + km_off);
-        T.kz8[e] = *reinterpret_cast<const uint4*>(kzb + (int64_t)grp * (D * 2) + km_off);
+        T.ks8[e] = load16(rs_ks, km_off, (uint32_t)grp * (D * 2));
+        T.kz8[e] = load16(rs_kz, km_off, (uint32_t)grp * (D * 2));
       }
     };
     auto load_kcodes = [&](Tile& T, int t) {
-      const char* kcp = kcb + (int64_t)t * (2 * 64 * WPL * 4);
 #pragma unroll
       for (int b2 = 0; b2 < 2; ++b2)
-        T.kc[b2] = *reinterpret_cast<const Words<WPL>*>(kcp + b2 * (64 * WPL * 4) + code_off);
+        T.kc[b2] = load_words(rs_kc, code_off, (uint32_t)t * (2 * 64 * WPL * 4) + b2 * (64 * WPL * 4));
     };
     auto load_v = [&](Tile& T, int t, int b2) {
-      T.vc[b2] = *reinterpret_cast<const Words<WPL>*>(vcb + (int64_t)t * (2 * 64 * WPL * 4) + b2 * (64 * WPL * 4) + code_off);
-      T.vs[b2] = *reinterpret_cast<const uint4*>(vsb + (int64_t)t * (2 * NGC * 32 * 2) + b2 * (NGC * 32 * 2) + vm_off);
-      T.vz[b2] = *reinterpret_cast<const uint4*>(vzb + (int64_t)t * (2 * NGC * 32 * 2) + b2 * (NGC * 32 * 2) + vm_off);
+      T.vc[b2] = load_words(rs_vc, code_off, (uint32_t)t * (2 * 64 * WPL * 4) + b2 * (64 * WPL * 4));
+      T.vs[b2] = load16(rs_vs, vm_off, (uint32_t)t * (2 * NGC * 32 * 2) + b2 * (NGC * 32 * 2));
+      T.vz[b2] = load16(rs_vz, vm_off, (uint32_t)t * (2 * NGC * 32 * 2) + b2 * (NGC * 32 * 2));
     };
 
     // Tile schedule.  The first two tiles of a wavefront are fixed (wq, wq + NWQ) and
@@ -504,7 +543,7 @@ attn_mfma_kernel(const AttnParams P) {
     uint16_t* qs_wr = &qs_lds[wave][0][q4][8 * c8];
     // probabilities: written per (head q4, token), read per (head g, token octet q4);
     // lanes of absent channel groups read the zero row
-    const uint16_t* p_rd = &p_lds[wave][0][up < NGC ? g : 4][4 * q4];
+    const uint16_t* p_rd = &p_lds[wave][0][!row_live ? 4 : tail_row ? 5 + g : g][4 * q4];
     uint16_t* p_wr = &p_lds[wave][0][q4][n16];
     {
       for (int e = 0; e < NGRP; ++e)
@@ -578,14 +617,19 @@ attn_mfma_kernel(const AttnParams P) {
 
       // ---- hand the probabilities (fp16) to the lanes that feed the output step
 #pragma unroll
-      for (int u = 0; u < 4; ++u) p_wr[(u >> 1) * (5 * 32) + 16 * (u & 1)] = __builtin_bit_cast(uint16_t, (_Float16)p[u]);
+      for (int u = 0; u < 4; ++u) {
+        const _Float16 ph16 = (_Float16)p[u];
+        p_wr[(u >> 1) * (9 * 32) + 16 * (u & 1)] = __builtin_bit_cast(uint16_t, ph16);
+        if constexpr (VPIECES == 2)   // what the rounding to fp16 dropped, for the residual rows
+          p_wr[(u >> 1) * (9 * 32) + 16 * (u & 1) + 5 * 32] = __builtin_bit_cast(uint16_t, (_Float16)(p[u] - (float)ph16));
+      }
       wave_lds_sync();
 
       // ---- output: two 32-token steps x NNT channel tiles
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks) {
-        const uint2 pa = *reinterpret_cast<const uint2*>(p_rd + ks * (5 * 32));        // tokens 4*q4 .. +3
-        const uint2 pb = *reinterpret_cast<const uint2*>(p_rd + ks * (5 * 32) + 16);   // tokens 16 + 4*q4 .. +3
+        const uint2 pa = *reinterpret_cast<const uint2*>(p_rd + ks * (9 * 32));        // tokens 4*q4 .. +3
+        const uint2 pb = *reinterpret_cast<const uint2*>(p_rd + ks * (9 * 32) + 16);   // tokens 16 + 4*q4 .. +3
         const uint32_t ph[4] = {pa.x, pa.y, pb.x, pb.y};      // slots (0,1) (2,3) (4,5) (6,7)
         uint4 vsr = cur.vs[ks], vzr = cur.vz[ks];
         if (partial) {   // slots beyond n_q hold unspecified bits: keep them out of the sums
@@ -640,16 +684,30 @@ attn_mfma_kernel(const AttnParams P) {
       for (int v = 0; v < 4; ++v) zs += st.zacc[v] * __builtin_ldexpf(1.f, -pos_exp<BITS>(v));
     }
     zs = rows_sum(zs);
-    if (q4 == 0) zs_lds[wave][up][g] = zs;
+    if (q4 == 0) zs_lds[wave][up][g] = zs;       // the residual rows hold the residual's share of sum_t p_t vz_t
     if (n16 == 0) { ml_lds[wave][q4][0] = st.m; ml_lds[wave][q4][1] = l_tot; }
     wave_lds_sync();
+    // the accumulators of lane group q4 are the rows of channel group q4 (and of its
+    // residual piece, q4 + NGC): sum_t p_t vz_t of that group, both pieces, per head
+    const int gq = q4 < NGC ? q4 : 0;
+    float zsv[4];
+#pragma unroll
+    for (int gg = 0; gg < 4; ++gg) {
+      zsv[gg] = zs_lds[wave][gq][gg];
+      if constexpr (VPIECES == 2) zsv[gg] += zs_lds[wave][gq + NGC][gg];
+    }
 #pragma unroll
     for (int nt = 0; nt < NNT; ++nt) {
       const int gc = (16 * nt) / G;
-      if (q4 == gc) {
 #pragma unroll
-        for (int gg = 0; gg < 4; ++gg)
-          o_lds[wave][gg][16 * nt + n16] = st.acc[nt][gg] * CODE_SCALE<BITS> + zs_lds[wave][gc][gg];
+      for (int gg = 0; gg < 4; ++gg) {
+        float a = st.acc[nt][gg];
+        if constexpr (VPIECES == 2) {   // add the residual piece's row: lane group q4 + NGC
+          float x, y;
+          if constexpr (NGC == 2) xor32_pair(a, &x, &y); else xor16_pair(a, &x, &y);
+          a = x + y;
+        }
+        if (q4 == gc) o_lds[wave][gg][16 * nt + n16] = a * CODE_SCALE<BITS> + zsv[gg];
       }
     }
   } else {

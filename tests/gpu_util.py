@@ -168,13 +168,19 @@ def build_gpu_sampled(wl, seed_id, L, distinct, q_capacity=None):
     return dc
 
 
+def q_capacity_for(wl, L):
+    """A valid q_capacity (multiple of W and of 64) with room for L tokens."""
+    W = wl["F"] // 2
+    q_capacity = max(64, -(-L // (2 * W)) * 2 * W)
+    while q_capacity % 64 or q_capacity % W:
+        q_capacity += W
+    return q_capacity
+
+
 def new_cache(wl, L, q_capacity=None, poison=False):
     from paper_2503_19950_amd import binding
-    W = wl["F"] // 2
     if q_capacity is None:
-        q_capacity = max(64, -(-L // (2 * W)) * 2 * W)
-        while q_capacity % 64 or q_capacity % W:
-            q_capacity += W
+        q_capacity = q_capacity_for(wl, L)
     cfg = binding.make_config(wl["B"], wl["Hq"], wl["Hkv"], wl["d"], wl["F"], wl["G"], wl["dtype"],
                               q_capacity, wl.get("bits", 2))
     return binding.DeviceCache(cfg, poison=poison)
