@@ -16,11 +16,14 @@ cache      : streaming cache state for one (batch, kv-head) slice: Alg. 1 on
              rows of K/V, evicted rows quantized once (Fig. 6 caption, Sec. 2.3).
 attention  : Eq. 2 with the 1/sqrt(d) of Eq. 6 over [fp rows || dequantized rows]
              (Sec. 2.4: order of rows is irrelevant, Eq. 3).
+diagnostics: L1 distance between the exact attention distribution and the one seen
+             after quantizing or evicting the tokens a selection rule does not keep
+             (synthetic analogue of Table 2, Sec. 2.3).
 layout     : the physical index functions documented in include/logquant.h,
              re-implemented independently so packed words can be compared
              bit for bit.
 
-Parity status: selection, quantizer, attention and layout are pinned by
+Parity status: selection, quantizer, attention, diagnostics and layout are pinned by
 tests/test_oracle_*.py against hand traces of Algorithm 1, closed forms,
 brute force, exact rational arithmetic, textbook softmax attention and
 permutation invariance.  Accuracy-level behaviour (the paper's Tables 1-4,

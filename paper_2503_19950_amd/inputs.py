@@ -121,3 +121,47 @@ def queries(cfg_id, step=0, wl=None):
     wl = wl or WORKLOADS[cfg_id]
     x = _draw(_rng(cfg_id, T_Q, step), (wl["B"], wl["Hq"], wl["d"]), "normal")
     return to_T(x, wl["dtype"])
+
+
+# ---------------------------------------------------------------------------
+# Spiky variant of a slice, for the attention-error diagnostic (the paper's Sec. 2.2
+# observes that the positions which attract attention thin out with their distance
+# from the newest token roughly like 1/distance; Table 2 measures what that means for
+# quantizing or evicting the other tokens).  A fixed unit direction per kv head is
+# added to the key rows of `n_spikes` positions whose distance from the newest token
+# is log-uniform, and to every query, so those positions carry most of the attention
+# mass.  Pure data generation: nothing of the method is computed here.
+T_TOPIC, T_SPIKES = 5, 6
+
+
+def topic_direction(cfg_id, h, d):
+    u = _rng(cfg_id, h, T_TOPIC).standard_normal(d)
+    return (u / np.linalg.norm(u)).astype(np.float32)
+
+
+def spike_positions(cfg_id, b, h, L, n_spikes):
+    """Distinct positions in [0, L): distance to position L-1 is floor(L**U), U uniform."""
+    u = _rng(cfg_id, b, h, T_SPIKES).random(4 * n_spikes)
+    dist = np.floor(np.exp(u * np.log(L))).astype(np.int64)
+    pos = np.unique(np.clip(L - 1 - dist, 0, L - 1))
+    return pos[-n_spikes:] if pos.size > n_spikes else pos
+
+
+def slice_kv_spiky(cfg_id, b, h, L, wl=None, n_spikes=48, gain=12.0):
+    """slice_kv(…, 0, L) with the topic direction added to the spike rows of K."""
+    wl = wl or WORKLOADS[cfg_id]
+    K, V = slice_kv(cfg_id, b, h, 0, L, wl)
+    pos = spike_positions(cfg_id, b, h, L, n_spikes)
+    K = K.copy()
+    K[pos] += gain * topic_direction(cfg_id, h, wl["d"])
+    return to_T(K, wl["dtype"]), V, pos
+
+
+def queries_spiky(cfg_id, step=0, wl=None, gain=12.0):
+    """queries(…) with each head's query shifted along its kv head's topic direction."""
+    wl = wl or WORKLOADS[cfg_id]
+    q = queries(cfg_id, step, wl).copy()
+    gh = wl["Hq"] // wl["Hkv"]
+    for h in range(wl["Hkv"]):
+        q[:, h * gh:(h + 1) * gh] += gain * topic_direction(cfg_id, h, wl["d"])
+    return to_T(q, wl["dtype"])
