@@ -29,12 +29,29 @@ def parse():
     ap.add_argument("--copies", type=int, default=0, help="cache copies to rotate over (0 = auto)")
     ap.add_argument("--bits", type=int, default=2, choices=(2, 4),
                     help="code width; 2 is BASELINE.json's setting, 4 the paper's higher-precision variant")
+    ap.add_argument("--fp-budget", type=int, default=0,
+                    help="override the workload's fp budget F = 2W (e.g. 84 or 170: the paper's W = floor(R/3), "
+                         "R = 128 / 256, which the group size does not divide)")
     ap.add_argument("--unfused", action="store_true",
                     help="time the step as separate append and attention launches instead of logquant_decode_step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 256 MiB device copy a few times (reference for HBM counters)")
     return ap.parse_args()
+
+
+def slots_per_event(wl):
+    """Quantized slots one filtering event takes: W rounded up to whole key groups."""
+    W, G = wl["F"] // 2, wl["G"]
+    return -(-W // G) * G
+
+
+def q_capacity(wl):
+    Wq = slots_per_event(wl)
+    qcap = (wl["L"] // (wl["F"] // 2) + 4) * Wq
+    while qcap % 64:
+        qcap += Wq
+    return qcap
 
 
 def build_states(wl, cfg_id, copies):
@@ -47,9 +64,7 @@ def build_states(wl, cfg_id, copies):
     from paper_2503_19950_amd import binding, inputs
     from tests.gpu_util import to_dev
     W, L, dt = wl["F"] // 2, wl["L"], wl["dtype"]
-    qcap = (L // W + 4) * W
-    while qcap % 64:
-        qcap += W
+    qcap = q_capacity(wl)
     cfg = binding.make_config(wl["B"], wl["Hq"], wl["Hkv"], wl["d"], wl["F"], wl["G"], dt, qcap,
                               wl.get("bits", 2))
     tdt = torch.bfloat16 if dt == "bf16" else torch.float16
@@ -74,10 +89,11 @@ def build_states(wl, cfg_id, copies):
         ev[2 * i + 1].record(stream)
     torch.cuda.synchronize()
     ms = sorted(ev[2 * i].elapsed_time(ev[2 * i + 1]) for i in range(1, 4))[1]
-    n_q = dc.c.n_q
+    n_q = dc.c.n_q                                # slots; of every Wq slots W hold tokens
+    n_tok = n_q // slots_per_event(wl) * W
     sizes = binding.logquant_sizes(cfg)
     bh = wl["B"] * wl["Hkv"]
-    written = bh * (n_q * (wl["d"] * wl.get("bits", 2) // 4 + 4 * -(-wl["d"] // wl["G"])) + n_q // wl["G"] * 4 * wl["d"]
+    written = bh * (n_tok * (wl["d"] * wl.get("bits", 2) // 4 + 4 * -(-wl["d"] // wl["G"])) + n_q // wl["G"] * 4 * wl["d"]
                     + dc.c.n_fp * 4 * wl["d"])
     read = 2 * Kd.numel() * 2
     prefill = {"ms_per_call": ms, "tokens_per_s": wl["B"] * L / (ms * 1e-3),
@@ -103,14 +119,16 @@ def main():
     wl["bits"] = a.bits
     if a.bits != 2:
         wl["name"] += "_bits%d" % a.bits
+    if a.fp_budget:
+        wl["F"] = a.fp_budget
+        wl["name"] += "_F%d" % a.fp_budget
     W, L, dt = wl["F"] // 2, wl["L"], wl["dtype"]
     steps = a.steps or W
     plan0 = None
     # enough copies that the rotation's footprint is >= 1 GiB (4x the 256 MB last-level cache)
     cfg_probe = binding.make_config(wl["B"], wl["Hq"], wl["Hkv"], wl["d"], wl["F"], wl["G"], dt,
-                                    (L // W + 4) * W if ((L // W + 4) * W) % 64 == 0 else (L // W + 5) * W,
-                                    a.bits)
-    plan0 = binding.logquant_decode_plan(cfg_probe, 2 * W, (L - 2 * W) // W * W)
+                                    q_capacity(wl), a.bits)
+    plan0 = binding.logquant_decode_plan(cfg_probe, 2 * W, (L - 2 * W) // W * slots_per_event(wl))
     copies = a.copies or max(2, min(16, -(-(1 << 30) // max(1, plan0.bytes_read))))
     t_build = time.time()
     cfg, caches, prefill = build_states(wl, a.workload, copies)

@@ -25,7 +25,8 @@
  * 64-lane matrix instructions consume it; a lane then reads its operand with
  * one contiguous 16-byte load.  With
  *     bh    = b * Hkv + h                     (batch row b, kv head h)
- *     NKC   = d / 32,  NNT = d / 16,  NGC = ceil(d / G),  CAP = 3W = 3*fp_budget/2
+ *     NKC   = d / 32,  NNT = d / 16,  NGC = ceil(d / G),  W = fp_budget/2,
+ *     CAP   = 3W rounded up to a multiple of 32,  WQ = ceil(W / G) * G
  *     kperm(x) = 8*((x % 16) / 4) + 4*(x / 16) + (x % 4)          for 0 <= x < 32
  * the element (slot t, channel c) of one (b, h) slice lives at:
  *
@@ -50,8 +51,14 @@
  *   pos_q       i32   index b*q_capacity + t              absolute position of quantized slot t
  *
  * Slots 0..n_fp-1 of the fp region are in the logical order of Algorithm 1's
- * list; slots 0..n_q-1 of the quantized region are in eviction order.  Content
- * of slots beyond the counts is unspecified and never influences a result.
+ * list.  The quantized region is filled in eviction order, WQ slots per filtering
+ * event: the i-th row an event removes (0 <= i < W) goes to slot (n_q before the
+ * event) + i.  When G divides W (WQ == W) every slot below n_q holds a token.
+ * Otherwise (e.g. the paper's W = floor(R/3), R = 128 or 256, with G = 64; Sec. 3.1,
+ * appendix D) the last key group of an event is short and the WQ - W slots behind it
+ * are padding: zero codes, zero value scales and zero-points, pos_q = -1; attention
+ * gives them no weight.  Content of slots beyond the counts is unspecified and
+ * never influences a result.
  *
  * Quantizer (one group of values x_i of type T, n = 2^bits - 1 steps; a reading, the
  * paper prints no formula): zero z = min x_i (with -0 stored as +0); scale
@@ -60,7 +67,8 @@
  * with the subtraction exact (fp64), all 0 when s == 0; dequantized value
  * z + code_i * s.  bits = 2 is the paper's main setting (INT2, Sec. 3.1), bits = 4 its
  * higher-precision variant (Sec. 3.2.1, Table 3).  Key groups: one channel, G consecutive
- * quantized slots (G tokens evicted together).  Value groups: one slot, G
+ * quantized slots (G tokens evicted together), the last group of a filtering event
+ * shorter (W mod G tokens) when G does not divide W.  Value groups: one slot, G
  * consecutive channels, the last group shorter when G does not divide d.
  */
 #ifndef LOGQUANT_H
@@ -78,7 +86,7 @@ typedef enum {
   LQ_ERR_NULL = 1,        /* a required pointer is null                              */
   LQ_ERR_SHAPE = 2,       /* inconsistent B/Hq/Hkv/d/fp_budget/group/q_capacity       */
   LQ_ERR_UNSUPPORTED = 3, /* valid in the paper but not built: bits not 2 or 4, G not in
-                             {32,64,128}, G not dividing W, d not in {64,96,128}      */
+                             {32,64,128}, d not in {64,96,128}                        */
   LQ_ERR_CAPACITY = 4,    /* fp region or quantized region would overflow             */
   LQ_ERR_STATE = 5,       /* call not allowed in the cache's current state            */
   LQ_ERR_HIP = 6          /* the HIP runtime reported a launch error                  */
@@ -93,10 +101,10 @@ typedef struct {
   int32_t Hkv;         /* kv heads, Hq % Hkv == 0                                      */
   int32_t d;           /* head dimension, one of 64, 96, 128                           */
   int32_t fp_budget;   /* F = 2W: fp tokens left after a compress; fp capacity is 3W   */
-  int32_t group;       /* G: quantization group size, 32/64/128, must divide W         */
+  int32_t group;       /* G: quantization group size, 32/64/128                        */
   int32_t bits;        /* 2 or 4                                                       */
   int32_t dtype;       /* lq_dtype                                                     */
-  int32_t q_capacity;  /* max quantized slots per sequence; multiple of W and of 64    */
+  int32_t q_capacity;  /* max quantized slots per sequence; multiple of WQ and of 64   */
 } lq_config;
 
 /* Cache state (HOST struct, DEVICE buffers; layouts above). */
@@ -109,7 +117,7 @@ typedef struct {
   int32_t  *pos_q;
   int32_t   cur;         /* which fp buffer is live (0 or 1)                           */
   int32_t   n_fp;        /* tokens in the fp region, 0..3W                             */
-  int32_t   n_q;         /* slots in the quantized region, multiple of W               */
+  int32_t   n_q;         /* slots in the quantized region, multiple of WQ              */
 } lq_cache;
 
 /* Byte sizes of every buffer of lq_cache for a given config (HOST out). */
@@ -136,8 +144,8 @@ lq_status logquant_workspace_init(const lq_config *cfg, void *workspace, void *s
 
 /* Algorithm 1, the append branch: store n_new new tokens per sequence in fp
  * slots n_fp .. n_fp+n_new-1 and record their absolute positions
- * n_fp+n_q .. (every token ever appended is either in the fp region or in the
- * quantized region, so that sum is the next position).
+ * n_fp + (n_q/WQ)*W .. (every token ever appended is either in the fp region or in
+ * the quantized region, so the number of tokens held is the next position).
  *   k_new, v_new : DEVICE [B][Hkv][n_new][d] T, row-major.
  * Requires n_fp + n_new <= 3W (else LQ_ERR_CAPACITY).  On success n_fp += n_new.
  * The caller runs logquant_compress when n_fp reaches 3W. */
@@ -146,13 +154,13 @@ lq_status logquant_append(const lq_config *cfg, lq_cache *cache, const void *k_n
 
 /* Algorithm 1, the filtering branch, plus the quantization of what it removes
  * (Fig. 6 caption; Sec. 2.3).  Requires n_fp == 3W (else LQ_ERR_STATE) and
- * n_q + W <= q_capacity (else LQ_ERR_CAPACITY).  For every sequence and kv head:
+ * n_q + WQ <= q_capacity (else LQ_ERR_CAPACITY).  For every sequence and kv head:
  *   - logical fp rows 1,3,..,2W-1 are quantized with the quantizer above and
  *     appended, in that order, as quantized slots n_q .. n_q+W-1 (codes, scales,
- *     zero-points, positions);
+ *     zero-points, positions); slots n_q+W .. n_q+WQ-1 become padding;
  *   - logical rows 0,2,..,2W-2 followed by rows 2W..3W-1 become rows 0..2W-1 of
  *     the other fp buffer, which becomes the live one (cache->cur flips).
- * On success n_fp = 2W, n_q += W.  `workspace` is not used at present and may
+ * On success n_fp = 2W, n_q += WQ.  `workspace` is not used at present and may
  * be null. */
 lq_status logquant_compress(const lq_config *cfg, lq_cache *cache, void *workspace,
                             void *stream);
@@ -166,8 +174,8 @@ lq_status logquant_compress(const lq_config *cfg, lq_cache *cache, void *workspa
  * slots.
  *   k, v : DEVICE [B][Hkv][L][d] T, row-major (as for logquant_append with n_new = L).
  * Requires an empty cache (n_fp == n_q == 0, else LQ_ERR_STATE), L >= 1 (else
- * LQ_ERR_SHAPE) and E*W <= q_capacity for the E = 0 (L < 3W) or floor((L-3W)/W)+1
- * events (else LQ_ERR_CAPACITY).  On success n_q = E*W, n_fp = L - E*W, and the live fp
+ * LQ_ERR_SHAPE) and E*WQ <= q_capacity for the E = 0 (L < 3W) or floor((L-3W)/W)+1
+ * events (else LQ_ERR_CAPACITY).  On success n_q = E*WQ, n_fp = L - E*W, and the live fp
  * buffer is unchanged (cache->cur). */
 lq_status logquant_prefill(const lq_config *cfg, lq_cache *cache, const void *k, const void *v,
                            int32_t L, void *stream);
@@ -184,7 +192,8 @@ lq_status logquant_prefill_positions(int32_t W, int32_t L, int32_t *pos_fp, int3
 
 /* Decode attention, Eq. 2 with Eq. 6's scaling, over the whole cache:
  *   out[b][h] = softmax_t( scale * q[b][h] . k_t ) applied to v_t,
- * t running over the n_fp original-precision rows and the n_q dequantized rows
+ * t running over the n_fp original-precision rows and the dequantized rows of the
+ * n_q quantized slots (padding slots excluded)
  * of kv head h / (Hq/Hkv); one softmax over both regions (Sec. 2.4).  The 2-bit
  * rows are dequantized in registers, never in memory.
  *   q   : DEVICE [B][Hq][d] T          out : DEVICE [B][Hq][d] T

@@ -22,7 +22,7 @@ class SliceCache:
         ngc = -(-d // G)
         self.pos_q = []
         # quantized region, one chunk per compress event (joined on demand):
-        # K_codes/V_codes [n_q][d] uint8, K_scale/K_zero [n_q/G][d],
+        # K_codes/V_codes [n_q][d] uint8, K_scale/K_zero [events * ceil(W/G)][d],
         # V_scale/V_zero [n_q][ceil(d/G)]
         self._chunks = {"K_codes": [np.zeros((0, d), np.uint8)],
                         "V_codes": [np.zeros((0, d), np.uint8)],
@@ -98,7 +98,7 @@ class SliceCache:
 
     def rows_fp64(self):
         """All rows the decode step attends over: fp rows, then dequantized rows."""
-        Kq = quantizer.dequantize_keys(self.K_codes, self.K_scale, self.K_zero, self.G)
+        Kq = quantizer.dequantize_keys(self.K_codes, self.K_scale, self.K_zero, self.G, self.W)
         Vq = quantizer.dequantize_values(self.V_codes, self.V_scale, self.V_zero, self.G)
         K = np.concatenate([self.K_fp.astype(np.float64), Kq], 0)
         V = np.concatenate([self.V_fp.astype(np.float64), Vq], 0)

@@ -52,9 +52,10 @@ def log_quant_keys(K, W, G, dtype, bits=2):
     K = np.asarray(K, np.float32)
     A, Q = selection.stream_eager(K.shape[0], W)
     K_hat = K.astype(np.float64).copy()
-    if Q:
-        codes, s, z = quantizer.quantize_keys(K[Q], G, dtype, bits)   # eviction order; W % G == 0
-        K_hat[Q] = quantizer.dequantize_keys(codes, s, z, G)
+    for e in range(len(Q) // W):                    # one filtering event at a time, eviction order
+        ev = Q[e * W:(e + 1) * W]
+        codes, s, z = quantizer.quantize_keys(K[ev], G, dtype, bits)
+        K_hat[ev] = quantizer.dequantize_keys(codes, s, z, G)
     return K_hat, A
 
 

@@ -133,3 +133,24 @@ def gather_v_meta(flat, n, d, G):
     t = np.arange(n)[:, None]
     g = np.arange(ngc)[None, :]
     return flat[((t // 32) * ngc + g) * 32 + kperm(t % 32)]
+
+
+def slots_per_event(W, G):
+    """Quantized slots one filtering event occupies: ceil(W/G) * G."""
+    return -(-W // G) * G
+
+
+def token_slots(n_tok, W, G):
+    """Slot of the i-th quantized token (eviction order): events of W tokens each start
+    at a multiple of slots_per_event; the slots behind a short last group are padding."""
+    i = np.arange(n_tok)
+    return (i // W) * slots_per_event(W, G) + i % W
+
+
+def to_slots(rows, W, G, fill=0):
+    """[n_tok][...] in eviction order -> [n_slots][...] with `fill` in the padding slots."""
+    rows = np.asarray(rows)
+    n_tok = rows.shape[0]
+    out = np.full((n_tok // W * slots_per_event(W, G),) + rows.shape[1:], fill, dtype=rows.dtype)
+    out[token_slots(n_tok, W, G)] = rows
+    return out

@@ -20,7 +20,10 @@ The scale is the one place evaluated in fp32 on purpose: it is a stored
 parameter that has to be reproducible bit for bit.
 
 Grouping.  Keys: statistics run along the token axis, one group per channel
-per run of G tokens in the order the tokens were evicted.  Values: statistics
+per run of G tokens in the order the tokens were evicted; the runs restart at
+every filtering event (its W tokens are quantized together, Sec. 2.5), the last
+run of an event shorter when G does not divide W (a reading: the paper's
+W = floor(R/3) with G = 64, Sec. 3.1 / appendix D, needs one).  Values: statistics
 run along the channel axis, one group per token per run of G channels, the last
 run shorter when G does not divide d (a reading: the paper is silent on values).
 """
@@ -67,16 +70,27 @@ def quantize_groups(x, dtype, bits=2):
     return codes, s, mn
 
 
-def quantize_keys(K_ev, G, dtype, bits=2):
-    """Keys of one compress event, [W][d] in eviction order, W % G == 0.
+def key_group_bounds(W, G):
+    """Token runs of one compress event: [(0,G), (G,2G), ..., (kG, W)]."""
+    return [(lo, min(lo + G, W)) for lo in range(0, W, G)]
 
-    Returns codes [W][d] uint8, scale [W/G][d], zero [W/G][d]."""
+
+def quantize_keys(K_ev, G, dtype, bits=2):
+    """Keys of one compress event, [W][d] in eviction order.
+
+    Returns codes [W][d] uint8, scale [ceil(W/G)][d], zero [ceil(W/G)][d]."""
     W, d = K_ev.shape
-    if W % G:
-        raise ValueError("group size must divide the number of evicted tokens")
-    x = np.asarray(K_ev, dtype=np.float32).reshape(W // G, G, d).transpose(0, 2, 1)
-    codes, s, z = quantize_groups(x, dtype, bits)    # [W/G][d][G]
-    return codes.transpose(0, 2, 1).reshape(W, d), s, z
+    K_ev = np.asarray(K_ev, dtype=np.float32)
+    bounds = key_group_bounds(W, G)
+    codes = np.zeros((W, d), dtype=np.uint8)
+    s = np.zeros((len(bounds), d), dtype=np.float32)
+    z = np.zeros((len(bounds), d), dtype=np.float32)
+    for j, (lo, hi) in enumerate(bounds):
+        c, sj, zj = quantize_groups(K_ev[lo:hi].T, dtype, bits)      # [d][hi-lo]: one group per channel
+        codes[lo:hi] = c.T
+        s[j] = sj
+        z[j] = zj
+    return codes, s, z
 
 
 def value_group_bounds(d, G):
@@ -101,10 +115,14 @@ def quantize_values(V_ev, G, dtype, bits=2):
     return codes, s, z
 
 
-def dequantize_keys(codes, scale, zero, G):
-    """x_hat[t][c] = zero[t//G][c] + codes[t][c] * scale[t//G][c], fp64."""
+def dequantize_keys(codes, scale, zero, G, W=None):
+    """x_hat[t][c] = zero[g(t)][c] + codes[t][c] * scale[g(t)][c], fp64.  The rows are
+    whole compress events of W tokens one after the other (W=None: one event), each
+    with ceil(W/G) groups: g(t) = (t // W) * ceil(W/G) + (t % W) // G."""
     n, d = codes.shape
-    grp = np.arange(n) // G
+    W = W or max(n, 1)
+    t = np.arange(n)
+    grp = (t // W) * (-(-W // G)) + (t % W) // G
     return zero.astype(np.float64)[grp] + codes.astype(np.float64) * scale.astype(np.float64)[grp]
 
 

@@ -20,12 +20,13 @@ lq_status make_shape(const lq_config* cfg, Shape* s) {
   if (cfg->d != 64 && cfg->d != 96 && cfg->d != 128) return LQ_ERR_UNSUPPORTED;
   if (cfg->group != 32 && cfg->group != 64 && cfg->group != 128) return LQ_ERR_UNSUPPORTED;
   const int W = cfg->fp_budget / 2;
-  if (W % cfg->group) return LQ_ERR_UNSUPPORTED;  // ragged key groups are not built
-  if (cfg->q_capacity % W || cfg->q_capacity % 64) return LQ_ERR_SHAPE;
+  const int Wq = (W + cfg->group - 1) / cfg->group * cfg->group;
+  if (cfg->q_capacity % Wq || cfg->q_capacity % 64) return LQ_ERR_SHAPE;
   if ((int64_t)cfg->B * cfg->Hkv * (int64_t)cfg->q_capacity * cfg->d > ((int64_t)1 << 40))
     return LQ_ERR_SHAPE;
   s->B = cfg->B; s->Hq = cfg->Hq; s->Hkv = cfg->Hkv; s->d = cfg->d;
-  s->W = W; s->G = cfg->group; s->cap = 3 * W; s->qcap = cfg->q_capacity;
+  s->W = W; s->G = cfg->group; s->full = 3 * W; s->cap = (3 * W + 31) / 32 * 32; s->Wq = Wq;
+  s->qcap = cfg->q_capacity;
   s->gh = cfg->Hq / cfg->Hkv;
   s->nkc = cfg->d / 32; s->nnt = cfg->d / 16; s->ngc = (cfg->d + cfg->group - 1) / cfg->group;
   s->bf16 = cfg->dtype == LQ_BF16;
@@ -42,9 +43,10 @@ int max_splits(const Shape& s) {
 }
 
 int64_t cache_bytes_read(const Shape& s, int n_fp, int n_q) {
-  // per quantized slot: K codes and V codes d*bits/8 bytes each; key scale+zero 4d
-  // bytes per G slots; value scale+zero 4 bytes per channel group.
-  const int64_t q_bytes = (int64_t)n_q * (s.d * s.bits / 4 + 4 * s.ngc) + (int64_t)(n_q / s.G) * 4 * s.d;
+  // per quantized token: K codes and V codes d*bits/8 bytes each, value scale+zero 4
+  // bytes per channel group; key scale+zero 4d bytes per key group (G slots).
+  const int64_t q_bytes = (int64_t)quantized_tokens(s, n_q) * (s.d * s.bits / 4 + 4 * s.ngc) +
+                          (int64_t)(n_q / s.G) * 4 * s.d;
   const int64_t fp_bytes = (int64_t)n_fp * 4 * s.d;
   return (int64_t)s.B * s.Hkv * (q_bytes + fp_bytes);
 }
@@ -63,8 +65,8 @@ static bool cache_ptrs_ok(const lq_cache* c) {
 
 static lq_status cache_state_ok(const Shape& s, const lq_cache* c) {
   if (c->cur != 0 && c->cur != 1) return LQ_ERR_STATE;
-  if (c->n_fp < 0 || c->n_fp > s.cap) return LQ_ERR_STATE;
-  if (c->n_q < 0 || c->n_q > s.qcap || c->n_q % s.W) return LQ_ERR_STATE;
+  if (c->n_fp < 0 || c->n_fp > s.full) return LQ_ERR_STATE;
+  if (c->n_q < 0 || c->n_q > s.qcap || c->n_q % s.Wq) return LQ_ERR_STATE;
   return LQ_OK;
 }
 
@@ -118,7 +120,7 @@ lq_status logquant_append(const lq_config* cfg, lq_cache* cache, const void* k_n
   if (!cache_ptrs_ok(cache)) return LQ_ERR_NULL;
   if ((st = cache_state_ok(s, cache)) != LQ_OK) return st;
   if (n_new <= 0) return LQ_ERR_SHAPE;
-  if (cache->n_fp + n_new > s.cap) return LQ_ERR_CAPACITY;
+  if (cache->n_fp + n_new > s.full) return LQ_ERR_CAPACITY;
   clear_stale_error();
   if (launch_append(s, *cache, k_new, v_new, n_new, (hipStream_t)stream) != hipSuccess)
     return LQ_ERR_HIP;
@@ -134,13 +136,13 @@ lq_status logquant_compress(const lq_config* cfg, lq_cache* cache, void* workspa
   if (st != LQ_OK) return st;
   if (!cache_ptrs_ok(cache)) return LQ_ERR_NULL;
   if ((st = cache_state_ok(s, cache)) != LQ_OK) return st;
-  if (cache->n_fp != s.cap) return LQ_ERR_STATE;
-  if (cache->n_q + s.W > s.qcap) return LQ_ERR_CAPACITY;
+  if (cache->n_fp != s.full) return LQ_ERR_STATE;
+  if (cache->n_q + s.Wq > s.qcap) return LQ_ERR_CAPACITY;
   clear_stale_error();
   if (launch_compress(s, *cache, (hipStream_t)stream) != hipSuccess) return LQ_ERR_HIP;
   cache->cur ^= 1;
   cache->n_fp = 2 * s.W;
-  cache->n_q += s.W;
+  cache->n_q += s.Wq;
   return LQ_OK;
 }
 
@@ -158,12 +160,12 @@ lq_status logquant_prefill(const lq_config* cfg, lq_cache* cache, const void* k,
   if (L < 1) return LQ_ERR_SHAPE;
   if (cache->n_fp != 0 || cache->n_q != 0) return LQ_ERR_STATE;
   const int E = events_after(L, s.W);
-  if ((int64_t)E * s.W > s.qcap) return LQ_ERR_CAPACITY;
+  if ((int64_t)E * s.Wq > s.qcap) return LQ_ERR_CAPACITY;
   const int n_fp = L - E * s.W;
   clear_stale_error();
   if (launch_prefill(s, *cache, k, v, L, E, n_fp, (hipStream_t)stream) != hipSuccess) return LQ_ERR_HIP;
   cache->n_fp = n_fp;
-  cache->n_q = E * s.W;
+  cache->n_q = E * s.Wq;
   return LQ_OK;
 }
 
@@ -187,7 +189,7 @@ lq_status logquant_decode_plan(const lq_config* cfg, int32_t n_fp, int32_t n_q, 
   Shape s;
   lq_status st = make_shape(cfg, &s);
   if (st != LQ_OK) return st;
-  if (n_fp < 0 || n_fp > s.cap || n_q < 0 || n_q > s.qcap || n_q % s.W || n_fp + n_q < 1)
+  if (n_fp < 0 || n_fp > s.full || n_q < 0 || n_q > s.qcap || n_q % s.Wq || n_fp + n_q < 1)
     return LQ_ERR_STATE;
   plan_decode(s, n_fp, n_q, out);
   return LQ_OK;
@@ -221,7 +223,7 @@ lq_status logquant_decode_step(const lq_config* cfg, lq_cache* cache, const void
   if (st != LQ_OK) return st;
   if (!cache_ptrs_ok(cache)) return LQ_ERR_NULL;
   if ((st = cache_state_ok(s, cache)) != LQ_OK) return st;
-  if (cache->n_fp + 1 >= s.cap) return LQ_ERR_STATE;   // the window would be full: append, compress, attend
+  if (cache->n_fp + 1 >= s.full) return LQ_ERR_STATE;   // the window would be full: append, compress, attend
   lq_cache after = *cache;
   after.n_fp += 1;
   lq_plan plan;

@@ -41,7 +41,7 @@ hipError_t launch_append(const Shape& s, const lq_cache& c, const void* k_new, c
   dim3 grid(n_new, s.B * s.Hkv);
   hipLaunchKernelGGL(append_kernel, grid, dim3(s.d), 0, st, (const uint16_t*)k_new,
                      (const uint16_t*)v_new, (uint16_t*)c.k_fp[c.cur], (uint16_t*)c.v_fp[c.cur],
-                     c.pos_fp[c.cur], n_new, c.n_fp, c.n_fp + c.n_q, s.d, s.cap, s.Hkv);
+                     c.pos_fp[c.cur], n_new, c.n_fp, c.n_fp + quantized_tokens(s, c.n_q), s.d, s.cap, s.Hkv);
   return launch_status(__func__);
 }
 

@@ -40,8 +40,10 @@ void plan_decode(const Shape& s, int n_fp, int n_q, lq_plan* plan) {
   const double fixed = 2.5, per_split = 0.02;
   int best_wpb = 8, best_splits = 1;
   double best = 1e300;
+  const bool ragged = s.Wq != s.W;   // padding slots in the quantized region: 8-wavefront kernel only
   for (int wpb = 8; wpb >= 4; wpb -= 4) {
-    if (force_wpb && force_wpb != 12 && wpb != force_wpb) continue;
+    if (ragged && wpb != 8) continue;
+    if (!ragged && force_wpb && force_wpb != 12 && wpb != force_wpb) continue;
     const int slots = cus * (8 / wpb);
     int smax = (int)ceil(units / wpb);            // at least one unit per wavefront
     if (smax > max_splits(s)) smax = max_splits(s);
@@ -58,7 +60,7 @@ void plan_decode(const Shape& s, int n_fp, int n_q, lq_plan* plan) {
   // than 8 with fewer than ~6 tiles per wavefront and slower than 4 when every
   // compute unit holds two workgroups anyway.  Only built for 2-bit codes (the 4-bit
   // tile does not fit 168 registers).
-  if (s.bits == 2 && (force_wpb == 12 || (!force_wpb && best_wpb == 8 && units / (best_splits * 8.0) >= 6.0)))
+  if (!ragged && s.bits == 2 && (force_wpb == 12 || (!force_wpb && best_wpb == 8 && units / (best_splits * 8.0) >= 6.0)))
     best_wpb = 12;
   const int splits = best_splits, WPB = best_wpb;
   const int NW = WPB * splits;

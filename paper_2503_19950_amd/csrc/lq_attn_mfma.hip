@@ -78,12 +78,15 @@ struct AttnParams {
   int32_t* pos_fp;
   int Hkv;
   int cap, qcap, n_fp, n_q, gh, hb, splits, nwf;
+  int W, Wq;          // of every Wq quantized slots (one filtering event) the first W hold tokens
+  int n_tok_q;        // tokens in the n_q quantized slots
   int dynamic;        // 0: static tile schedule only
   float c;  // softmax scale * log2(e)
 };
 
 constexpr int PSHIFT = 5;   // probabilities are kept relative to 2^(max - PSHIFT)
 constexpr float MAX_SLACK = 4.f;
+constexpr float DEAD_LOGIT = -1e30f;   // logit of a padding slot; exp2(DEAD_LOGIT - anything finite) == 0
 
 __device__ __forceinline__ floatx4 mfma_f16(uint4 a, uint4 b, floatx4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a),
@@ -336,7 +339,9 @@ __device__ __forceinline__ void online_softmax_rows(State<NNT>& st, const float*
 // two workgroups on every compute unit; 12 (three wavefronts per SIMD, at most 168
 // registers) for long contexts, where the extra wavefront hides more than the tighter
 // register budget costs.
-template <bool BF16, int D, int G, int NWB, int BITS>
+// RAGGED: the group size does not divide the window, so the quantized region has
+// padding slots (built for 8 wavefronts per workgroup only).
+template <bool BF16, int D, int G, int NWB, int BITS, bool RAGGED = false>
 __global__ void __launch_bounds__(64 * NWB, NWB == 12 ? 3 : 2)
 attn_mfma_kernel(const AttnParams P) {
   constexpr int NKC = D / 32, NNT = D / 16, NGC = (D + G - 1) / G;
@@ -613,6 +618,18 @@ attn_mfma_kernel(const AttnParams P) {
         for (int u = 0; u < 4; ++u)
           if (64 * t + 16 * u + n16 >= P.n_q) s[u] = -INFINITY;
       }
+      if constexpr (RAGGED) {
+        // padding slots behind a short key group (zero codes, zero value scales and
+        // zero-points): a finite sentinel, so that a tile made of padding only leaves
+        // a state whose weight in every later merge is exactly 0
+        const int r0 = (64 * t) % P.Wq;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          int r = r0 + 16 * u + n16;
+          r = r >= P.Wq ? r - P.Wq : r;
+          if (r >= P.W) s[u] = DEAD_LOGIT;
+        }
+      }
       online_softmax_rows<NNT>(st, s, p, g);
 
       // ---- hand the probabilities (fp16) to the lanes that feed the output step
@@ -766,7 +783,7 @@ attn_mfma_kernel(const AttnParams P) {
           }
         }
         if (hsub == 0 && bh % P.Hkv == 0 && lane == 0)
-          P.pos_fp[(bh / P.Hkv) * P.cap + P.n_fp - 1] = P.n_fp - 1 + P.n_q;
+          P.pos_fp[(bh / P.Hkv) * P.cap + P.n_fp - 1] = P.n_fp - 1 + P.n_tok_q;
       }
 
       floatx4 Du[2] = {floatx4{0.f, 0.f, 0.f, 0.f}, floatx4{0.f, 0.f, 0.f, 0.f}};
@@ -1022,6 +1039,16 @@ hipError_t launch_combine(const Shape& s, const float* ws, void* out, int splits
 
 template <bool BF16, int D, int NWB, int BITS>
 static hipError_t launch_mfma_dg(const Shape& s, const AttnParams& P, dim3 grid, hipStream_t st) {
+  if constexpr (NWB == 8) {
+    if (s.Wq != s.W) {
+      switch (s.G) {
+        case 32: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 32, 8, BITS, true>), grid, dim3(512), 0, st, P); break;
+        case 64: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 64, 8, BITS, true>), grid, dim3(512), 0, st, P); break;
+        default: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 128, 8, BITS, true>), grid, dim3(512), 0, st, P); break;
+      }
+      return launch_status(__func__);
+    }
+  }
   switch (s.G) {
     case 32: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 32, NWB, BITS>), grid, dim3(64 * NWB), 0, st, P); break;
     case 64: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 64, NWB, BITS>), grid, dim3(64 * NWB), 0, st, P); break;
@@ -1061,12 +1088,17 @@ hipError_t launch_decode_attn_mfma(const Shape& s, const lq_cache& c, const void
   P.ws = (float*)((char*)ws + counter_bytes(s));
   P.out = (uint16_t*)out;
   P.cap = s.cap; P.qcap = s.qcap; P.n_fp = c.n_fp; P.n_q = c.n_q; P.gh = s.gh;
+  P.W = s.W; P.Wq = s.Wq; P.n_tok_q = quantized_tokens(s, c.n_q);
   P.hb = s.gh % 4 == 0 ? 4 : (s.gh % 2 == 0 ? 2 : 1);
   P.splits = plan.splits; P.nwf = plan.fp_waves;
   P.c = scale * 1.4426950408889634f;
   static const int dynamic = [] { const char* v = getenv("LOGQUANT_ATTN_DYNAMIC"); return v && *v ? atoi(v) : 1; }();
   P.dynamic = dynamic;
   dim3 grid(plan.splits, s.B * s.Hkv * (s.gh / P.hb));
+  if (s.Wq != s.W) {   // padding slots: the kernel variant that skips them exists for 8 wavefronts only
+    if (plan.waves_per_block != 8) return hipErrorInvalidConfiguration;
+    return s.bits == 4 ? launch_mfma_t<8, 4>(s, P, grid, st) : launch_mfma_t<8, 2>(s, P, grid, st);
+  }
   if (plan.waves_per_block == 12 && s.bits == 2) return launch_mfma_t<12, 2>(s, P, grid, st);
   if (plan.waves_per_block == 4)
     return s.bits == 4 ? launch_mfma_t<4, 4>(s, P, grid, st) : launch_mfma_t<4, 2>(s, P, grid, st);

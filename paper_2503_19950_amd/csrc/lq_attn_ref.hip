@@ -23,7 +23,8 @@ attn_ref_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_f
                 const uint32_t* __restrict__ v_codes, const uint16_t* __restrict__ k_scale,
                 const uint16_t* __restrict__ k_zero, const uint16_t* __restrict__ v_scale,
                 const uint16_t* __restrict__ v_zero, float* __restrict__ ws, int d, int G, int cap,
-                int qcap, int n_fp, int n_q, int gh, int splits, float scale_log2e, int bits) {
+                int qcap, int n_fp, int n_q, int gh, int splits, float scale_log2e, int bits, int W,
+                int Wq) {
   __shared__ float sm_o[4][HB][128];
   __shared__ float sm_ml[4][HB][2];
   const int split = blockIdx.x;
@@ -54,6 +55,7 @@ attn_ref_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_f
   const int64_t vmeta_slice = (int64_t)bh * (qcap >> 5) * ngc * 32;
 
   for (int t = t0 + wave; t < t1; t += 4) {
+    if (t >= n_fp && (t - n_fp) % Wq >= W) continue;   // padding slot behind a short key group
     float kx[2] = {0.f, 0.f}, vx[2] = {0.f, 0.f};
 #pragma unroll
     for (int e = 0; e < 2; ++e) {
@@ -131,7 +133,8 @@ static hipError_t launch_ref_t(const Shape& s, const lq_cache& c, const void* q,
                      (const uint16_t*)c.k_fp[c.cur], (const uint16_t*)c.v_fp[c.cur], c.k_codes,
                      c.v_codes, (const uint16_t*)c.k_scale, (const uint16_t*)c.k_zero,
                      (const uint16_t*)c.v_scale, (const uint16_t*)c.v_zero, (float*)ws, s.d, s.G,
-                     s.cap, s.qcap, c.n_fp, c.n_q, s.gh, splits, scale * 1.4426950408889634f, s.bits);
+                     s.cap, s.qcap, c.n_fp, c.n_q, s.gh, splits, scale * 1.4426950408889634f, s.bits,
+                     s.W, s.Wq);
   return launch_status(__func__);
 }
 

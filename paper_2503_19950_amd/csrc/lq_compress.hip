@@ -73,32 +73,40 @@ struct FpSource {
   const uint16_t* v_fp;
   const int32_t* pos_fp;  // row of this batch entry
   int j;
+  int ng;                 // rows of this group (G, fewer in the last group of an event when G does not divide W)
+  int cap;                // rows allocated per slice (multiple of 32)
+  // FULL: the group has all G rows (compile-time trip counts, no row checks)
+  template <bool FULL>
   __device__ __forceinline__ void stage_keys(uint16_t* sm, int ld) const {
     for (int idx = threadIdx.x; idx < G * nkc * 4; idx += 256) {
       const int oct = idx % (nkc * 4), e = idx / (nkc * 4);
       const int ts = 2 * (j * G + e) + 1;
-      const uint4 v = *reinterpret_cast<const uint4*>(k_fp + k_fp_index(ts, oct * 8, nkc));
+      uint4 v = make_uint4(0u, 0u, 0u, 0u);
+      if (FULL || e < ng) v = *reinterpret_cast<const uint4*>(k_fp + k_fp_index(ts, oct * 8, nkc));
       uint32_t* dst = reinterpret_cast<uint32_t*>(sm + e * ld + oct * 8);
       dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
     }
   }
   // source rows: logical slots 2jG .. 2jG + 2G - 1 (whole 32-slot tiles)
+  template <bool FULL>
   __device__ __forceinline__ void stage_values(uint16_t* sm, int ld) const {
     for (int idx = threadIdx.x; idx < (2 * G >> 5) * nnt * 64; idx += 256) {
       const int lane = idx & 63, nt = (idx >> 6) % nnt, sb = idx / (64 * nnt);
       const int qq = lane >> 4, n = lane & 15;
-      const int64_t src = ((((int64_t)((2 * j * G) >> 5) + sb) * nnt + nt) * 64 + lane) * 8;
-      const uint4 v = *reinterpret_cast<const uint4*>(v_fp + src);
+      const int tile = ((2 * j * G) >> 5) + sb;
+      const int64_t src = (((int64_t)tile * nnt + nt) * 64 + lane) * 8;
+      uint4 v = make_uint4(0u, 0u, 0u, 0u);
+      if (FULL || (32 * tile < cap && 16 * sb < ng)) v = *reinterpret_cast<const uint4*>(v_fp + src);
       const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
       for (int i = 1; i < 8; i += 2) {  // odd element <=> odd logical slot <=> evicted
         const int x = kperm_inv(8 * qq + i);
         const int e = (sb * 32 + x - 1) >> 1;
-        sm[e * ld + 16 * nt + n] = (uint16_t)(w[i >> 1] >> 16);
+        sm[e * ld + 16 * nt + n] = (FULL || e < ng) ? (uint16_t)(w[i >> 1] >> 16) : (uint16_t)0;
       }
     }
   }
-  __device__ __forceinline__ int position(int e) const { return pos_fp[2 * (j * G + e) + 1]; }
+  __device__ __forceinline__ int position(int e) const { return e < ng ? pos_fp[2 * (j * G + e) + 1] : -1; }
 };
 // (b) bulk prefill: rows of a row-major prompt tensor, at the positions Algorithm 1
 // evicts at event `ev`
@@ -107,13 +115,17 @@ struct PromptSource {
   const uint16_t* k;      // slice base, [L][d]
   const uint16_t* v;
   const int* posl;        // LDS: positions of the G rows
-  __device__ __forceinline__ void stage_keys(uint16_t* sm, int ld) const { stage(k, sm, ld); }
-  __device__ __forceinline__ void stage_values(uint16_t* sm, int ld) const { stage(v, sm, ld); }
+  template <bool FULL>
+  __device__ __forceinline__ void stage_keys(uint16_t* sm, int ld) const { stage<FULL>(k, sm, ld); }
+  template <bool FULL>
+  __device__ __forceinline__ void stage_values(uint16_t* sm, int ld) const { stage<FULL>(v, sm, ld); }
+  template <bool FULL>
   __device__ __forceinline__ void stage(const uint16_t* x, uint16_t* sm, int ld) const {
     constexpr int octs = d >> 3;
     for (int idx = threadIdx.x; idx < G * octs; idx += 256) {
       const int oct = idx % octs, e = idx / octs;
-      const uint4 val = *reinterpret_cast<const uint4*>(x + (int64_t)posl[e] * d + oct * 8);
+      uint4 val = make_uint4(0u, 0u, 0u, 0u);   // rows past a short group: zeros
+      if (FULL || posl[e] >= 0) val = *reinterpret_cast<const uint4*>(x + (int64_t)posl[e] * d + oct * 8);
       uint32_t* dst = reinterpret_cast<uint32_t*>(sm + e * ld + oct * 8);
       dst[0] = val.x; dst[1] = val.y; dst[2] = val.z; dst[3] = val.w;
     }
@@ -121,7 +133,10 @@ struct PromptSource {
   __device__ __forceinline__ int position(int e) const { return posl[e]; }
 };
 
-// Quantize one key group (G rows) of slice bh into quantized slots q0 .. q0+G-1.
+// Quantize one key group (ng <= G rows) of slice bh into quantized slots q0 .. q0+G-1.
+// Slots past a short group (the last group of an event when G does not divide W) get
+// zero codes, zero value scales and zero-points and position -1; the key statistics
+// run over the ng rows only.  The staged rows past ng are zeros.
 // 256 threads.  LDS: sm = G * (d + 4) uint16 (the staged rows), cb = QG_CODE_BYTES
 // bytes (the codes, one byte each: keys [token][d + 4], values transposed
 // [channel][G + 4], so that the eight codes of a packed operand are two aligned
@@ -129,13 +144,14 @@ struct PromptSource {
 template <int d, int G>
 constexpr int QG_CODE_BYTES = (G * (d + 4) > d * (G + 4) ? G * (d + 4) : d * (G + 4));
 
-template <bool BF16, int d, int G, int BITS, class Src>
-__device__ __forceinline__ void quantize_group(
-    uint16_t* sm, uint8_t* cb, float* red, const Src& src, int bh, int q0, uint32_t* __restrict__ k_codes,
+template <bool BF16, int d, int G, int BITS, bool FULL, class Src>
+__device__ __forceinline__ void quantize_group_t(
+    uint16_t* sm, uint8_t* cb, float* red, const Src& src, int ng_in, int bh, int q0, uint32_t* __restrict__ k_codes,
     uint32_t* __restrict__ v_codes, uint16_t* __restrict__ k_scale, uint16_t* __restrict__ k_zero,
     uint16_t* __restrict__ v_scale, uint16_t* __restrict__ v_zero, int32_t* __restrict__ pos_q,
     int qcap, int Hkv) {
   const int tid = threadIdx.x;
+  const int ng = FULL ? G : ng_in;        // a compile-time constant for whole groups
   constexpr int nkc = d >> 5, ngc = (d + G - 1) / G, ld = d + 4;
   constexpr int WPL = nkc * (BITS / 2);   // code words per lane and 32-slot block
   constexpr int KP = d + 4, VP = G + 4;   // byte pitches of the code arrays
@@ -143,7 +159,7 @@ __device__ __forceinline__ void quantize_group(
   const uint32_t* cw = reinterpret_cast<const uint32_t*>(cb);
 
   // ---------------- keys ----------------
-  src.stage_keys(sm, ld);
+  src.template stage_keys<FULL>(sm, ld);
   __syncthreads();
   // per channel: 256 / d threads each scan a share of the G tokens, exchange their
   // partial minima and maxima, and then encode their own share
@@ -153,7 +169,8 @@ __device__ __forceinline__ void quantize_group(
     const int e0 = part * per;
     float mn = INFINITY, mx = -INFINITY;
     if (part < parts) {
-      for (int e = e0; e < e0 + per; ++e) {
+      const int e1 = FULL ? e0 + per : min(e0 + per, ng);
+      for (int e = e0; e < e1; ++e) {
         const float x = t2f<BF16>(sm[e * ld + c]);
         mn = fminf(mn, x);
         mx = fmaxf(mx, x);
@@ -176,7 +193,8 @@ __device__ __forceinline__ void quantize_group(
         k_zero[mi] = zt;
       }
       const Encoder<BITS> enc(z, sc);
-      for (int e = e0; e < e0 + per; ++e) cb[e * KP + c] = (uint8_t)enc(t2f<BF16>(sm[e * ld + c]));
+      for (int e = e0; e < e0 + per; ++e)
+        cb[e * KP + c] = (FULL || e < ng) ? (uint8_t)enc(t2f<BF16>(sm[e * ld + c])) : (uint8_t)0;
     }
   }
   __syncthreads();
@@ -204,7 +222,7 @@ __device__ __forceinline__ void quantize_group(
   __syncthreads();
 
   // ---------------- values ----------------
-  src.stage_values(sm, ld);
+  src.template stage_values<FULL>(sm, ld);
   __syncthreads();
   // per (token, channel group): VP threads each scan a share of the channels; the
   // shares of one group sit in neighbouring lanes and are combined by lane shuffles
@@ -266,8 +284,22 @@ __device__ __forceinline__ void quantize_group(
   // positions of the evicted tokens, once per batch row
   if (bh % Hkv == 0) {
     const int b = bh / Hkv;
-    for (int e = tid; e < G; e += 256) pos_q[(int64_t)b * qcap + q0 + e] = src.position(e);
+    for (int e = tid; e < G; e += 256) pos_q[(int64_t)b * qcap + q0 + e] = src.position(e);   // -1 past a short group
   }
+}
+
+template <bool BF16, int d, int G, int BITS, class Src>
+__device__ __forceinline__ void quantize_group(
+    uint16_t* sm, uint8_t* cb, float* red, const Src& src, int ng, int bh, int q0, uint32_t* __restrict__ k_codes,
+    uint32_t* __restrict__ v_codes, uint16_t* __restrict__ k_scale, uint16_t* __restrict__ k_zero,
+    uint16_t* __restrict__ v_scale, uint16_t* __restrict__ v_zero, int32_t* __restrict__ pos_q,
+    int qcap, int Hkv) {
+  if (ng == G)
+    quantize_group_t<BF16, d, G, BITS, true>(sm, cb, red, src, ng, bh, q0, k_codes, v_codes, k_scale, k_zero, v_scale,
+                                             v_zero, pos_q, qcap, Hkv);
+  else
+    quantize_group_t<BF16, d, G, BITS, false>(sm, cb, red, src, ng, bh, q0, k_codes, v_codes, k_scale, k_zero, v_scale,
+                                              v_zero, pos_q, qcap, Hkv);
 }
 
 // Kept rows -> rows 32*nb .. 32*nb+31 of the other fp buffer of slice bh.  256 threads.
@@ -282,8 +314,9 @@ __device__ __forceinline__ void compact_rows(
     const int x = idx & 31, oct = idx >> 5;
     const int tn = nb * 32 + x;
     const int ts = tn < W ? 2 * tn : tn + W;
-    *reinterpret_cast<uint4*>(k_new + slice + k_fp_index(tn, oct * 8, nkc)) =
-        *reinterpret_cast<const uint4*>(k_old + slice + k_fp_index(ts, oct * 8, nkc));
+    if (tn < 2 * W)   // the last block is short when 32 does not divide 2W
+      *reinterpret_cast<uint4*>(k_new + slice + k_fp_index(tn, oct * 8, nkc)) =
+          *reinterpret_cast<const uint4*>(k_old + slice + k_fp_index(ts, oct * 8, nkc));
   }
   for (int idx = tid; idx < nnt * 64; idx += 256) {
     const int lane = idx & 63, nt = idx >> 6;
@@ -293,7 +326,7 @@ __device__ __forceinline__ void compact_rows(
     for (int i = 0; i < 8; ++i) {
       const int tn = nb * 32 + kperm_inv(8 * qq + i);
       const int ts = tn < W ? 2 * tn : tn + W;
-      const uint32_t e = v_old[slice + v_fp_index(ts, 16 * nt + n, nnt)];
+      const uint32_t e = tn < 2 * W ? v_old[slice + v_fp_index(ts, 16 * nt + n, nnt)] : 0u;
       w[i >> 1] |= e << (16 * (i & 1));
     }
     *reinterpret_cast<uint4*>(v_new + slice + (((int64_t)nb * nnt + nt) * 64 + lane) * 8) =
@@ -302,7 +335,7 @@ __device__ __forceinline__ void compact_rows(
   if (bh % Hkv == 0 && tid < 32) {
     const int b = bh / Hkv, tn = nb * 32 + tid;
     const int ts = tn < W ? 2 * tn : tn + W;
-    pos_new[b * cap + tn] = pos_old[b * cap + ts];
+    if (tn < 2 * W) pos_new[b * cap + tn] = pos_old[b * cap + ts];
   }
 }
 
@@ -318,20 +351,21 @@ struct CompressParams {
 };
 
 // One launch does both halves of the filtering branch; they read the same buffer and
-// write disjoint ones.  grid (W/G + 2W/32, B*Hkv), block 256: workgroups x < W/G
-// quantize one key group each, the others move 32 kept rows each.
+// write disjoint ones.  grid (ceil(W/G) + ceil(2W/32), B*Hkv), block 256: workgroups
+// x < ceil(W/G) quantize one key group each, the others move 32 kept rows each.
 // Dynamic LDS: G * (d + 4) uint16.
 template <bool BF16, int D, int G, int BITS>
 __global__ void __launch_bounds__(256) compress_kernel(const CompressParams P) {
   extern __shared__ uint16_t sm[];  // [G][d + 4]: the staged rows
   __shared__ float red[8 * 128];    // partial minima [4][d] and maxima [4][d] of the key channels
   __shared__ __attribute__((aligned(16))) uint8_t cb[QG_CODE_BYTES<D, G>];
-  const int nq = P.W / G, bh = blockIdx.y;
+  const int nq = (P.W + G - 1) / G, bh = blockIdx.y;
   if ((int)blockIdx.x < nq) {
     const int j = blockIdx.x;
+    const int ng = min(G, P.W - j * G);
     const int64_t fp_slice = (int64_t)bh * P.cap * D;
-    const FpSource<D, G> src{P.k_old + fp_slice, P.v_old + fp_slice, P.pos_old + (bh / P.Hkv) * P.cap, j};
-    quantize_group<BF16, D, G, BITS>(sm, cb, red, src, bh, P.n_q + j * G, P.k_codes, P.v_codes, P.k_scale, P.k_zero,
+    const FpSource<D, G> src{P.k_old + fp_slice, P.v_old + fp_slice, P.pos_old + (bh / P.Hkv) * P.cap, j, ng, P.cap};
+    quantize_group<BF16, D, G, BITS>(sm, cb, red, src, ng, bh, P.n_q + j * G, P.k_codes, P.v_codes, P.k_scale, P.k_zero,
                                P.v_scale, P.v_zero, P.pos_q, P.qcap, P.Hkv);
   } else {
     compact_rows(blockIdx.x - nq, bh, P.k_old, P.v_old, P.pos_old, P.k_new, P.v_new, P.pos_new, P.d,
@@ -343,8 +377,8 @@ __global__ void __launch_bounds__(256) compress_kernel(const CompressParams P) {
 // The state Algorithm 1 (filtering as soon as the list is full) reaches after L
 // appends, computed from the whole prompt in one launch.  Which position ends up in
 // which slot is known in closed form (list_entry / evicted_position), so every key
-// group of every event is independent: grid (E * W/G + ceil(n_fp/32), B*Hkv), block
-// 256; workgroups x < E*W/G quantize key group x % (W/G) of event x / (W/G) + 1
+// group of every event is independent: grid (E * KG + ceil(n_fp/32), B*Hkv), KG =
+// ceil(W/G), block 256; workgroups x < E*KG quantize key group x % KG of event x / KG + 1
 // exactly as the filtering step would have, the others place 32 fp rows each.
 struct PrefillParams {
   const uint16_t *k, *v;          // [B*Hkv][L][d]
@@ -363,14 +397,15 @@ __global__ void __launch_bounds__(256) prefill_kernel(const PrefillParams P) {
   __shared__ __attribute__((aligned(16))) uint8_t cb[QG_CODE_BYTES<D, G>];
   __shared__ int posl[128];
   const int tid = threadIdx.x, bh = blockIdx.y;
-  const int per_event = P.W / G, nqb = P.E * per_event;
+  const int per_event = (P.W + G - 1) / G, nqb = P.E * per_event;
   const int64_t prompt = (int64_t)bh * P.L * D;
   if ((int)blockIdx.x < nqb) {
     const int ev = blockIdx.x / per_event + 1, j = blockIdx.x % per_event;
-    if (tid < G) posl[tid] = evicted_position(ev, j * G + tid, P.W);
+    const int ng = min(G, P.W - j * G);
+    if (tid < G) posl[tid] = tid < ng ? evicted_position(ev, j * G + tid, P.W) : -1;
     __syncthreads();
     const PromptSource<D, G> src{P.k + prompt, P.v + prompt, posl};
-    quantize_group<BF16, D, G, BITS>(sm, cb, red, src, bh, (ev - 1) * P.W + j * G, P.k_codes, P.v_codes, P.k_scale,
+    quantize_group<BF16, D, G, BITS>(sm, cb, red, src, ng, bh, (ev - 1) * per_event * G + j * G, P.k_codes, P.v_codes, P.k_scale,
                                P.k_zero, P.v_scale, P.v_zero, P.pos_q, P.qcap, P.Hkv);
     return;
   }
@@ -457,7 +492,7 @@ hipError_t launch_compress(const Shape& s, const lq_cache& c, hipStream_t st) {
   P.pos_q = c.pos_q;
   P.d = s.d; P.G = s.G; P.W = s.W; P.cap = s.cap; P.qcap = s.qcap; P.n_q = c.n_q; P.Hkv = s.Hkv;
   const size_t lds = (size_t)s.G * (s.d + 4) * sizeof(uint16_t);
-  dim3 grid(s.W / s.G + 2 * s.W / 32, s.B * s.Hkv);
+  dim3 grid(s.Wq / s.G + (2 * s.W + 31) / 32, s.B * s.Hkv);
   dispatch_dg<CompressLaunch>(s, grid, lds, st, P);
   return launch_status(__func__);
 }
@@ -474,7 +509,7 @@ hipError_t launch_prefill(const Shape& s, const lq_cache& c, const void* k, cons
   P.d = s.d; P.G = s.G; P.W = s.W; P.cap = s.cap; P.qcap = s.qcap; P.Hkv = s.Hkv;
   P.L = L; P.E = E; P.n_fp = n_fp;
   const size_t lds = (size_t)s.G * (s.d + 4) * sizeof(uint16_t);
-  dim3 grid(E * (s.W / s.G) + (n_fp + 31) / 32, s.B * s.Hkv);
+  dim3 grid(E * (s.Wq / s.G) + (n_fp + 31) / 32, s.B * s.Hkv);
   dispatch_dg<PrefillLaunch>(s, grid, lds, st, P);
   return launch_status(__func__);
 }

@@ -8,7 +8,9 @@
 namespace lq {
 
 struct Shape {
-  int B, Hq, Hkv, d, W, G, cap, qcap, gh;  // gh = Hq/Hkv, cap = 3W
+  int B, Hq, Hkv, d, W, G, cap, qcap, gh;  // gh = Hq/Hkv; cap = fp rows allocated per slice (3W rounded up to 32)
+  int full;                                // 3W: list length at which the filtering step runs
+  int Wq;                                  // quantized slots per filtering event: ceil(W/G) * G (W when G divides W)
   int nkc, nnt, ngc;                       // d/32, d/16, ceil(d/G)
   int bits;                                // 2 or 4
   bool bf16;
@@ -32,6 +34,8 @@ hipError_t launch_workspace_init(const Shape& s, void* ws, hipStream_t st);
 
 // Bytes one decode step reads from the cache (live slots only).
 int64_t cache_bytes_read(const Shape& s, int n_fp, int n_q);
+// Tokens held in n_q quantized slots (n_q is a multiple of Wq; W of every Wq slots are live).
+inline int quantized_tokens(const Shape& s, int n_q) { return n_q / s.Wq * s.W; }
 
 // hipGetLastError() also reports failures of earlier, unrelated runtime calls made
 // by other code in the process (an expected hipErrorNotReady, say).  Launchers

@@ -33,9 +33,7 @@ def build_gpu(wl, seed_id, L, q_capacity=None, poison=False, b_list=None):
     from paper_2503_19950_amd import binding
     W = wl["F"] // 2
     if q_capacity is None:
-        q_capacity = max(64, -(-L // (2 * W)) * 2 * W)
-        while q_capacity % 64 or q_capacity % W:
-            q_capacity += W
+        q_capacity = q_capacity_for(wl, L)
     cfg = binding.make_config(wl["B"], wl["Hq"], wl["Hkv"], wl["d"], wl["F"], wl["G"], wl["dtype"],
                               q_capacity, wl.get("bits", 2))
     dc = binding.DeviceCache(cfg, poison=poison)
@@ -64,16 +62,17 @@ def check_state(dc, oc, wl, b, h):
     """Bit-exact comparison of one (b, h) slice of the GPU cache with the oracle."""
     d, G, dt = wl["d"], wl["G"], wl["dtype"]
     W = wl["F"] // 2
-    cap, qcap = 3 * W, dc.cfg.q_capacity
+    cap, qcap = fp_rows_allocated(W), dc.cfg.q_capacity
     nkc, ngc = d // 32, -(-d // G)
     bh = b * wl["Hkv"] + h
     cur = dc.c.cur
-    assert (dc.c.n_fp, dc.c.n_q) == (oc.n_fp, oc.n_q)
-    n_fp, n_q = oc.n_fp, oc.n_q
+    # the library counts quantized slots (padding behind short key groups included)
+    n_fp, n_q = oc.n_fp, oc.n_q // W * layout.slots_per_event(W, G)
+    assert (dc.c.n_fp, dc.c.n_q) == (n_fp, n_q)
     pos_fp = _np(dc.pos_fp[cur], np.int32)[b * cap:b * cap + n_fp]
     assert pos_fp.tolist() == oc.pos_fp, "fp positions"
     pos_q = _np(dc.pos_q, np.int32)[b * qcap:b * qcap + n_q]
-    assert pos_q.tolist() == oc.pos_q, "quantized positions"
+    assert pos_q.tolist() == layout.to_slots(np.array(oc.pos_q, np.int64), W, G, fill=-1).tolist(), "quantized positions"
     for which, buf, rows in (("k", dc.k_fp[cur], oc.K_fp), ("v", dc.v_fp[cur], oc.V_fp)):
         flat = _np(buf, np.uint16)[bh * cap * d:(bh + 1) * cap * d]
         got = layout.gather_fp(flat, which, n_fp, d)
@@ -84,14 +83,14 @@ def check_state(dc, oc, wl, b, h):
     nw = n_q // 32 * 64 * nkc * (bits // 2)
     for which, buf, codes in (("k", dc.k_codes, oc.K_codes), ("v", dc.v_codes, oc.V_codes)):
         words = _np(buf, np.uint32)[bh * (qcap // 32) * 64 * nkc * (bits // 2):][:nw]
-        want = layout.pack_codes(codes, which, bits=bits)
+        want = layout.pack_codes(layout.to_slots(codes, W, G), which, bits=bits)   # padding slots: zero codes
         assert np.array_equal(words, want), "packed codes " + which
     for buf, meta, name in ((dc.k_scale, oc.K_scale, "k_scale"), (dc.k_zero, oc.K_zero, "k_zero")):
         got = _np(buf, np.uint16)[bh * (qcap // G) * d:][:n_q // G * d]
         assert np.array_equal(got, inputs.to_bits16(meta, dt).ravel()), name
     for buf, meta, name in ((dc.v_scale, oc.V_scale, "v_scale"), (dc.v_zero, oc.V_zero, "v_zero")):
         got = _np(buf, np.uint16)[bh * (qcap // 32) * ngc * 32:][:n_q // 32 * ngc * 32]
-        want = layout.scatter_v_meta(inputs.to_bits16(meta, dt), d, G)
+        want = layout.scatter_v_meta(layout.to_slots(inputs.to_bits16(meta, dt), W, G), d, G)   # padding: zeros
         assert np.array_equal(got, want), name
 
 
@@ -169,12 +168,18 @@ def build_gpu_sampled(wl, seed_id, L, distinct, q_capacity=None):
 
 
 def q_capacity_for(wl, L):
-    """A valid q_capacity (multiple of W and of 64) with room for L tokens."""
+    """A valid q_capacity (multiple of the slots of one event and of 64) with room for L tokens."""
     W = wl["F"] // 2
-    q_capacity = max(64, -(-L // (2 * W)) * 2 * W)
-    while q_capacity % 64 or q_capacity % W:
-        q_capacity += W
+    Wq = layout.slots_per_event(W, wl["G"])
+    q_capacity = max(64, -(-L // (2 * W)) * 2 * Wq)
+    while q_capacity % 64 or q_capacity % Wq:
+        q_capacity += Wq
     return q_capacity
+
+
+def fp_rows_allocated(W):
+    """Rows per slice of the fp buffers: 3W rounded up to whole 32-row tiles."""
+    return -(-3 * W // 32) * 32
 
 
 def new_cache(wl, L, q_capacity=None, poison=False):
@@ -198,7 +203,7 @@ def live_buffers(dc, wl):
     """Every buffer of the cache restricted to what the counts make meaningful, as numpy."""
     d, G = wl["d"], wl["G"]
     W = wl["F"] // 2
-    cap, qcap, BH = 3 * W, dc.cfg.q_capacity, wl["B"] * wl["Hkv"]
+    cap, qcap, BH = fp_rows_allocated(W), dc.cfg.q_capacity, wl["B"] * wl["Hkv"]
     nkc, ngc = d // 32, -(-d // G)
     cur, n_fp, n_q = dc.c.cur, dc.c.n_fp, dc.c.n_q
     out = {"counts": np.array([n_fp, n_q])}

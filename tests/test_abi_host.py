@@ -43,6 +43,14 @@ def test_sizes_match_the_documented_layouts():
     assert s4.k_codes == s4.v_codes == bh * qc * d // 2 and s4.k_meta == s.k_meta and s4.k_fp == s.k_fp
     s = B.logquant_sizes(_cfg(d=96, group=64, Hq=8, Hkv=8, fp_budget=384, q_capacity=384 * 2))
     assert s.v_meta == 8 * 768 * 2 * 2        # ceil(96/64) = 2 channel groups
+    # the paper's W = floor(128/3) = 42 with G = 64: the fp buffers hold 3W = 126 rows rounded up to
+    # whole 32-row tiles; every filtering event takes 64 quantized slots (one short key group)
+    s = B.logquant_sizes(_cfg(fp_budget=84, group=64, q_capacity=640))
+    assert s.k_fp == 8 * 128 * 128 * 2 and s.pos_fp == 128 * 4
+    assert s.k_meta == 8 * (640 // 64) * 128 * 2 and s.k_codes == 8 * 640 * 128 // 4
+    # W = 85 (floor(256/3)): 128 slots per event
+    assert B._lib.logquant_sizes(C.byref(_cfg(fp_budget=170, group=64, q_capacity=128 * 5)), C.byref(B.lq_sizes())) == B.LQ_OK
+    assert B._lib.logquant_sizes(C.byref(_cfg(fp_budget=170, group=64, q_capacity=85 * 64)), C.byref(B.lq_sizes())) == B.LQ_ERR_SHAPE
 
 
 @pytest.mark.parametrize("kw,status", [
@@ -50,7 +58,7 @@ def test_sizes_match_the_documented_layouts():
     (dict(bits=8), B.LQ_ERR_UNSUPPORTED),
     (dict(d=80), B.LQ_ERR_UNSUPPORTED),
     (dict(group=16), B.LQ_ERR_UNSUPPORTED),
-    (dict(fp_budget=84, q_capacity=42 * 64), B.LQ_ERR_UNSUPPORTED),   # the paper's W = 42: G does not divide W
+    (dict(fp_budget=170, group=64, q_capacity=192), B.LQ_ERR_SHAPE),   # W = 85, G = 64: an event takes 128 slots
     (dict(Hq=30), B.LQ_ERR_SHAPE),
     (dict(B=0), B.LQ_ERR_SHAPE),
     (dict(q_capacity=1000), B.LQ_ERR_SHAPE),
@@ -178,6 +186,21 @@ def test_launch_plans_of_the_five_workloads():
     assert (p4.waves_per_block, p4.splits) == (4, 1)
     # 4-bit codes are not built for 12-wavefront workgroups
     assert B.logquant_decode_plan(_cfg(bits=4, **shapes[3][0]), 512, 130560).waves_per_block == 8
+    # neither is the variant that skips padding slots (window not a multiple of the group size)
+    rag = _cfg(fp_budget=84, group=64, dtype="bf16", q_capacity=3200 * 64)
+    assert B.logquant_decode_plan(rag, 100, 3118 * 64).waves_per_block == 8
+    rag4 = _cfg(B=64, fp_budget=170, group=64, q_capacity=128 * 48)
+    assert B.logquant_decode_plan(rag4, 200, 128 * 46).waves_per_block == 8
+
+
+def test_plan_counts_live_slots_only_and_state_checks_use_slots():
+    # W = 42, G = 64: 64 slots per filtering event, 42 of them hold tokens; key scales and
+    # zero-points exist once per 64 slots
+    cfg = _cfg(fp_budget=84, group=64, q_capacity=640)
+    p = B.logquant_decode_plan(cfg, 100, 5 * 64)
+    assert p.bytes_read == 8 * (100 * 512 + 5 * 42 * (64 + 8) + 5 * 512)
+    assert B._lib.logquant_decode_plan(C.byref(cfg), 100, 5 * 42, C.byref(B.lq_plan())) == B.LQ_ERR_STATE
+    assert B._lib.logquant_decode_plan(C.byref(cfg), 127, 64, C.byref(B.lq_plan())) == B.LQ_ERR_STATE   # n_fp > 3W = 126
 
 
 def test_status_strings():

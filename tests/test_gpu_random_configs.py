@@ -1,6 +1,7 @@
 """Seeded sweep over configurations the hand-picked parity cases do not cover: every
 head dimension, group size, cache type and code width the library accepts, odd
-grouped-query ratios, batch sizes and context lengths around window boundaries.  Each
+grouped-query ratios, batch sizes and context lengths around window boundaries, and
+(the last 16 cases) windows of any length, which the group size does not divide.  Each
 case builds its state with logquant_prefill, continues with fused decode steps, and is
 compared with the oracle (state bit for bit, outputs to tolerance)."""
 import numpy as np
@@ -25,6 +26,25 @@ def _cases():
         bits = int(rng.choice([2, 2, 4]))
         dtype = str(rng.choice(["f16", "bf16"]))
         events = int(rng.integers(0, 7))
+        L = 1 + int(rng.integers(0, 3 * W - 1)) if events == 0 else 3 * W + (events - 1) * W + int(rng.integers(0, W))
+        wl = U.make_wl(B=B, Hq=gh * Hkv, Hkv=Hkv, d=d, G=G, F=2 * W, dtype=dtype, bits=bits,
+                       dist=str(rng.choice(["normal", "laplace"])), sinks=int(rng.choice([0, 0, 4])))
+        steps = int(rng.integers(1, 6))
+        out.append(("%02d_d%d_g%d_w%d_gh%d_hkv%d_b%d_%s_bits%d_L%d" % (i, d, G, W, gh, Hkv, B, dtype, bits, L), wl, L, steps))
+    # windows the group size does not divide (short last key group per filtering event, padding slots)
+    rng = np.random.default_rng(20250320)
+    for i in range(28, 44):
+        d = int(rng.choice([64, 96, 128]))
+        G = int(rng.choice([32, 64, 128]))
+        W = int(rng.integers(1, 3 * G))
+        if W % G == 0:
+            W += 1
+        gh = int(rng.choice([1, 2, 3, 4, 8]))
+        Hkv = int(rng.choice([1, 2, 3]))
+        B = int(rng.choice([1, 1, 2]))
+        bits = int(rng.choice([2, 2, 4]))
+        dtype = str(rng.choice(["f16", "bf16"]))
+        events = int(rng.integers(0, 9))
         L = 1 + int(rng.integers(0, 3 * W - 1)) if events == 0 else 3 * W + (events - 1) * W + int(rng.integers(0, W))
         wl = U.make_wl(B=B, Hq=gh * Hkv, Hkv=Hkv, d=d, G=G, F=2 * W, dtype=dtype, bits=bits,
                        dist=str(rng.choice(["normal", "laplace"])), sinks=int(rng.choice([0, 0, 4])))

@@ -99,3 +99,18 @@ def test_four_bit_hand_evaluated_positions_and_roundtrip():
         words = layout.pack_codes(codes, which, bits=4)
         assert words.shape == (96 // 32 * 64 * (d // 32) * 2,)
         assert np.array_equal(layout.unpack_codes(words, which, 96, d, bits=4), codes)
+
+
+def test_slot_mapping_with_short_key_groups():
+    """Window 42, group 64 (the paper's floor(128/3)): every filtering event takes 64 slots,
+    the first 42 hold its tokens in eviction order; window 85: 128 slots, 85 live."""
+    assert layout.slots_per_event(42, 64) == 64 and layout.slots_per_event(85, 64) == 128 and layout.slots_per_event(64, 64) == 64
+    assert layout.slots_per_event(96, 32) == 96 and layout.slots_per_event(1, 32) == 32
+    s = layout.token_slots(3 * 42, 42, 64)
+    assert s[:42].tolist() == list(range(42)) and s[42] == 64 and s[83] == 105 and s[84] == 128
+    assert np.array_equal(layout.token_slots(200, 50, 25), np.arange(200))     # G divides W: identity
+    rows = np.arange(2 * 85 * 3).reshape(170, 3)
+    out = layout.to_slots(rows, 85, 64, fill=-1)
+    assert out.shape == (256, 3)
+    assert np.array_equal(out[:85], rows[:85]) and (out[85:128] == -1).all()
+    assert np.array_equal(out[128:213], rows[85:]) and (out[213:] == -1).all()

@@ -148,9 +148,37 @@ def test_key_and_value_grouping_axes():
     assert Kh[t, c] == kz[1, c].astype(np.float64) + kc[t, c] * ks[1, c].astype(np.float64)
 
 
-def test_quantize_keys_needs_divisible_window():
-    with pytest.raises(ValueError):
-        Q.quantize_keys(np.zeros((42, 8), np.float32), 32, "f16")
+def test_short_last_key_group_of_an_event():
+    """W = 85 (the paper's floor(256/3)), G = 64: runs of 64 and 21 tokens, each with its
+    own statistics; two events one after the other are addressed per event."""
+    rng = np.random.default_rng(7)
+    W, d, G = 85, 64, 64
+    assert Q.key_group_bounds(W, G) == [(0, 64), (64, 85)] and Q.key_group_bounds(42, 64) == [(0, 42)]
+    K = Q.round_to_T(rng.standard_normal((2 * W, d)).astype(np.float32), "bf16")
+    parts = [Q.quantize_keys(K[e * W:(e + 1) * W], G, "bf16") for e in range(2)]
+    for e, (kc, ks, kz) in enumerate(parts):
+        assert kc.shape == (W, d) and ks.shape == (2, d) and kz.shape == (2, d)
+        for j, (lo, hi) in enumerate(((0, 64), (64, 85))):
+            for c in (0, 31, 63):
+                col = K[e * W + lo:e * W + hi, c]
+                c1, s1, z1 = Q.quantize_groups(col, "bf16")
+                assert kz[j, c] == col.min() == z1 and ks[j, c] == s1
+                assert (kc[lo:hi, c] == c1).all()
+    codes = np.concatenate([p[0] for p in parts])
+    scale = np.concatenate([p[1] for p in parts])
+    zero = np.concatenate([p[2] for p in parts])
+    Kh = Q.dequantize_keys(codes, scale, zero, G, W)
+    for t, grp in ((0, 0), (63, 0), (64, 1), (84, 1), (85, 2), (85 + 64, 3), (169, 3)):
+        want = zero[grp].astype(np.float64) + codes[t] * scale[grp].astype(np.float64)
+        assert np.array_equal(Kh[t], want)
+    # every dequantized value within half a step of the original (scale not rounded down)
+    t = np.arange(2 * W)
+    s_t = scale[(t // W) * 2 + (t % W) // G].astype(np.float64)
+    assert (np.abs(Kh - K) <= s_t / 2 * 1.01 + 1e-6).all()
+    # a group that divides evenly gives what the run-by-run form gives
+    kc, ks, kz = Q.quantize_keys(K[:128], 64, "bf16")
+    c1, s1, z1 = Q.quantize_keys(K[64:128], 64, "bf16")
+    assert np.array_equal(kc[64:], c1) and np.array_equal(ks[1:], s1) and np.array_equal(kz[1:], z1)
 
 
 # ---- 4-bit variant (Sec. 3.2.1, Table 3: the same method at higher precision) ----
