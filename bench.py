@@ -32,6 +32,9 @@ def parse():
     ap.add_argument("--fp-budget", type=int, default=0,
                     help="override the workload's fp budget F = 2W (e.g. 84 or 170: the paper's W = floor(R/3), "
                          "R = 128 / 256, which the group size does not divide)")
+    ap.add_argument("--per-sequence", action="store_true",
+                    help="rows of different lengths (seeded, between L/2 and L) through the per-sequence entry "
+                         "points; reports the same line for that batch")
     ap.add_argument("--unfused", action="store_true",
                     help="time the step as separate append and attention launches instead of logquant_decode_step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -124,6 +127,8 @@ def main():
         wl["name"] += "_F%d" % a.fp_budget
     W, L, dt = wl["F"] // 2, wl["L"], wl["dtype"]
     steps = a.steps or W
+    if a.per_sequence:
+        return main_per_sequence(a, wl, steps)
     plan0 = None
     # enough copies that the rotation's footprint is >= 1 GiB (4x the 256 MB last-level cache)
     cfg_probe = binding.make_config(wl["B"], wl["Hq"], wl["Hkv"], wl["d"], wl["F"], wl["G"], dt,
@@ -268,6 +273,95 @@ def main():
     if not a.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, a.workload)
     print(json.dumps(result), flush=True)
+
+
+def main_per_sequence(a, wl, steps):
+    """The same measurement for a batch whose rows have different lengths: states built by
+    logquant_prefill_seq, a step is logquant_decode_step_seq for every row (append_seq +
+    compress_seq + decode_attn_seq at the steps where some row's window fills)."""
+    import numpy as np
+    import torch
+    from paper_2503_19950_amd import binding, inputs
+    from tests.gpu_util import to_dev
+    B, L, dt, W = wl["B"], wl["L"], wl["dtype"], wl["F"] // 2
+    wl["name"] += "_per_sequence"
+    lengths = [int(x) for x in np.random.default_rng(inputs.SEED).integers(L // 2, L + 1, size=B)]
+    cfg = binding.make_config(B, wl["Hq"], wl["Hkv"], wl["d"], wl["F"], wl["G"], dt, q_capacity(wl), a.bits)
+    tdt = torch.bfloat16 if dt == "bf16" else torch.float16
+    n_in = steps + a.warmup
+    Kd = torch.empty((B, wl["Hkv"], L + n_in, wl["d"]), dtype=tdt, device="cuda:0")
+    Vd = torch.empty_like(Kd)
+    for t0 in range(0, L + n_in, 1 << 14):
+        t1 = min(L + n_in, t0 + (1 << 14))
+        K, V = inputs.batch_kv(a.workload, t0, t1, wl)
+        Kd[:, :, t0:t1] = to_dev(K, dt)
+        Vd[:, :, t0:t1] = to_dev(V, dt)
+    one = binding.logquant_decode_plan_seq(cfg, [2 * W] * B, [(l - 2 * W) // W * slots_per_event(wl) for l in lengths])
+    copies = a.copies or max(2, min(16, -(-(1 << 30) // max(1, one.bytes_read))))
+    Kp, Vp = Kd[:, :, :L].contiguous(), Vd[:, :, :L].contiguous()
+    caches = []
+    for _ in range(copies):
+        dc = binding.DeviceCacheSeq(cfg)
+        dc.prefill_seq(Kp, Vp, lengths)
+        caches.append(dc)
+    del Kp, Vp
+    # step j of a cache: row b's token at its own position lengths[b] + j
+    idx = torch.tensor(lengths, device="cuda:0")
+    newK = torch.stack([Kd[torch.arange(B), :, idx + j] for j in range(-(-n_in // copies))]).unsqueeze(3).contiguous()
+    newV = torch.stack([Vd[torch.arange(B), :, idx + j] for j in range(-(-n_in // copies))]).unsqueeze(3).contiguous()
+    qs = to_dev(np.stack([inputs.queries(a.workload, s, wl) for s in range(n_in)]), dt)
+    out = torch.empty_like(qs[0])
+    stream = torch.cuda.current_stream()
+
+    def run(n, visits):
+        n_sep = 0
+        for s in range(n):
+            dc = caches[s % copies]
+            j = visits[s % copies]
+            visits[s % copies] += 1
+            if all(dc.n_fp[b] + 1 < 3 * W for b in range(B)):
+                dc.decode_step_seq(newK[j], newV[j], qs[s], out)
+            else:
+                dc.append_seq(newK[j], newV[j])
+                dc.compress_seq()
+                dc.decode_attn_seq(qs[s], out)
+                n_sep += 1
+        return n_sep
+
+    visits = [0] * copies
+    run(a.warmup, visits)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    n_sep = run(steps, visits)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
+    nb2b = max(200, steps)
+    for s in range(20):
+        caches[s % copies].decode_attn_seq(qs[0], out)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for s in range(nb2b):
+        caches[s % copies].decode_attn_seq(qs[0], out)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    attn_us = e0.elapsed_time(e1) * 1e3 / nb2b     # includes the small launch that hands over the counts
+    dc = caches[0]
+    plan = binding.logquant_decode_plan_seq(cfg, list(dc.n_fp), list(dc.n_q))
+    achieved = plan.bytes_read / (attn_us * 1e-6) / 1e9
+    tokens = sum(lengths)
+    print(json.dumps({
+        "metric": "decode-attn effective KV tokens/sec", "value": tokens / (ms_per_step * 1e-3), "unit": "KV tokens/s",
+        "n_gpus": 1, "steps": steps, "warmup": a.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": dt, "data": "synthetic",
+        "config": {"workload": wl["name"], "B": B, "Hq": wl["Hq"], "Hkv": wl["Hkv"], "d": wl["d"],
+                   "L_min": min(lengths), "L_max": max(lengths), "L_mean": tokens / B, "group": wl["G"],
+                   "fp_budget": wl["F"], "bits": wl["bits"], "cache_copies_rotated": copies,
+                   "steps_with_a_compress": n_sep, "attn_blocks": plan.blocks, "attn_splits": plan.splits},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "decode attention (per-sequence counts; with the launch that hands them over)",
+                     "us_per_launch": attn_us, "algorithmic_bytes_per_launch": float(plan.bytes_read),
+                     "launches_timed": nb2b}}), flush=True)
 
 
 def read_traffic(workload_name):

@@ -229,6 +229,60 @@ typedef struct {
 } lq_plan;
 lq_status logquant_decode_plan(const lq_config *cfg, int32_t n_fp, int32_t n_q, lq_plan *out);
 
+/* ---- Per-sequence lengths ---------------------------------------------------------
+ * Algorithm 1 runs per sequence (Sec. 2.5): in a batch whose sequences have different
+ * lengths every sequence fills its window, and runs its filtering events, at its own
+ * pace.  The calls below are the ones above with the counts kept per batch row.  The
+ * device buffers and their layouts are those of lq_cache (one q_capacity and one fp
+ * capacity for all rows); cur, n_fp and n_q are HOST arrays of B entries, owned by the
+ * caller and updated by the calls; seq_state is DEVICE scratch of
+ * logquant_seq_state_bytes(cfg) bytes through which each call hands the counts to its
+ * kernels (written by every call, so it carries nothing between calls; a cache serves
+ * one stream at a time).  Errors are detected before anything is launched or changed. */
+typedef struct {
+  void     *k_fp[2];
+  void     *v_fp[2];
+  int32_t  *pos_fp[2];
+  uint32_t *k_codes, *v_codes;
+  void     *k_scale, *k_zero, *v_scale, *v_zero;
+  int32_t  *pos_q;
+  int32_t  *cur;         /* HOST [B]: which fp buffer of row b is live                  */
+  int32_t  *n_fp;        /* HOST [B]: tokens in row b's fp region, 0..3W                */
+  int32_t  *n_q;         /* HOST [B]: slots in row b's quantized region, multiple of WQ */
+  void     *seq_state;   /* DEVICE scratch, logquant_seq_state_bytes(cfg) bytes         */
+} lq_cache_seq;
+
+size_t logquant_seq_state_bytes(const lq_config *cfg);   /* 0 for an invalid config */
+
+/* logquant_prefill with one prompt length per row: L is a HOST array of B lengths,
+ * 0 <= L[b] <= L_stride (else LQ_ERR_SHAPE); k, v : DEVICE [B][Hkv][L_stride][d] T, of which
+ * row b's first L[b] tokens are read.  Requires every row empty (else LQ_ERR_STATE). */
+lq_status logquant_prefill_seq(const lq_config *cfg, lq_cache_seq *cache, const void *k,
+                               const void *v, const int32_t *L, int32_t L_stride, void *stream);
+
+/* logquant_append of one token for every row b with active[b] != 0 (HOST array of B
+ * entries; null: all rows).  k_new, v_new : DEVICE [B][Hkv][1][d] T (rows that sit out are
+ * not read).  Requires n_fp[b] + 1 <= 3W for the active rows (else LQ_ERR_CAPACITY). */
+lq_status logquant_append_seq(const lq_config *cfg, lq_cache_seq *cache, const void *k_new,
+                              const void *v_new, const int32_t *active, void *stream);
+
+/* logquant_compress for every row whose n_fp == 3W, in one launch (no such row: nothing
+ * is launched, LQ_OK).  LQ_ERR_CAPACITY if one of them has no room for the event. */
+lq_status logquant_compress_seq(const lq_config *cfg, lq_cache_seq *cache, void *stream);
+
+/* logquant_decode_attn / logquant_decode_step with per-row counts.  Every row needs at
+ * least one token (else LQ_ERR_STATE); decode_step requires n_fp[b] + 1 < 3W for every
+ * row (else LQ_ERR_STATE: append, compress and attend with the separate calls). */
+lq_status logquant_decode_attn_seq(const lq_config *cfg, const lq_cache_seq *cache, const void *q,
+                                   float softmax_scale, void *out, void *workspace, void *stream);
+lq_status logquant_decode_step_seq(const lq_config *cfg, lq_cache_seq *cache, const void *k_new,
+                                   const void *v_new, const void *q, float softmax_scale, void *out,
+                                   void *workspace, void *stream);
+/* Launch shape for per-row counts (HOST arrays of B entries): planned for the longest row,
+ * bytes_read summed over the rows; fp_waves is the longest row's share. */
+lq_status logquant_decode_plan_seq(const lq_config *cfg, const int32_t *n_fp, const int32_t *n_q,
+                                   lq_plan *out);
+
 const char *logquant_status_string(lq_status s);
 
 #ifdef __cplusplus

@@ -35,6 +35,16 @@ class lq_cache(C.Structure):
                 ("cur", C.c_int32), ("n_fp", C.c_int32), ("n_q", C.c_int32)]
 
 
+class lq_cache_seq(C.Structure):
+    _fields_ = [("k_fp", C.c_void_p * 2), ("v_fp", C.c_void_p * 2), ("pos_fp", C.c_void_p * 2),
+                ("k_codes", C.c_void_p), ("v_codes", C.c_void_p),
+                ("k_scale", C.c_void_p), ("k_zero", C.c_void_p),
+                ("v_scale", C.c_void_p), ("v_zero", C.c_void_p),
+                ("pos_q", C.c_void_p),
+                ("cur", C.POINTER(C.c_int32)), ("n_fp", C.POINTER(C.c_int32)), ("n_q", C.POINTER(C.c_int32)),
+                ("seq_state", C.c_void_p)]
+
+
 class lq_sizes(C.Structure):
     _fields_ = [(n, C.c_size_t) for n in ("k_fp", "v_fp", "pos_fp", "k_codes", "v_codes", "k_meta",
                                           "v_meta", "pos_q", "workspace")]
@@ -48,6 +58,8 @@ class lq_plan(C.Structure):
 EXPORTS = ("logquant_sizes", "logquant_workspace_bytes", "logquant_workspace_init", "logquant_append", "logquant_compress",
            "logquant_prefill", "logquant_prefill_positions", "logquant_decode_attn", "logquant_decode_step",
            "logquant_decode_plan",
+           "logquant_seq_state_bytes", "logquant_prefill_seq", "logquant_append_seq", "logquant_compress_seq",
+           "logquant_decode_attn_seq", "logquant_decode_step_seq", "logquant_decode_plan_seq",
            "logquant_status_string")
 
 if not os.path.exists(LIB_PATH):
@@ -80,6 +92,25 @@ _lib.logquant_decode_step.argtypes = [C.POINTER(lq_config), C.POINTER(lq_cache),
 _lib.logquant_decode_step.restype = C.c_int
 _lib.logquant_decode_plan.argtypes = [C.POINTER(lq_config), C.c_int32, C.c_int32, C.POINTER(lq_plan)]
 _lib.logquant_decode_plan.restype = C.c_int
+_I32P = C.POINTER(C.c_int32)
+_lib.logquant_seq_state_bytes.argtypes = [C.POINTER(lq_config)]
+_lib.logquant_seq_state_bytes.restype = C.c_size_t
+_lib.logquant_prefill_seq.argtypes = [C.POINTER(lq_config), C.POINTER(lq_cache_seq), C.c_void_p, C.c_void_p, _I32P,
+                                      C.c_int32, C.c_void_p]
+_lib.logquant_prefill_seq.restype = C.c_int
+_lib.logquant_append_seq.argtypes = [C.POINTER(lq_config), C.POINTER(lq_cache_seq), C.c_void_p, C.c_void_p, _I32P,
+                                     C.c_void_p]
+_lib.logquant_append_seq.restype = C.c_int
+_lib.logquant_compress_seq.argtypes = [C.POINTER(lq_config), C.POINTER(lq_cache_seq), C.c_void_p]
+_lib.logquant_compress_seq.restype = C.c_int
+_lib.logquant_decode_attn_seq.argtypes = [C.POINTER(lq_config), C.POINTER(lq_cache_seq), C.c_void_p, C.c_float,
+                                          C.c_void_p, C.c_void_p, C.c_void_p]
+_lib.logquant_decode_attn_seq.restype = C.c_int
+_lib.logquant_decode_step_seq.argtypes = [C.POINTER(lq_config), C.POINTER(lq_cache_seq), C.c_void_p, C.c_void_p,
+                                          C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]
+_lib.logquant_decode_step_seq.restype = C.c_int
+_lib.logquant_decode_plan_seq.argtypes = [C.POINTER(lq_config), _I32P, _I32P, C.POINTER(lq_plan)]
+_lib.logquant_decode_plan_seq.restype = C.c_int
 _lib.logquant_status_string.argtypes = [C.c_int]
 _lib.logquant_status_string.restype = C.c_char_p
 
@@ -162,6 +193,47 @@ def logquant_decode_plan(cfg, n_fp, n_q):
     st = _lib.logquant_decode_plan(_p(cfg), int(n_fp), int(n_q), C.byref(out))
     if st != LQ_OK:
         raise LogQuantError(st, "logquant_decode_plan")
+    return out
+
+
+def _i32(values):
+    """Host int32 array (or null) from a Python sequence."""
+    if values is None:
+        return None
+    return (C.c_int32 * len(values))(*[int(x) for x in values])
+
+
+def logquant_seq_state_bytes(cfg):
+    return int(_lib.logquant_seq_state_bytes(_p(cfg)))
+
+
+def logquant_prefill_seq(cfg, cache, k, v, L, L_stride, stream=0):
+    return _lib.logquant_prefill_seq(_p(cfg), _p(cache), _ptr(k), _ptr(v), _i32(L), int(L_stride), stream)
+
+
+def logquant_append_seq(cfg, cache, k_new, v_new, active=None, stream=0):
+    return _lib.logquant_append_seq(_p(cfg), _p(cache), _ptr(k_new), _ptr(v_new), _i32(active), stream)
+
+
+def logquant_compress_seq(cfg, cache, stream=0):
+    return _lib.logquant_compress_seq(_p(cfg), _p(cache), stream)
+
+
+def logquant_decode_attn_seq(cfg, cache, q, softmax_scale, out, workspace, stream=0):
+    return _lib.logquant_decode_attn_seq(_p(cfg), _p(cache), _ptr(q), float(softmax_scale), _ptr(out),
+                                         _ptr(workspace), stream)
+
+
+def logquant_decode_step_seq(cfg, cache, k_new, v_new, q, softmax_scale, out, workspace, stream=0):
+    return _lib.logquant_decode_step_seq(_p(cfg), _p(cache), _ptr(k_new), _ptr(v_new), _ptr(q),
+                                         float(softmax_scale), _ptr(out), _ptr(workspace), stream)
+
+
+def logquant_decode_plan_seq(cfg, n_fp, n_q):
+    out = lq_plan()
+    st = _lib.logquant_decode_plan_seq(_p(cfg), _i32(n_fp), _i32(n_q), C.byref(out))
+    if st != LQ_OK:
+        raise LogQuantError(st, "logquant_decode_plan_seq")
     return out
 
 
@@ -282,3 +354,53 @@ class DeviceCache:
         self._check(logquant_decode_attn(self.cfg, self.c, q, softmax_scale, out, self.workspace,
                                          self._stream()), "logquant_decode_attn")
         return out
+
+
+class DeviceCacheSeq(DeviceCache):
+    """The same device buffers with per-sequence counts (lq_cache_seq): host arrays of B
+    entries for cur / n_fp / n_q and the device scratch the calls pass them through."""
+
+    def __init__(self, cfg, device="cuda:0", poison=False):
+        super().__init__(cfg, device, poison)
+        B = cfg.B
+        self.cur, self.n_fp, self.n_q = ((C.c_int32 * B)() for _ in range(3))
+        self.seq_state = self.torch.zeros(max(logquant_seq_state_bytes(cfg), 16), dtype=self.torch.uint8,
+                                          device=self.device)
+        cs = lq_cache_seq()
+        for name, _ in lq_cache._fields_[:10]:
+            setattr(cs, name, getattr(self.c, name))
+        cs.cur = C.cast(self.cur, _I32P)
+        cs.n_fp = C.cast(self.n_fp, _I32P)
+        cs.n_q = C.cast(self.n_q, _I32P)
+        cs.seq_state = self.seq_state.data_ptr()
+        self.cs = cs
+
+    def prefill_seq(self, K, V, L):
+        assert K.is_contiguous() and V.is_contiguous()
+        self._check(logquant_prefill_seq(self.cfg, self.cs, K, V, L, K.shape[2], self._stream()), "logquant_prefill_seq")
+
+    def append_seq(self, k_new, v_new, active=None):
+        assert k_new.is_contiguous() and v_new.is_contiguous()
+        self._check(logquant_append_seq(self.cfg, self.cs, k_new, v_new, active, self._stream()), "logquant_append_seq")
+
+    def compress_seq(self):
+        self._check(logquant_compress_seq(self.cfg, self.cs, self._stream()), "logquant_compress_seq")
+
+    def decode_attn_seq(self, q, out=None, softmax_scale=0.0):
+        if out is None:
+            out = self.torch.empty_like(q)
+        self._check(logquant_decode_attn_seq(self.cfg, self.cs, q, softmax_scale, out, self.workspace,
+                                             self._stream()), "logquant_decode_attn_seq")
+        return out
+
+    def decode_step_seq(self, k_new, v_new, q, out=None, softmax_scale=0.0):
+        if out is None:
+            out = self.torch.empty_like(q)
+        assert k_new.is_contiguous() and v_new.is_contiguous()
+        self._check(logquant_decode_step_seq(self.cfg, self.cs, k_new, v_new, q, softmax_scale, out, self.workspace,
+                                             self._stream()), "logquant_decode_step_seq")
+        return out
+
+    def view(self, b):
+        """Counts of sequence b as a (cur, n_fp, n_q) triple."""
+        return (self.cur[b], self.n_fp[b], self.n_q[b])

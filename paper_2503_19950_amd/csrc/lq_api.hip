@@ -3,6 +3,8 @@
 // on machines without a GPU as well.
 #include <stdio.h>
 
+#include <vector>
+
 #include "lq_device.h"
 #include "lq_internal.h"
 
@@ -234,6 +236,211 @@ lq_status logquant_decode_step(const lq_config* cfg, lq_cache* cache, const void
                          (hipStream_t)stream) != hipSuccess)
     return LQ_ERR_HIP;
   cache->n_fp = after.n_fp;
+  return LQ_OK;
+}
+
+// ---- per-sequence lengths ---------------------------------------------------------
+// The same kernels; every call writes the B sets of counts its kernels need into
+// cache->seq_state first (same stream, so the order is kept) and then updates the
+// host arrays.
+
+static bool seq_ptrs_ok(const lq_cache_seq* c) {
+  return c && c->k_fp[0] && c->k_fp[1] && c->v_fp[0] && c->v_fp[1] && c->pos_fp[0] && c->pos_fp[1] &&
+         c->k_codes && c->v_codes && c->k_scale && c->k_zero && c->v_scale && c->v_zero && c->pos_q &&
+         c->cur && c->n_fp && c->n_q && c->seq_state;
+}
+
+static lq_status seq_state_ok(const Shape& s, const lq_cache_seq* c) {
+  for (int b = 0; b < s.B; ++b) {
+    if (c->cur[b] != 0 && c->cur[b] != 1) return LQ_ERR_STATE;
+    if (c->n_fp[b] < 0 || c->n_fp[b] > s.full) return LQ_ERR_STATE;
+    if (c->n_q[b] < 0 || c->n_q[b] > s.qcap || c->n_q[b] % s.Wq) return LQ_ERR_STATE;
+  }
+  return LQ_OK;
+}
+
+// the buffers as the launchers take them; counts = the largest over the batch
+static lq_cache seq_view(const Shape& s, const lq_cache_seq* c, const int* n_fp, const int* n_q) {
+  lq_cache v;
+  for (int i = 0; i < 2; ++i) { v.k_fp[i] = c->k_fp[i]; v.v_fp[i] = c->v_fp[i]; v.pos_fp[i] = c->pos_fp[i]; }
+  v.k_codes = c->k_codes; v.v_codes = c->v_codes;
+  v.k_scale = c->k_scale; v.k_zero = c->k_zero; v.v_scale = c->v_scale; v.v_zero = c->v_zero;
+  v.pos_q = c->pos_q;
+  v.cur = 0; v.n_fp = 0; v.n_q = 0;
+  for (int b = 0; b < s.B; ++b) {
+    if (n_fp[b] > v.n_fp) v.n_fp = n_fp[b];
+    if (n_q[b] > v.n_q) v.n_q = n_q[b];
+  }
+  return v;
+}
+
+static SeqState seq_entry(const Shape& s, int n_fp, int n_q, int cur) {
+  SeqState e{};
+  e.n_fp = n_fp; e.n_q = n_q; e.cur = cur; e.n_tok_q = quantized_tokens(s, n_q);
+  return e;
+}
+
+// Plan for the longest sequence; bytes and the fp share of the wavefronts per sequence.
+static void plan_seq(const Shape& s, const int* n_fp, const int* n_q, lq_plan* plan, SeqState* st) {
+  int mf = 0, mq = 0;
+  for (int b = 0; b < s.B; ++b) { if (n_fp[b] > mf) mf = n_fp[b]; if (n_q[b] > mq) mq = n_q[b]; }
+  plan_decode(s, mf, mq, plan, true);
+  const int NW = plan->splits * plan->waves_per_block;
+  int64_t bytes = 0;
+  Shape one = s;
+  one.B = 1;
+  for (int b = 0; b < s.B; ++b) {
+    bytes += cache_bytes_read(one, n_fp[b], n_q[b]);
+    if (st) st[b].nwf = fp_wave_share(s, NW, n_fp[b], n_q[b]);
+  }
+  plan->bytes_read = bytes;
+}
+
+size_t logquant_seq_state_bytes(const lq_config* cfg) {
+  Shape s;
+  if (make_shape(cfg, &s) != LQ_OK) return 0;
+  return (size_t)s.B * sizeof(SeqState);
+}
+
+#define LQ_SEQ_PROLOGUE                                          \
+  Shape s;                                                       \
+  lq_status st_ = make_shape(cfg, &s);                           \
+  if (st_ != LQ_OK) return st_;                                  \
+  if (!seq_ptrs_ok(cache)) return LQ_ERR_NULL;                   \
+  if ((st_ = seq_state_ok(s, cache)) != LQ_OK) return st_;       \
+  std::vector<SeqState> host(s.B)
+
+lq_status logquant_prefill_seq(const lq_config* cfg, lq_cache_seq* cache, const void* k, const void* v,
+                               const int32_t* L, int32_t L_stride, void* stream) {
+  if (!cfg || !cache || !k || !v || !L) return LQ_ERR_NULL;
+  LQ_SEQ_PROLOGUE;
+  if (L_stride < 1) return LQ_ERR_SHAPE;
+  std::vector<int> nf(s.B), nq(s.B);
+  int Emax = 0, fmax = 0;
+  for (int b = 0; b < s.B; ++b) {
+    if (L[b] < 0 || L[b] > L_stride) return LQ_ERR_SHAPE;
+    if (cache->n_fp[b] != 0 || cache->n_q[b] != 0) return LQ_ERR_STATE;
+    const int E = events_after(L[b], s.W);
+    if ((int64_t)E * s.Wq > s.qcap) return LQ_ERR_CAPACITY;
+    nf[b] = L[b] - E * s.W; nq[b] = E * s.Wq;
+    host[b] = seq_entry(s, nf[b], nq[b], cache->cur[b]);
+    host[b].flag = L[b];
+    if (E > Emax) Emax = E;
+    if (nf[b] > fmax) fmax = nf[b];
+  }
+  if (Emax == 0 && fmax == 0) return LQ_OK;   // every prompt is empty
+  clear_stale_error();
+  SeqState* dev = (SeqState*)cache->seq_state;
+  if (launch_seq_upload(dev, host.data(), s.B, (hipStream_t)stream) != hipSuccess) return LQ_ERR_HIP;
+  const lq_cache view = seq_view(s, cache, nf.data(), nq.data());
+  if (launch_prefill(s, view, k, v, L_stride, Emax, fmax, (hipStream_t)stream, dev) != hipSuccess) return LQ_ERR_HIP;
+  for (int b = 0; b < s.B; ++b) { cache->n_fp[b] = nf[b]; cache->n_q[b] = nq[b]; }
+  return LQ_OK;
+}
+
+lq_status logquant_append_seq(const lq_config* cfg, lq_cache_seq* cache, const void* k_new,
+                              const void* v_new, const int32_t* active, void* stream) {
+  if (!cfg || !cache || !k_new || !v_new) return LQ_ERR_NULL;
+  LQ_SEQ_PROLOGUE;
+  int n_active = 0;
+  for (int b = 0; b < s.B; ++b) {
+    const int a = active ? (active[b] != 0) : 1;
+    if (a && cache->n_fp[b] + 1 > s.full) return LQ_ERR_CAPACITY;
+    host[b] = seq_entry(s, cache->n_fp[b] + a, cache->n_q[b], cache->cur[b]);   // counts after the append
+    host[b].flag = a;
+    n_active += a;
+  }
+  if (!n_active) return LQ_OK;
+  clear_stale_error();
+  SeqState* dev = (SeqState*)cache->seq_state;
+  if (launch_seq_upload(dev, host.data(), s.B, (hipStream_t)stream) != hipSuccess) return LQ_ERR_HIP;
+  const lq_cache view = seq_view(s, cache, cache->n_fp, cache->n_q);
+  if (launch_append_seq(s, view, k_new, v_new, dev, (hipStream_t)stream) != hipSuccess) return LQ_ERR_HIP;
+  for (int b = 0; b < s.B; ++b) cache->n_fp[b] = host[b].n_fp;
+  return LQ_OK;
+}
+
+lq_status logquant_compress_seq(const lq_config* cfg, lq_cache_seq* cache, void* stream) {
+  if (!cfg || !cache) return LQ_ERR_NULL;
+  LQ_SEQ_PROLOGUE;
+  int n_items = 0;
+  for (int b = 0; b < s.B; ++b) {
+    host[b] = seq_entry(s, cache->n_fp[b], cache->n_q[b], cache->cur[b]);      // counts before the event
+    if (cache->n_fp[b] == s.full) {
+      if (cache->n_q[b] + s.Wq > s.qcap) return LQ_ERR_CAPACITY;
+      host[n_items++].item = b;
+    }
+  }
+  if (!n_items) return LQ_OK;
+  clear_stale_error();
+  SeqState* dev = (SeqState*)cache->seq_state;
+  if (launch_seq_upload(dev, host.data(), s.B, (hipStream_t)stream) != hipSuccess) return LQ_ERR_HIP;
+  const lq_cache view = seq_view(s, cache, cache->n_fp, cache->n_q);
+  if (launch_compress(s, view, (hipStream_t)stream, dev, n_items) != hipSuccess) return LQ_ERR_HIP;
+  for (int i = 0; i < n_items; ++i) {
+    const int b = host[i].item;
+    cache->cur[b] ^= 1;
+    cache->n_fp[b] = 2 * s.W;
+    cache->n_q[b] += s.Wq;
+  }
+  return LQ_OK;
+}
+
+lq_status logquant_decode_plan_seq(const lq_config* cfg, const int32_t* n_fp, const int32_t* n_q, lq_plan* out) {
+  if (!cfg || !n_fp || !n_q || !out) return LQ_ERR_NULL;
+  Shape s;
+  lq_status st = make_shape(cfg, &s);
+  if (st != LQ_OK) return st;
+  for (int b = 0; b < s.B; ++b)
+    if (n_fp[b] < 0 || n_fp[b] > s.full || n_q[b] < 0 || n_q[b] > s.qcap || n_q[b] % s.Wq || n_fp[b] + n_q[b] < 1)
+      return LQ_ERR_STATE;
+  plan_seq(s, n_fp, n_q, out, nullptr);
+  return LQ_OK;
+}
+
+lq_status logquant_decode_attn_seq(const lq_config* cfg, const lq_cache_seq* cache, const void* q,
+                                   float softmax_scale, void* out, void* workspace, void* stream) {
+  if (!cfg || !cache || !q || !out || !workspace) return LQ_ERR_NULL;
+  LQ_SEQ_PROLOGUE;
+  for (int b = 0; b < s.B; ++b) {
+    if (cache->n_fp[b] + cache->n_q[b] < 1) return LQ_ERR_STATE;
+    host[b] = seq_entry(s, cache->n_fp[b], cache->n_q[b], cache->cur[b]);
+  }
+  lq_plan plan;
+  plan_seq(s, cache->n_fp, cache->n_q, &plan, host.data());
+  if (!(softmax_scale > 0.f)) softmax_scale = 1.0f / sqrtf((float)s.d);
+  clear_stale_error();
+  SeqState* dev = (SeqState*)cache->seq_state;
+  if (launch_seq_upload(dev, host.data(), s.B, (hipStream_t)stream) != hipSuccess) return LQ_ERR_HIP;
+  const lq_cache view = seq_view(s, cache, cache->n_fp, cache->n_q);
+  if (launch_decode_attn(s, view, q, softmax_scale, out, workspace, plan, (hipStream_t)stream, dev) != hipSuccess)
+    return LQ_ERR_HIP;
+  return LQ_OK;
+}
+
+lq_status logquant_decode_step_seq(const lq_config* cfg, lq_cache_seq* cache, const void* k_new,
+                                   const void* v_new, const void* q, float softmax_scale, void* out,
+                                   void* workspace, void* stream) {
+  if (!cfg || !cache || !k_new || !v_new || !q || !out || !workspace) return LQ_ERR_NULL;
+  LQ_SEQ_PROLOGUE;
+  std::vector<int> nf(s.B);
+  for (int b = 0; b < s.B; ++b) {
+    if (cache->n_fp[b] + 1 >= s.full) return LQ_ERR_STATE;   // some window would be full: separate calls
+    nf[b] = cache->n_fp[b] + 1;
+    host[b] = seq_entry(s, nf[b], cache->n_q[b], cache->cur[b]);
+    host[b].flag = 1;
+  }
+  lq_plan plan;
+  plan_seq(s, nf.data(), cache->n_q, &plan, host.data());
+  if (!(softmax_scale > 0.f)) softmax_scale = 1.0f / sqrtf((float)s.d);
+  clear_stale_error();
+  SeqState* dev = (SeqState*)cache->seq_state;
+  if (launch_seq_upload(dev, host.data(), s.B, (hipStream_t)stream) != hipSuccess) return LQ_ERR_HIP;
+  const lq_cache view = seq_view(s, cache, nf.data(), cache->n_q);
+  if (launch_decode_step(s, view, k_new, v_new, q, softmax_scale, out, workspace, plan, (hipStream_t)stream, dev) !=
+      hipSuccess)
+    return LQ_ERR_HIP;
+  for (int b = 0; b < s.B; ++b) cache->n_fp[b] = nf[b];
   return LQ_OK;
 }
 

@@ -23,6 +23,55 @@ __global__ void append_kernel(const uint16_t* __restrict__ k_new, const uint16_t
   if (c == 0 && bh % Hkv == 0) pos_fp[(bh / Hkv) * cap + t] = pos0 + j;
 }
 
+// Per-sequence lengths: sequence b appends (flag set) or sits the call out.  The entry
+// already counts the new row: it becomes fp slot n_fp - 1 of the sequence's live buffer.
+// grid (1, B*Hkv), block d.
+__global__ void append_seq_kernel(const uint16_t* __restrict__ k_new, const uint16_t* __restrict__ v_new,
+                                  uint16_t* k_fp0, uint16_t* v_fp0, int32_t* pos_fp0, uint16_t* k_fp1,
+                                  uint16_t* v_fp1, int32_t* pos_fp1, const SeqState* __restrict__ seq,
+                                  int d, int cap, int Hkv) {
+  const int bh = blockIdx.y, c = threadIdx.x;
+  const SeqState sq = seq[bh / Hkv];
+  if (!sq.flag) return;
+  uint16_t* k_fp = sq.cur ? k_fp1 : k_fp0;
+  uint16_t* v_fp = sq.cur ? v_fp1 : v_fp0;
+  int32_t* pos_fp = sq.cur ? pos_fp1 : pos_fp0;
+  const int t = sq.n_fp - 1;
+  const int64_t src = (int64_t)bh * d + c;
+  const int64_t slice = (int64_t)bh * cap * d;
+  k_fp[slice + k_fp_index(t, c, d >> 5)] = k_new[src];
+  v_fp[slice + v_fp_index(t, c, d >> 4)] = v_new[src];
+  if (c == 0 && bh % Hkv == 0) pos_fp[(bh / Hkv) * cap + t] = t + sq.n_tok_q;
+}
+
+// Hands up to SEQ_CHUNK entries of per-sequence state to the device by value (kernel
+// arguments), so that no host buffer has to outlive the call.
+struct SeqChunk { int base, n; SeqState e[SEQ_CHUNK]; };
+__global__ void seq_upload_kernel(SeqState* dst, const SeqChunk ch) {
+  const int i = threadIdx.x;
+  if (i < ch.n) dst[ch.base + i] = ch.e[i];
+}
+
+hipError_t launch_seq_upload(SeqState* dst, const SeqState* host, int n, hipStream_t st) {
+  for (int base = 0; base < n; base += SEQ_CHUNK) {
+    SeqChunk ch;
+    ch.base = base;
+    ch.n = n - base < SEQ_CHUNK ? n - base : SEQ_CHUNK;
+    for (int i = 0; i < ch.n; ++i) ch.e[i] = host[base + i];
+    for (int i = ch.n; i < SEQ_CHUNK; ++i) ch.e[i] = SeqState{};
+    hipLaunchKernelGGL(seq_upload_kernel, dim3(1), dim3(SEQ_CHUNK), 0, st, dst, ch);
+  }
+  return launch_status(__func__);
+}
+
+hipError_t launch_append_seq(const Shape& s, const lq_cache& c, const void* k_new, const void* v_new,
+                             const SeqState* seq, hipStream_t st) {
+  hipLaunchKernelGGL(append_seq_kernel, dim3(1, s.B * s.Hkv), dim3(s.d), 0, st, (const uint16_t*)k_new,
+                     (const uint16_t*)v_new, (uint16_t*)c.k_fp[0], (uint16_t*)c.v_fp[0], c.pos_fp[0],
+                     (uint16_t*)c.k_fp[1], (uint16_t*)c.v_fp[1], c.pos_fp[1], seq, s.d, s.cap, s.Hkv);
+  return launch_status(__func__);
+}
+
 // Zero the ticket counters at the head of the workspace (a fill kernel rather than
 // a memset node, so the call can be recorded into a HIP graph).
 __global__ void zero_kernel(int* p, int n) {

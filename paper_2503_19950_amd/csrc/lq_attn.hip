@@ -8,10 +8,12 @@
 namespace lq {
 
 hipError_t launch_decode_attn_ref(const Shape& s, const lq_cache& c, const void* q, float scale,
-                                  void* out, void* ws, int splits, hipStream_t st);
+                                  void* out, void* ws, int splits, hipStream_t st, const SeqState* seq);
 hipError_t launch_decode_attn_mfma(const Shape& s, const lq_cache& c, const void* q, float scale,
                                    void* out, void* ws, const lq_plan& plan, hipStream_t st,
-                                   const void* k_new, const void* v_new);
+                                   const void* k_new, const void* v_new, const SeqState* seq);
+hipError_t launch_append_seq(const Shape& s, const lq_cache& c, const void* k_new, const void* v_new,
+                             const SeqState* seq, hipStream_t st);
 
 static int env_int(const char* name, int dflt) {
   const char* v = getenv(name);
@@ -26,11 +28,31 @@ static int env_int(const char* name, int dflt) {
 //     rounds * (units per wavefront + fixed) + merge cost per split,
 // rounds = how many times the chip has to be refilled, fixed = start-up and merge
 // tail of a workgroup expressed in tiles.
-void plan_decode(const Shape& s, int n_fp, int n_q, lq_plan* plan) {
-  const int TQ = (n_q + 63) / 64, TF = (n_fp + 31) / 32;
+static double fp_unit_weight(const Shape& s) {
   const double q_tile_bytes = 64.0 * (s.d * s.bits / 4 + 4 * s.ngc + 4.0 * s.d / s.G);
   const double fp_unit_bytes = 32.0 * 4 * s.d;
-  const double r = fp_unit_bytes / q_tile_bytes;
+  return fp_unit_bytes / q_tile_bytes;
+}
+
+int fp_wave_share(const Shape& s, int NW, int n_fp, int n_q) {
+  const int TQ = (n_q + 63) / 64, TF = (n_fp + 31) / 32;
+  const double r = fp_unit_weight(s);
+  const double units = TQ + r * TF;
+  int nwf = units > 0 ? (int)lround(NW * (r * TF) / units) : 0;
+  if (TF > 0) {
+    if (nwf < 1) nwf = 1;
+    if (nwf > TF) nwf = TF;
+  } else {
+    nwf = 0;
+  }
+  if (TQ > 0 && nwf > NW - 1) nwf = NW - 1;
+  if (TQ == 0) nwf = NW;
+  return nwf;
+}
+
+void plan_decode(const Shape& s, int n_fp, int n_q, lq_plan* plan, bool per_sequence) {
+  const int TQ = (n_q + 63) / 64, TF = (n_fp + 31) / 32;
+  const double r = fp_unit_weight(s);
   const double units = TQ + r * TF;
   const int hb = s.gh % 4 == 0 ? 4 : (s.gh % 2 == 0 ? 2 : 1);
   const int groups = s.B * s.Hkv * (s.gh / hb);
@@ -40,7 +62,8 @@ void plan_decode(const Shape& s, int n_fp, int n_q, lq_plan* plan) {
   const double fixed = 2.5, per_split = 0.02;
   int best_wpb = 8, best_splits = 1;
   double best = 1e300;
-  const bool ragged = s.Wq != s.W;   // padding slots in the quantized region: 8-wavefront kernel only
+  // padding slots in the quantized region, per-sequence counts: 8-wavefront kernel only
+  const bool ragged = s.Wq != s.W || per_sequence;
   for (int wpb = 8; wpb >= 4; wpb -= 4) {
     if (ragged && wpb != 8) continue;
     if (!ragged && force_wpb && force_wpb != 12 && wpb != force_wpb) continue;
@@ -64,15 +87,7 @@ void plan_decode(const Shape& s, int n_fp, int n_q, lq_plan* plan) {
     best_wpb = 12;
   const int splits = best_splits, WPB = best_wpb;
   const int NW = WPB * splits;
-  int nwf = (int)lround(NW * (r * TF) / units);
-  if (TF > 0) {
-    if (nwf < 1) nwf = 1;
-    if (nwf > TF) nwf = TF;
-  } else {
-    nwf = 0;
-  }
-  if (TQ > 0 && nwf > NW - 1) nwf = NW - 1;
-  if (TQ == 0) nwf = NW;
+  const int nwf = fp_wave_share(s, NW, n_fp, n_q);
   plan->splits = splits;
   plan->waves_per_block = WPB;
   plan->blocks = splits * groups;
@@ -87,24 +102,29 @@ static bool plain_attention() {
 }
 
 hipError_t launch_decode_attn(const Shape& s, const lq_cache& c, const void* q, float scale,
-                              void* out, void* ws, const lq_plan& plan, hipStream_t st) {
-  if (plain_attention()) return launch_decode_attn_ref(s, c, q, scale, out, ws, plan.splits, st);
-  return launch_decode_attn_mfma(s, c, q, scale, out, ws, plan, st, nullptr, nullptr);
+                              void* out, void* ws, const lq_plan& plan, hipStream_t st, const SeqState* seq) {
+  if (plain_attention()) return launch_decode_attn_ref(s, c, q, scale, out, ws, plan.splits, st, seq);
+  return launch_decode_attn_mfma(s, c, q, scale, out, ws, plan, st, nullptr, nullptr, seq);
 }
 
 // `c` already counts the new row (n_fp includes it); the row itself is still only in
 // k_new / v_new.
 hipError_t launch_decode_step(const Shape& s, const lq_cache& c, const void* k_new, const void* v_new,
                               const void* q, float scale, void* out, void* ws, const lq_plan& plan,
-                              hipStream_t st) {
+                              hipStream_t st, const SeqState* seq) {
   if (plain_attention()) {
-    lq_cache before = c;
-    before.n_fp -= 1;
-    hipError_t e = launch_append(s, before, k_new, v_new, 1, st);
+    hipError_t e;
+    if (seq) {
+      e = launch_append_seq(s, c, k_new, v_new, seq, st);   // entries already count the new row
+    } else {
+      lq_cache before = c;
+      before.n_fp -= 1;
+      e = launch_append(s, before, k_new, v_new, 1, st);
+    }
     if (e != hipSuccess) return e;
-    return launch_decode_attn_ref(s, c, q, scale, out, ws, plan.splits, st);
+    return launch_decode_attn_ref(s, c, q, scale, out, ws, plan.splits, st, seq);
   }
-  return launch_decode_attn_mfma(s, c, q, scale, out, ws, plan, st, k_new, v_new);
+  return launch_decode_attn_mfma(s, c, q, scale, out, ws, plan, st, k_new, v_new, seq);
 }
 
 }  // namespace lq

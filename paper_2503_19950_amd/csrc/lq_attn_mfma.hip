@@ -58,8 +58,6 @@ typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
 struct AttnParams {
   const uint16_t* q;
-  const uint16_t* k_fp;
-  const uint16_t* v_fp;
   const uint32_t* k_codes;
   const uint32_t* v_codes;
   const uint16_t* k_scale;
@@ -73,9 +71,10 @@ struct AttnParams {
   // becomes fp slot n_fp - 1 (n_fp already counts it)
   const uint16_t* k_new;
   const uint16_t* v_new;
-  uint16_t* k_fp_w;
-  uint16_t* v_fp_w;
-  int32_t* pos_fp;
+  uint16_t* k_fp[2];      // [0]: the live fp buffer (the same for every sequence), or, with
+  uint16_t* v_fp[2];      // per-sequence state, the two buffers, chosen by the sequence's `cur`
+  int32_t* pos_fp[2];
+  const SeqState* seq;    // null: counts below hold for every sequence
   int Hkv;
   int cap, qcap, n_fp, n_q, gh, hb, splits, nwf;
   int W, Wq;          // of every Wq quantized slots (one filtering event) the first W hold tokens
@@ -339,9 +338,10 @@ __device__ __forceinline__ void online_softmax_rows(State<NNT>& st, const float*
 // two workgroups on every compute unit; 12 (three wavefronts per SIMD, at most 168
 // registers) for long contexts, where the extra wavefront hides more than the tighter
 // register budget costs.
-// RAGGED: the group size does not divide the window, so the quantized region has
-// padding slots (built for 8 wavefronts per workgroup only).
-template <bool BF16, int D, int G, int NWB, int BITS, bool RAGGED = false>
+// GENERAL: the variant that also handles padding slots in the quantized region (group
+// size not dividing the window) and per-sequence counts; built for 8 wavefronts per
+// workgroup only.  The other instantiations carry neither check.
+template <bool BF16, int D, int G, int NWB, int BITS, bool GENERAL = false>
 __global__ void __launch_bounds__(64 * NWB, NWB == 12 ? 3 : 2)
 attn_mfma_kernel(const AttnParams P) {
   constexpr int NKC = D / 32, NNT = D / 16, NGC = (D + G - 1) / G;
@@ -376,9 +376,24 @@ attn_mfma_kernel(const AttnParams P) {
   const bool head_ok = g < P.hb;
   const int64_t qrow = ((int64_t)bh * P.gh + hsub * P.hb + (head_ok ? g : 0)) * D;
 
-  const int NW = P.splits * NWB, NWF = P.nwf, NWQ = NW - NWF;
+  // counts and live fp buffer: the same for every sequence, or (per-sequence lengths)
+  // read from the sequence's entry of the state array
+  int n_fp = P.n_fp, n_q = P.n_q, nwf = P.nwf, n_tok_q = P.n_tok_q, cur = 0;
+  if constexpr (GENERAL) {
+    if (P.seq) {
+      const SeqState sq = P.seq[bh / P.Hkv];
+      n_fp = sq.n_fp; n_q = sq.n_q; nwf = sq.nwf; n_tok_q = sq.n_tok_q; cur = sq.cur;
+    }
+  }
+  // (a select between two kernel arguments, not a load that depends on `cur`)
+  uint16_t* k_fp_w = cur ? P.k_fp[1] : P.k_fp[0];
+  uint16_t* v_fp_w = cur ? P.v_fp[1] : P.v_fp[0];
+  int32_t* pos_fp = cur ? P.pos_fp[1] : P.pos_fp[0];
+  const uint16_t* k_fp = k_fp_w;
+  const uint16_t* v_fp = v_fp_w;
+  const int NW = P.splits * NWB, NWF = nwf, NWQ = NW - NWF;
   const int gw = split * NWB + wave;
-  const int TQ = (P.n_q + 63) >> 6, TF = (P.n_fp + 31) >> 5;
+  const int TQ = (n_q + 63) >> 6, TF = (n_fp + 31) >> 5;
   const int64_t part_base = (((int64_t)bh * P.splits + split) * P.gh + hsub * P.hb) * (D + 4);
   State<NNT> st;
 #pragma unroll
@@ -612,13 +627,13 @@ attn_mfma_kernel(const AttnParams P) {
       float s[4], p[4];
 #pragma unroll
       for (int u = 0; u < 4; ++u) s[u] = fmaf(Du[u][0] + Du[u][1], c21, bo[u]);
-      const bool partial = 64 * t + 64 > P.n_q;
+      const bool partial = 64 * t + 64 > n_q;
       if (partial) {
 #pragma unroll
         for (int u = 0; u < 4; ++u)
-          if (64 * t + 16 * u + n16 >= P.n_q) s[u] = -INFINITY;
+          if (64 * t + 16 * u + n16 >= n_q) s[u] = -INFINITY;
       }
-      if constexpr (RAGGED) {
+      if (GENERAL && P.Wq != P.W) {
         // padding slots behind a short key group (zero codes, zero value scales and
         // zero-points): a finite sentinel, so that a tile made of padding only leaves
         // a state whose weight in every later merge is exactly 0
@@ -655,8 +670,8 @@ attn_mfma_kernel(const AttnParams P) {
           for (int r = 0; r < 4; ++r) {
             const int i0 = 2 * r, i1 = 2 * r + 1;
             const int x0 = 16 * ((i0 >> 2) & 1) + 4 * q4 + (i0 & 3), x1 = 16 * ((i1 >> 2) & 1) + 4 * q4 + (i1 & 3);
-            keep[r] = (64 * t + 32 * ks + x0 < P.n_q ? 0x0000FFFFu : 0u) |
-                      (64 * t + 32 * ks + x1 < P.n_q ? 0xFFFF0000u : 0u);
+            keep[r] = (64 * t + 32 * ks + x0 < n_q ? 0x0000FFFFu : 0u) |
+                      (64 * t + 32 * ks + x1 < n_q ? 0xFFFF0000u : 0u);
           }
           vsr.x &= keep[0]; vsr.y &= keep[1]; vsr.z &= keep[2]; vsr.w &= keep[3];
           vzr.x &= keep[0]; vzr.y &= keep[1]; vzr.z &= keep[2]; vzr.w &= keep[3];
@@ -731,8 +746,8 @@ attn_mfma_kernel(const AttnParams P) {
     // ------------------------- original-precision rows -------------------------
     const int wf = gw;
     const int64_t fp_slice = (int64_t)bh * P.cap * D;
-    const uint16_t* kb = P.k_fp + fp_slice + lane * 8;
-    const uint16_t* vb = P.v_fp + fp_slice + lane * 8;
+    const uint16_t* kb = k_fp + fp_slice + lane * 8;
+    const uint16_t* vb = v_fp + fp_slice + lane * 8;
     uint4 qreg[NKC];
 #pragma unroll
     for (int kc = 0; kc < NKC; ++kc) {
@@ -750,12 +765,12 @@ attn_mfma_kernel(const AttnParams P) {
       for (int nt = 0; nt < NNT; ++nt)
         va[nt] = *reinterpret_cast<const uint4*>(vb + ((int64_t)unit * NNT + nt) * 512);
 
-      if (P.k_new && unit == (P.n_fp - 1) >> 5) {
+      if (P.k_new && unit == (n_fp - 1) >> 5) {
         // Fused append.  This wavefront is the only reader of the unit that receives
         // the new row: it takes the row from the caller's buffers instead of the cache
         // (whatever the loads above found in that slot is replaced) and stores it into
         // the cache for the steps to come (once per (b, kv head): head group 0).
-        const int sx = (P.n_fp - 1) & 31, uu_ = sx >> 4;
+        const int sx = (n_fp - 1) & 31, uu_ = sx >> 4;
         const uint16_t* kn = P.k_new + (int64_t)bh * D;
         const uint16_t* vn = P.v_new + (int64_t)bh * D;
         if (n16 == (sx & 15)) {
@@ -764,7 +779,7 @@ attn_mfma_kernel(const AttnParams P) {
             const uint4 x = *reinterpret_cast<const uint4*>(kn + 32 * kc + 8 * q4);
             if (uu_ == 0) ka[0][kc] = x; else ka[1][kc] = x;
             if (hsub == 0)
-              *reinterpret_cast<uint4*>(P.k_fp_w + fp_slice + lane * 8 + ((int64_t)(2 * unit + uu_) * NKC + kc) * 512) = x;
+              *reinterpret_cast<uint4*>(k_fp_w + fp_slice + lane * 8 + ((int64_t)(2 * unit + uu_) * NKC + kc) * 512) = x;
           }
         }
         const int kx = kperm(sx);      // element kx & 7 of the lanes of token octet kx >> 3
@@ -779,11 +794,11 @@ attn_mfma_kernel(const AttnParams P) {
               if (i == wi) w[i] = (w[i] & ~(0xFFFFu << sh)) | (e << sh);
             va[nt] = make_uint4(w[0], w[1], w[2], w[3]);
             if (hsub == 0)
-              P.v_fp_w[fp_slice + (((int64_t)unit * NNT + nt) * 64 + lane) * 8 + (kx & 7)] = (uint16_t)e;
+              v_fp_w[fp_slice + (((int64_t)unit * NNT + nt) * 64 + lane) * 8 + (kx & 7)] = (uint16_t)e;
           }
         }
         if (hsub == 0 && bh % P.Hkv == 0 && lane == 0)
-          P.pos_fp[(bh / P.Hkv) * P.cap + P.n_fp - 1] = P.n_fp - 1 + P.n_tok_q;
+          pos_fp[(bh / P.Hkv) * P.cap + n_fp - 1] = n_fp - 1 + n_tok_q;
       }
 
       floatx4 Du[2] = {floatx4{0.f, 0.f, 0.f, 0.f}, floatx4{0.f, 0.f, 0.f, 0.f}};
@@ -797,7 +812,7 @@ attn_mfma_kernel(const AttnParams P) {
         const floatx4 d = up == 0 ? Du[0] : Du[1];
         const int tok0 = 32 * unit + 16 * up + 4 * q4;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) s[j] = (up < 2 && tok0 + j < P.n_fp) ? d[j] * P.c : -INFINITY;
+        for (int j = 0; j < 4; ++j) s[j] = (up < 2 && tok0 + j < n_fp) ? d[j] * P.c : -INFINITY;
       }
       online_softmax<NNT, false>(st, s, p);
 
@@ -818,13 +833,13 @@ attn_mfma_kernel(const AttnParams P) {
       uint4 a;
       a.x = pack_T<BF16>(av[0], av[1]); a.y = pack_T<BF16>(av[2], av[3]);
       a.z = pack_T<BF16>(av[4], av[5]); a.w = pack_T<BF16>(av[6], av[7]);
-      if (32 * unit + 32 > P.n_fp) {   // slots beyond n_fp hold unspecified bits
+      if (32 * unit + 32 > n_fp) {   // slots beyond n_fp hold unspecified bits
         uint32_t keep[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const int i0 = 2 * r, i1 = 2 * r + 1;
           const int x0 = 16 * ((i0 >> 2) & 1) + 4 * q4 + (i0 & 3), x1 = 16 * ((i1 >> 2) & 1) + 4 * q4 + (i1 & 3);
-          keep[r] = (32 * unit + x0 < P.n_fp ? 0x0000FFFFu : 0u) | (32 * unit + x1 < P.n_fp ? 0xFFFF0000u : 0u);
+          keep[r] = (32 * unit + x0 < n_fp ? 0x0000FFFFu : 0u) | (32 * unit + x1 < n_fp ? 0xFFFF0000u : 0u);
         }
 #pragma unroll
         for (int nt = 0; nt < NNT; ++nt) {
@@ -1040,7 +1055,7 @@ hipError_t launch_combine(const Shape& s, const float* ws, void* out, int splits
 template <bool BF16, int D, int NWB, int BITS>
 static hipError_t launch_mfma_dg(const Shape& s, const AttnParams& P, dim3 grid, hipStream_t st) {
   if constexpr (NWB == 8) {
-    if (s.Wq != s.W) {
+    if (s.Wq != s.W || P.seq) {
       switch (s.G) {
         case 32: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 32, 8, BITS, true>), grid, dim3(512), 0, st, P); break;
         case 64: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 64, 8, BITS, true>), grid, dim3(512), 0, st, P); break;
@@ -1071,16 +1086,21 @@ static hipError_t launch_mfma_t(const Shape& s, const AttnParams& P, dim3 grid, 
   return s.bf16 ? launch_mfma_d<true, NWB, BITS>(s, P, grid, st) : launch_mfma_d<false, NWB, BITS>(s, P, grid, st);
 }
 
+// seq == nullptr: every sequence has the counts of `c` and the live buffer c.cur;
+// otherwise the kernel reads counts, live buffer and fp-wavefront share per sequence
+// from seq[b] (c.n_fp / c.n_q are then the largest counts, which `plan` was made for).
 hipError_t launch_decode_attn_mfma(const Shape& s, const lq_cache& c, const void* q, float scale,
                                    void* out, void* ws, const lq_plan& plan, hipStream_t st,
-                                   const void* k_new, const void* v_new) {
+                                   const void* k_new, const void* v_new, const SeqState* seq) {
   AttnParams P;
   P.k_new = (const uint16_t*)k_new; P.v_new = (const uint16_t*)v_new;
-  P.k_fp_w = (uint16_t*)c.k_fp[c.cur]; P.v_fp_w = (uint16_t*)c.v_fp[c.cur];
-  P.pos_fp = c.pos_fp[c.cur]; P.Hkv = s.Hkv;
+  const int first = seq ? 0 : c.cur;
+  P.k_fp[0] = (uint16_t*)c.k_fp[first]; P.k_fp[1] = (uint16_t*)c.k_fp[first ^ 1];
+  P.v_fp[0] = (uint16_t*)c.v_fp[first]; P.v_fp[1] = (uint16_t*)c.v_fp[first ^ 1];
+  P.pos_fp[0] = c.pos_fp[first]; P.pos_fp[1] = c.pos_fp[first ^ 1];
+  P.seq = seq;
+  P.Hkv = s.Hkv;
   P.q = (const uint16_t*)q;
-  P.k_fp = (const uint16_t*)c.k_fp[c.cur];
-  P.v_fp = (const uint16_t*)c.v_fp[c.cur];
   P.k_codes = c.k_codes; P.v_codes = c.v_codes;
   P.k_scale = (const uint16_t*)c.k_scale; P.k_zero = (const uint16_t*)c.k_zero;
   P.v_scale = (const uint16_t*)c.v_scale; P.v_zero = (const uint16_t*)c.v_zero;
@@ -1095,7 +1115,7 @@ hipError_t launch_decode_attn_mfma(const Shape& s, const lq_cache& c, const void
   static const int dynamic = [] { const char* v = getenv("LOGQUANT_ATTN_DYNAMIC"); return v && *v ? atoi(v) : 1; }();
   P.dynamic = dynamic;
   dim3 grid(plan.splits, s.B * s.Hkv * (s.gh / P.hb));
-  if (s.Wq != s.W) {   // padding slots: the kernel variant that skips them exists for 8 wavefronts only
+  if (s.Wq != s.W || seq) {   // padding slots, per-sequence counts: that kernel variant exists for 8 wavefronts only
     if (plan.waves_per_block != 8) return hipErrorInvalidConfiguration;
     return s.bits == 4 ? launch_mfma_t<8, 4>(s, P, grid, st) : launch_mfma_t<8, 2>(s, P, grid, st);
   }

@@ -18,17 +18,26 @@ __device__ __forceinline__ float wave_sum(float v) {
 // grid (splits, B*Hkv*(gh/HB)), block 256 (4 wavefronts).
 template <bool BF16, int HB>
 __global__ void __launch_bounds__(256)
-attn_ref_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_fp,
-                const uint16_t* __restrict__ v_fp, const uint32_t* __restrict__ k_codes,
+attn_ref_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_fp0,
+                const uint16_t* __restrict__ v_fp0, const uint16_t* __restrict__ k_fp1,
+                const uint16_t* __restrict__ v_fp1, const SeqState* __restrict__ seq,
+                const uint32_t* __restrict__ k_codes,
                 const uint32_t* __restrict__ v_codes, const uint16_t* __restrict__ k_scale,
                 const uint16_t* __restrict__ k_zero, const uint16_t* __restrict__ v_scale,
                 const uint16_t* __restrict__ v_zero, float* __restrict__ ws, int d, int G, int cap,
                 int qcap, int n_fp, int n_q, int gh, int splits, float scale_log2e, int bits, int W,
-                int Wq) {
+                int Wq, int Hkv) {
   __shared__ float sm_o[4][HB][128];
   __shared__ float sm_ml[4][HB][2];
   const int split = blockIdx.x;
   const int hsub = blockIdx.y % (gh / HB), bh = blockIdx.y / (gh / HB);
+  const uint16_t* k_fp = k_fp0;
+  const uint16_t* v_fp = v_fp0;
+  if (seq) {   // per-sequence lengths and live buffers
+    const SeqState sq = seq[bh / Hkv];
+    n_fp = sq.n_fp; n_q = sq.n_q;
+    if (sq.cur) { k_fp = k_fp1; v_fp = v_fp1; }
+  }
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int nkc = d >> 5, nnt = d >> 4, ngc = (d + G - 1) / G;
   const int T = n_fp + n_q;
@@ -127,30 +136,32 @@ hipError_t launch_combine(const Shape& s, const float* ws, void* out, int splits
 
 template <bool BF16, int HB>
 static hipError_t launch_ref_t(const Shape& s, const lq_cache& c, const void* q, float scale,
-                               void* ws, int splits, hipStream_t st) {
+                               void* ws, int splits, hipStream_t st, const SeqState* seq) {
   dim3 grid(splits, s.B * s.Hkv * (s.gh / HB));
+  const int first = seq ? 0 : c.cur;
   hipLaunchKernelGGL((attn_ref_kernel<BF16, HB>), grid, dim3(256), 0, st, (const uint16_t*)q,
-                     (const uint16_t*)c.k_fp[c.cur], (const uint16_t*)c.v_fp[c.cur], c.k_codes,
+                     (const uint16_t*)c.k_fp[first], (const uint16_t*)c.v_fp[first],
+                     (const uint16_t*)c.k_fp[first ^ 1], (const uint16_t*)c.v_fp[first ^ 1], seq, c.k_codes,
                      c.v_codes, (const uint16_t*)c.k_scale, (const uint16_t*)c.k_zero,
                      (const uint16_t*)c.v_scale, (const uint16_t*)c.v_zero, (float*)ws, s.d, s.G,
                      s.cap, s.qcap, c.n_fp, c.n_q, s.gh, splits, scale * 1.4426950408889634f, s.bits,
-                     s.W, s.Wq);
+                     s.W, s.Wq, s.Hkv);
   return launch_status(__func__);
 }
 
 hipError_t launch_decode_attn_ref(const Shape& s, const lq_cache& c, const void* q, float scale,
-                                  void* out, void* ws_all, int splits, hipStream_t st) {
+                                  void* out, void* ws_all, int splits, hipStream_t st, const SeqState* seq) {
   void* ws = (char*)ws_all + counter_bytes(s);
   const int hb = s.gh % 4 == 0 ? 4 : (s.gh % 2 == 0 ? 2 : 1);
   hipError_t e;
   if (s.bf16) {
-    e = hb == 4 ? launch_ref_t<true, 4>(s, c, q, scale, ws, splits, st)
-        : hb == 2 ? launch_ref_t<true, 2>(s, c, q, scale, ws, splits, st)
-                  : launch_ref_t<true, 1>(s, c, q, scale, ws, splits, st);
+    e = hb == 4 ? launch_ref_t<true, 4>(s, c, q, scale, ws, splits, st, seq)
+        : hb == 2 ? launch_ref_t<true, 2>(s, c, q, scale, ws, splits, st, seq)
+                  : launch_ref_t<true, 1>(s, c, q, scale, ws, splits, st, seq);
   } else {
-    e = hb == 4 ? launch_ref_t<false, 4>(s, c, q, scale, ws, splits, st)
-        : hb == 2 ? launch_ref_t<false, 2>(s, c, q, scale, ws, splits, st)
-                  : launch_ref_t<false, 1>(s, c, q, scale, ws, splits, st);
+    e = hb == 4 ? launch_ref_t<false, 4>(s, c, q, scale, ws, splits, st, seq)
+        : hb == 2 ? launch_ref_t<false, 2>(s, c, q, scale, ws, splits, st, seq)
+                  : launch_ref_t<false, 1>(s, c, q, scale, ws, splits, st, seq);
   }
   if (e != hipSuccess) return e;
   return launch_combine(s, (const float*)ws, out, splits, st);

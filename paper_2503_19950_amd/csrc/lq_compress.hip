@@ -340,10 +340,10 @@ __device__ __forceinline__ void compact_rows(
 }
 
 struct CompressParams {
-  const uint16_t *k_old, *v_old;
-  const int32_t* pos_old;
-  uint16_t *k_new, *v_new;
-  int32_t* pos_new;
+  uint16_t *k_buf[2], *v_buf[2];   // the two fp buffers: `cur` is read, the other written
+  int32_t* pos_buf[2];
+  const SeqState* seq;             // null: every sequence, with the counts below
+  int cur;
   uint32_t *k_codes, *v_codes;
   uint16_t *k_scale, *k_zero, *v_scale, *v_zero;
   int32_t* pos_q;
@@ -359,17 +359,28 @@ __global__ void __launch_bounds__(256) compress_kernel(const CompressParams P) {
   extern __shared__ uint16_t sm[];  // [G][d + 4]: the staged rows
   __shared__ float red[8 * 128];    // partial minima [4][d] and maxima [4][d] of the key channels
   __shared__ __attribute__((aligned(16))) uint8_t cb[QG_CODE_BYTES<D, G>];
-  const int nq = (P.W + G - 1) / G, bh = blockIdx.y;
+  const int nq = (P.W + G - 1) / G;
+  int bh = blockIdx.y, cur = P.cur, n_q = P.n_q;
+  if (P.seq) {   // per-sequence lengths: grid row -> (i-th sequence to compress, kv head); counts before the event
+    const int b = P.seq[blockIdx.y / P.Hkv].item;
+    bh = b * P.Hkv + blockIdx.y % P.Hkv;
+    cur = P.seq[b].cur;
+    n_q = P.seq[b].n_q;
+  }
+  // (selects between kernel arguments, not loads that depend on `cur`)
+  const uint16_t* k_old = cur ? P.k_buf[1] : P.k_buf[0];
+  const uint16_t* v_old = cur ? P.v_buf[1] : P.v_buf[0];
+  const int32_t* pos_old = cur ? P.pos_buf[1] : P.pos_buf[0];
   if ((int)blockIdx.x < nq) {
     const int j = blockIdx.x;
     const int ng = min(G, P.W - j * G);
     const int64_t fp_slice = (int64_t)bh * P.cap * D;
-    const FpSource<D, G> src{P.k_old + fp_slice, P.v_old + fp_slice, P.pos_old + (bh / P.Hkv) * P.cap, j, ng, P.cap};
-    quantize_group<BF16, D, G, BITS>(sm, cb, red, src, ng, bh, P.n_q + j * G, P.k_codes, P.v_codes, P.k_scale, P.k_zero,
+    const FpSource<D, G> src{k_old + fp_slice, v_old + fp_slice, pos_old + (bh / P.Hkv) * P.cap, j, ng, P.cap};
+    quantize_group<BF16, D, G, BITS>(sm, cb, red, src, ng, bh, n_q + j * G, P.k_codes, P.v_codes, P.k_scale, P.k_zero,
                                P.v_scale, P.v_zero, P.pos_q, P.qcap, P.Hkv);
   } else {
-    compact_rows(blockIdx.x - nq, bh, P.k_old, P.v_old, P.pos_old, P.k_new, P.v_new, P.pos_new, P.d,
-                 P.W, P.cap, P.Hkv);
+    compact_rows(blockIdx.x - nq, bh, k_old, v_old, pos_old, cur ? P.k_buf[0] : P.k_buf[1],
+                 cur ? P.v_buf[0] : P.v_buf[1], cur ? P.pos_buf[0] : P.pos_buf[1], P.d, P.W, P.cap, P.Hkv);
   }
 }
 
@@ -382,8 +393,9 @@ __global__ void __launch_bounds__(256) compress_kernel(const CompressParams P) {
 // exactly as the filtering step would have, the others place 32 fp rows each.
 struct PrefillParams {
   const uint16_t *k, *v;          // [B*Hkv][L][d]
-  uint16_t *k_fp, *v_fp;
-  int32_t* pos_fp;
+  uint16_t *k_buf[2], *v_buf[2];  // [0]: the buffer to fill (the same for every sequence), or, with
+  int32_t* pos_buf[2];            // per-sequence state, the two buffers, chosen by the sequence's `cur`
+  const SeqState* seq;            // null: E and n_fp below hold for every sequence
   uint32_t *k_codes, *v_codes;
   uint16_t *k_scale, *k_zero, *v_scale, *v_zero;
   int32_t* pos_q;
@@ -397,8 +409,14 @@ __global__ void __launch_bounds__(256) prefill_kernel(const PrefillParams P) {
   __shared__ __attribute__((aligned(16))) uint8_t cb[QG_CODE_BYTES<D, G>];
   __shared__ int posl[128];
   const int tid = threadIdx.x, bh = blockIdx.y;
-  const int per_event = (P.W + G - 1) / G, nqb = P.E * per_event;
-  const int64_t prompt = (int64_t)bh * P.L * D;
+  const int per_event = (P.W + G - 1) / G;
+  int E = P.E, n_fp = P.n_fp, cur = 0;
+  if (P.seq) {   // per-sequence prompt lengths: the grid is sized for the longest
+    const SeqState sq = P.seq[bh / P.Hkv];
+    E = sq.n_q / (per_event * G); n_fp = sq.n_fp; cur = sq.cur;
+  }
+  const int nqb = E * per_event;
+  const int64_t prompt = (int64_t)bh * P.L * D;   // P.L: rows per slice of the prompt tensors
   if ((int)blockIdx.x < nqb) {
     const int ev = blockIdx.x / per_event + 1, j = blockIdx.x % per_event;
     const int ng = min(G, P.W - j * G);
@@ -410,18 +428,22 @@ __global__ void __launch_bounds__(256) prefill_kernel(const PrefillParams P) {
     return;
   }
   const int nb = blockIdx.x - nqb;
+  if (32 * nb >= n_fp) return;
+  uint16_t* k_fp = cur ? P.k_buf[1] : P.k_buf[0];
+  uint16_t* v_fp = cur ? P.v_buf[1] : P.v_buf[0];
+  int32_t* pos_fp = cur ? P.pos_buf[1] : P.pos_buf[0];
   const int nkc = P.d >> 5, nnt = P.d >> 4;
   const int64_t slice = (int64_t)bh * P.cap * P.d;
   if (tid < 32) {
     const int tn = nb * 32 + tid;
-    posl[tid] = tn < P.n_fp ? fp_position(P.E, tn, P.W) : -1;
+    posl[tid] = tn < n_fp ? fp_position(E, tn, P.W) : -1;
   }
   __syncthreads();
   for (int idx = tid; idx < 32 * nkc * 4; idx += 256) {
     const int x = idx & 31, oct = idx >> 5;
     const int p = posl[x];
     if (p >= 0)
-      *reinterpret_cast<uint4*>(P.k_fp + slice + k_fp_index(nb * 32 + x, oct * 8, nkc)) =
+      *reinterpret_cast<uint4*>(k_fp + slice + k_fp_index(nb * 32 + x, oct * 8, nkc)) =
           *reinterpret_cast<const uint4*>(P.k + prompt + (int64_t)p * P.d + oct * 8);
   }
   for (int idx = tid; idx < nnt * 64; idx += 256) {
@@ -434,11 +456,11 @@ __global__ void __launch_bounds__(256) prefill_kernel(const PrefillParams P) {
       const uint32_t e = p >= 0 ? P.v[prompt + (int64_t)p * P.d + 16 * nt + n] : 0u;
       w[i >> 1] |= e << (16 * (i & 1));
     }
-    *reinterpret_cast<uint4*>(P.v_fp + slice + (((int64_t)nb * nnt + nt) * 64 + lane) * 8) =
+    *reinterpret_cast<uint4*>(v_fp + slice + (((int64_t)nb * nnt + nt) * 64 + lane) * 8) =
         make_uint4(w[0], w[1], w[2], w[3]);
   }
   if (bh % P.Hkv == 0 && tid < 32 && posl[tid] >= 0)
-    P.pos_fp[(bh / P.Hkv) * P.cap + nb * 32 + tid] = posl[tid];
+    pos_fp[(bh / P.Hkv) * P.cap + nb * 32 + tid] = posl[tid];
 }
 
 // compile-time head dimension, group size and bit width: the index arithmetic of the staging,
@@ -481,27 +503,33 @@ static void dispatch_dg(const Shape& s, dim3 grid, size_t lds, hipStream_t st, c
   else dispatch_d<L, false>(s, grid, lds, st, P);
 }
 
-hipError_t launch_compress(const Shape& s, const lq_cache& c, hipStream_t st) {
-  const int cur = c.cur, alt = cur ^ 1;
+hipError_t launch_compress(const Shape& s, const lq_cache& c, hipStream_t st, const SeqState* seq, int n_items) {
   CompressParams P;
-  P.k_old = (const uint16_t*)c.k_fp[cur]; P.v_old = (const uint16_t*)c.v_fp[cur]; P.pos_old = c.pos_fp[cur];
-  P.k_new = (uint16_t*)c.k_fp[alt]; P.v_new = (uint16_t*)c.v_fp[alt]; P.pos_new = c.pos_fp[alt];
+  for (int i = 0; i < 2; ++i) {
+    P.k_buf[i] = (uint16_t*)c.k_fp[i]; P.v_buf[i] = (uint16_t*)c.v_fp[i]; P.pos_buf[i] = c.pos_fp[i];
+  }
+  P.seq = seq; P.cur = c.cur;
   P.k_codes = c.k_codes; P.v_codes = c.v_codes;
   P.k_scale = (uint16_t*)c.k_scale; P.k_zero = (uint16_t*)c.k_zero;
   P.v_scale = (uint16_t*)c.v_scale; P.v_zero = (uint16_t*)c.v_zero;
   P.pos_q = c.pos_q;
   P.d = s.d; P.G = s.G; P.W = s.W; P.cap = s.cap; P.qcap = s.qcap; P.n_q = c.n_q; P.Hkv = s.Hkv;
   const size_t lds = (size_t)s.G * (s.d + 4) * sizeof(uint16_t);
-  dim3 grid(s.Wq / s.G + (2 * s.W + 31) / 32, s.B * s.Hkv);
+  dim3 grid(s.Wq / s.G + (2 * s.W + 31) / 32, (seq ? n_items : s.B) * s.Hkv);
   dispatch_dg<CompressLaunch>(s, grid, lds, st, P);
   return launch_status(__func__);
 }
 
 hipError_t launch_prefill(const Shape& s, const lq_cache& c, const void* k, const void* v, int L, int E,
-                          int n_fp, hipStream_t st) {
+                          int n_fp, hipStream_t st, const SeqState* seq) {
   PrefillParams P;
   P.k = (const uint16_t*)k; P.v = (const uint16_t*)v;
-  P.k_fp = (uint16_t*)c.k_fp[c.cur]; P.v_fp = (uint16_t*)c.v_fp[c.cur]; P.pos_fp = c.pos_fp[c.cur];
+  const int first = seq ? 0 : c.cur;
+  for (int i = 0; i < 2; ++i) {
+    P.k_buf[i] = (uint16_t*)c.k_fp[first ^ i]; P.v_buf[i] = (uint16_t*)c.v_fp[first ^ i];
+    P.pos_buf[i] = c.pos_fp[first ^ i];
+  }
+  P.seq = seq;
   P.k_codes = c.k_codes; P.v_codes = c.v_codes;
   P.k_scale = (uint16_t*)c.k_scale; P.k_zero = (uint16_t*)c.k_zero;
   P.v_scale = (uint16_t*)c.v_scale; P.v_zero = (uint16_t*)c.v_zero;

@@ -16,6 +16,22 @@ struct Shape {
   bool bf16;
 };
 
+// Per-sequence lengths: one entry per batch row in device memory, written by the
+// library at the start of every call of the per-sequence entry points and read by
+// that call's kernels (a way to hand B sets of counts to a launch, not state).
+struct SeqState {
+  int n_fp, n_q;      // rows in the fp region, slots in the quantized region
+  int cur;            // which fp buffer is live
+  int nwf;            // attention: wavefronts of a head group that walk the fp rows
+  int n_tok_q;        // tokens held in the n_q slots
+  int item;           // compress: the i-th entry names the i-th sequence that is compressed
+  int flag;           // append: 1 if the sequence takes a token; prefill: prompt length
+  int pad;
+};
+
+constexpr int SEQ_CHUNK = 64;   // entries per upload launch (2 KB of kernel arguments)
+hipError_t launch_seq_upload(SeqState* dst, const SeqState* host, int n, hipStream_t st);
+
 // Fills `s`; returns LQ_OK or the config error.  Pure host arithmetic.
 lq_status make_shape(const lq_config* cfg, Shape* s);
 
@@ -46,14 +62,26 @@ hipError_t launch_status(const char* what);
 // --- launchers (enqueue only) -------------------------------------------------
 hipError_t launch_append(const Shape& s, const lq_cache& c, const void* k_new, const void* v_new,
                          int n_new, hipStream_t st);
-hipError_t launch_compress(const Shape& s, const lq_cache& c, hipStream_t st);
+hipError_t launch_append_seq(const Shape& s, const lq_cache& c, const void* k_new, const void* v_new,
+                             const SeqState* seq, hipStream_t st);
+// seq == nullptr: every sequence is compressed, from the counts of `c`.  Otherwise the
+// n_items sequences named by seq[0..n_items).item, each from its own counts.
+hipError_t launch_compress(const Shape& s, const lq_cache& c, hipStream_t st, const SeqState* seq = nullptr,
+                           int n_items = 0);
+// seq == nullptr: one prompt length L for all.  Otherwise seq[b].flag is the prompt length of
+// sequence b (n_fp / n_q what it leads to), L the row stride of the prompt tensors and
+// E / n_fp the largest values over the batch (they size the grid).
 hipError_t launch_prefill(const Shape& s, const lq_cache& c, const void* k, const void* v, int L, int E,
-                          int n_fp, hipStream_t st);
+                          int n_fp, hipStream_t st, const SeqState* seq = nullptr);
 hipError_t launch_decode_attn(const Shape& s, const lq_cache& c, const void* q, float scale,
-                              void* out, void* ws, const lq_plan& plan, hipStream_t st);
+                              void* out, void* ws, const lq_plan& plan, hipStream_t st,
+                              const SeqState* seq = nullptr);
 hipError_t launch_decode_step(const Shape& s, const lq_cache& c, const void* k_new, const void* v_new,
                               const void* q, float scale, void* out, void* ws, const lq_plan& plan,
-                              hipStream_t st);
-void plan_decode(const Shape& s, int n_fp, int n_q, lq_plan* plan);
+                              hipStream_t st, const SeqState* seq = nullptr);
+void plan_decode(const Shape& s, int n_fp, int n_q, lq_plan* plan, bool per_sequence = false);
+// Wavefronts (of the NW a head group has under `plan`) that walk n_fp fp rows when the
+// quantized region holds n_q slots.
+int fp_wave_share(const Shape& s, int NW, int n_fp, int n_q);
 
 }  // namespace lq

@@ -58,17 +58,18 @@ def _np(t, np_dtype):
     return t.cpu().numpy().view(np_dtype)
 
 
-def check_state(dc, oc, wl, b, h):
-    """Bit-exact comparison of one (b, h) slice of the GPU cache with the oracle."""
+def check_state(dc, oc, wl, b, h, counts=None):
+    """Bit-exact comparison of one (b, h) slice of the GPU cache with the oracle.
+    counts: (cur, n_fp, n_q) of batch row b when the cache keeps them per sequence."""
     d, G, dt = wl["d"], wl["G"], wl["dtype"]
     W = wl["F"] // 2
     cap, qcap = fp_rows_allocated(W), dc.cfg.q_capacity
     nkc, ngc = d // 32, -(-d // G)
     bh = b * wl["Hkv"] + h
-    cur = dc.c.cur
+    cur, have_fp, have_q = counts if counts is not None else (dc.c.cur, dc.c.n_fp, dc.c.n_q)
     # the library counts quantized slots (padding behind short key groups included)
     n_fp, n_q = oc.n_fp, oc.n_q // W * layout.slots_per_event(W, G)
-    assert (dc.c.n_fp, dc.c.n_q) == (n_fp, n_q)
+    assert (have_fp, have_q) == (n_fp, n_q)
     pos_fp = _np(dc.pos_fp[cur], np.int32)[b * cap:b * cap + n_fp]
     assert pos_fp.tolist() == oc.pos_fp, "fp positions"
     pos_q = _np(dc.pos_q, np.int32)[b * qcap:b * qcap + n_q]

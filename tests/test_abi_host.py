@@ -206,3 +206,34 @@ def test_plan_counts_live_slots_only_and_state_checks_use_slots():
 def test_status_strings():
     assert B.logquant_status_string(0) == "ok"
     assert "capacity" in B.logquant_status_string(B.LQ_ERR_CAPACITY)
+
+
+def test_per_sequence_calls_check_their_arguments_without_a_gpu():
+    cfg = _cfg(B=3, fp_budget=64, q_capacity=256)          # W = 32
+    assert B.logquant_seq_state_bytes(cfg) == 3 * 32
+    assert B.logquant_seq_state_bytes(_cfg(d=80)) == 0
+    cs = B.lq_cache_seq()
+    assert B.logquant_compress_seq(cfg, cs) == B.LQ_ERR_NULL
+    assert B.logquant_append_seq(cfg, cs, 4096, 4096) == B.LQ_ERR_NULL
+    for name, _ in B.lq_cache_seq._fields_[3:10]:
+        setattr(cs, name, 4096)
+    for i in range(2):
+        cs.k_fp[i] = cs.v_fp[i] = cs.pos_fp[i] = 4096
+    cs.seq_state = 4096
+    cur, n_fp, n_q = (C.c_int32 * 3)(0, 1, 0), (C.c_int32 * 3)(10, 96, 50), (C.c_int32 * 3)(0, 64, 32)
+    cs.cur, cs.n_fp, cs.n_q = (C.cast(x, C.POINTER(C.c_int32)) for x in (cur, n_fp, n_q))
+    assert B.logquant_decode_step_seq(cfg, cs, 4096, 4096, 4096, 0.0, 4096, 4096) == B.LQ_ERR_STATE   # row 1 is full
+    assert B.logquant_append_seq(cfg, cs, 4096, 4096) == B.LQ_ERR_CAPACITY
+    assert B.logquant_prefill_seq(cfg, cs, 4096, 4096, [5, 5, 5], 8) == B.LQ_ERR_STATE                # rows not empty
+    assert list(n_fp) == [10, 96, 50] and list(n_q) == [0, 64, 32] and list(cur) == [0, 1, 0]
+    n_q[2] = 33                                                                                     # not a multiple of W
+    assert B.logquant_compress_seq(cfg, cs) == B.LQ_ERR_STATE
+    n_q[2] = 32
+    n_q[1] = 256                                                                                    # no room for the event
+    assert B.logquant_compress_seq(cfg, cs) == B.LQ_ERR_CAPACITY
+    # plan: made for the longest row with the general kernel variant (8 wavefronts), bytes summed over the rows
+    p = B.logquant_decode_plan_seq(cfg, [10, 96, 50], [0, 64, 32])
+    assert p.waves_per_block == 8
+    assert p.bytes_read == 8 * ((10 + 96 + 50) * 512 + (64 + 32) * 96)
+    with pytest.raises(B.LogQuantError):
+        B.logquant_decode_plan_seq(cfg, [0, 96, 50], [0, 64, 32])                                   # an empty row

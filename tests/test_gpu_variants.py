@@ -21,10 +21,12 @@ def test_parity_cases_with_forced_kernel_variant(knob):
     env = dict(os.environ)
     k, v = knob.split("=")
     env[k] = v
-    # the second file: windows the group size does not divide (padding slots in the quantized region)
+    # the second file: windows the group size does not divide (padding slots in the quantized region);
+    # the third: per-sequence lengths
     r = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_gpu_parity.py"),
-                        os.path.join(ROOT, "tests", "test_gpu_ragged_window.py"), "-m", "gpu",
-                        "-x", "-q", "-k", CASES + " or w42 or w85 or w50 or w1_g32", "--timeout", "300",
+                        os.path.join(ROOT, "tests", "test_gpu_ragged_window.py"),
+                        os.path.join(ROOT, "tests", "test_gpu_per_sequence.py"), "-m", "gpu",
+                        "-x", "-q", "-k", CASES + " or w42 or w85 or w50 or w1_g32 or per_sequence or sit_out", "--timeout", "300",
                         "--timeout-method", "thread"],
                        cwd=ROOT, env=env, capture_output=True, text=True, timeout=600)
     print(r.stdout[-2000:])
