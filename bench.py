@@ -307,8 +307,9 @@ def main_per_sequence(a, wl, steps):
     del Kp, Vp
     # step j of a cache: row b's token at its own position lengths[b] + j
     idx = torch.tensor(lengths, device="cuda:0")
-    newK = torch.stack([Kd[torch.arange(B), :, idx + j] for j in range(-(-n_in // copies))]).unsqueeze(3).contiguous()
-    newV = torch.stack([Vd[torch.arange(B), :, idx + j] for j in range(-(-n_in // copies))]).unsqueeze(3).contiguous()
+    n_new = -(-a.warmup // copies) + -(-steps // copies)      # visits per cache copy, warm-up included
+    newK = torch.stack([Kd[torch.arange(B), :, idx + j] for j in range(n_new)]).unsqueeze(3).contiguous()
+    newV = torch.stack([Vd[torch.arange(B), :, idx + j] for j in range(n_new)]).unsqueeze(3).contiguous()
     qs = to_dev(np.stack([inputs.queries(a.workload, s, wl) for s in range(n_in)]), dt)
     out = torch.empty_like(qs[0])
     stream = torch.cuda.current_stream()
