@@ -65,7 +65,7 @@ def build_states(wl, cfg_id, copies):
     the way.  Returns (cfg, caches, prefill record)."""
     import torch
     from paper_2503_19950_amd import binding, inputs
-    from tests.gpu_util import to_dev
+    from paper_2503_19950_amd.binding import to_dev
     W, L, dt = wl["F"] // 2, wl["L"], wl["dtype"]
     qcap = q_capacity(wl)
     cfg = binding.make_config(wl["B"], wl["Hq"], wl["Hkv"], wl["d"], wl["F"], wl["G"], dt, qcap,
@@ -116,7 +116,7 @@ def main():
     import numpy as np
     import torch
     from paper_2503_19950_amd import binding, inputs
-    from tests.gpu_util import to_dev
+    from paper_2503_19950_amd.binding import to_dev
 
     wl = dict(inputs.WORKLOADS[a.workload])
     wl["bits"] = a.bits
@@ -282,7 +282,7 @@ def main_per_sequence(a, wl, steps):
     import numpy as np
     import torch
     from paper_2503_19950_amd import binding, inputs
-    from tests.gpu_util import to_dev
+    from paper_2503_19950_amd.binding import to_dev
     B, L, dt, W = wl["B"], wl["L"], wl["dtype"], wl["F"] // 2
     wl["name"] += "_per_sequence"
     lengths = [int(x) for x in np.random.default_rng(inputs.SEED).integers(L // 2, L + 1, size=B)]

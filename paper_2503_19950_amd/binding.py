@@ -237,6 +237,18 @@ def logquant_decode_plan_seq(cfg, n_fp, n_q):
     return out
 
 
+def torch_dtype(dtype):
+    import torch
+    return torch.bfloat16 if dtype == "bf16" else torch.float16
+
+
+def to_dev(x, dtype, device="cuda:0"):
+    """float32 numpy array of exact T values -> device tensor of type T."""
+    import numpy as np
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(x)).to(device).to(torch_dtype(dtype))
+
+
 def make_config(B, Hq, Hkv, d, fp_budget, group, dtype, q_capacity, bits=2):
     return lq_config(B, Hq, Hkv, d, fp_budget, group, bits, LQ_BF16 if dtype == "bf16" else LQ_F16,
                      q_capacity)

@@ -5,20 +5,10 @@ import numpy as np
 from oracle import attention, layout
 from oracle.cache import SliceCache
 from paper_2503_19950_amd import inputs
+from paper_2503_19950_amd.binding import to_dev, torch_dtype  # noqa: F401  (used by the tests through this module)
 
 TOL = {"f16": 2e-3, "bf16": 1e-2}      # max-abs tolerance on attention outputs
 HALF_ULP = {"f16": 2.0 ** -11, "bf16": 2.0 ** -8}   # worst relative half-ulp of the output type
-
-
-def torch_dtype(dtype):
-    import torch
-    return torch.bfloat16 if dtype == "bf16" else torch.float16
-
-
-def to_dev(x, dtype, device="cuda:0"):
-    """float32 numpy array of exact T values -> device tensor of type T."""
-    import torch
-    return torch.from_numpy(np.ascontiguousarray(x)).to(device).to(torch_dtype(dtype))
 
 
 def make_wl(**kw):
