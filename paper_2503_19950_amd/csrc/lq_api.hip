@@ -3,6 +3,7 @@
 // on machines without a GPU as well.
 #include <stdio.h>
 
+#include <algorithm>
 #include <vector>
 
 #include "lq_device.h"
@@ -294,6 +295,14 @@ static void plan_seq(const Shape& s, const int* n_fp, const int* n_q, lq_plan* p
     if (st) st[b].nwf = fp_wave_share(s, NW, n_fp[b], n_q[b]);
   }
   plan->bytes_read = bytes;
+  if (st) {   // rows by decreasing work (stable: equal rows keep their order)
+    std::vector<int> idx(s.B);
+    for (int b = 0; b < s.B; ++b) idx[b] = b;
+    std::stable_sort(idx.begin(), idx.end(), [&](int x, int y) {
+      return cache_bytes_read(one, n_fp[x], n_q[x]) > cache_bytes_read(one, n_fp[y], n_q[y]);
+    });
+    for (int b = 0; b < s.B; ++b) st[b].order = idx[b];
+  }
 }
 
 size_t logquant_seq_state_bytes(const lq_config* cfg) {

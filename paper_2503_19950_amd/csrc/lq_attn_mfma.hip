@@ -371,7 +371,13 @@ attn_mfma_kernel(const AttnParams P) {
     group = (L & 7) + 8 * (r / (int)gridDim.x);
     split = r % (int)gridDim.x;
   }
-  const int hsub = group % nhg, bh = group / nhg;
+  const int hsub = group % nhg;
+  int bh = group / nhg;
+  if constexpr (GENERAL) {
+    // per-sequence lengths: workgroups are dispatched in index order, so the rows are
+    // taken longest first (seq[i].order = the row with the i-th most tokens)
+    if (P.seq) bh = P.seq[bh / P.Hkv].order * P.Hkv + bh % P.Hkv;
+  }
   const int q4 = lane >> 4, n16 = lane & 15, up = n16 >> 2, g = lane & 3;
   const bool head_ok = g < P.hb;
   const int64_t qrow = ((int64_t)bh * P.gh + hsub * P.hb + (head_ok ? g : 0)) * D;

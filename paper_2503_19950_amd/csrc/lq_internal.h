@@ -26,7 +26,7 @@ struct SeqState {
   int n_tok_q;        // tokens held in the n_q slots
   int item;           // compress: the i-th entry names the i-th sequence that is compressed
   int flag;           // append: 1 if the sequence takes a token; prefill: prompt length
-  int pad;
+  int order;          // attention: the i-th entry names the row with the i-th most tokens
 };
 
 constexpr int SEQ_CHUNK = 64;   // entries per upload launch (2 KB of kernel arguments)
