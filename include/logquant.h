@@ -86,7 +86,7 @@ typedef enum {
   LQ_ERR_NULL = 1,        /* a required pointer is null                              */
   LQ_ERR_SHAPE = 2,       /* inconsistent B/Hq/Hkv/d/fp_budget/group/q_capacity       */
   LQ_ERR_UNSUPPORTED = 3, /* valid in the paper but not built: bits not 2 or 4, G not in
-                             {32,64,128}, d not in {64,96,128}                        */
+                             {32,64,128}, d not in {64,96,128}, B*Hq > 65535           */
   LQ_ERR_CAPACITY = 4,    /* fp region or quantized region would overflow             */
   LQ_ERR_STATE = 5,       /* call not allowed in the cache's current state            */
   LQ_ERR_HIP = 6          /* the HIP runtime reported a launch error                  */

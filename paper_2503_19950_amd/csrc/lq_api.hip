@@ -27,6 +27,8 @@ lq_status make_shape(const lq_config* cfg, Shape* s) {
   if (cfg->q_capacity % Wq || cfg->q_capacity % 64) return LQ_ERR_SHAPE;
   if ((int64_t)cfg->B * cfg->Hkv * (int64_t)cfg->q_capacity * cfg->d > ((int64_t)1 << 40))
     return LQ_ERR_SHAPE;
+  // one grid row per (batch row, kv head, head group): the y extent of a launch is 16 bits
+  if ((int64_t)cfg->B * cfg->Hq > 65535) return LQ_ERR_UNSUPPORTED;
   s->B = cfg->B; s->Hq = cfg->Hq; s->Hkv = cfg->Hkv; s->d = cfg->d;
   s->W = W; s->G = cfg->group; s->full = 3 * W; s->cap = (3 * W + 31) / 32 * 32; s->Wq = Wq;
   s->qcap = cfg->q_capacity;

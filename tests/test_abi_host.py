@@ -59,6 +59,7 @@ def test_sizes_match_the_documented_layouts():
     (dict(d=80), B.LQ_ERR_UNSUPPORTED),
     (dict(group=16), B.LQ_ERR_UNSUPPORTED),
     (dict(fp_budget=170, group=64, q_capacity=192), B.LQ_ERR_SHAPE),   # W = 85, G = 64: an event takes 128 slots
+    (dict(B=4096, Hq=16, Hkv=8), B.LQ_ERR_UNSUPPORTED),       # more (row, head) pairs than a launch has grid rows
     (dict(Hq=30), B.LQ_ERR_SHAPE),
     (dict(B=0), B.LQ_ERR_SHAPE),
     (dict(q_capacity=1000), B.LQ_ERR_SHAPE),
