@@ -120,3 +120,80 @@ def test_workload_3_shape_with_4_bit_codes():
     dc = U.build_gpu_prefill(wl, 3, wl["L"])
     assert (dc.c.n_fp, dc.c.n_q) == (512, 130560)
     _check(dc, wl, 3, wl["L"], [(0, 5)])
+
+
+def test_workload_3_shape_with_the_papers_window_42():
+    """Workload 3's size with W = floor(128/3) = 42 (Sec. 3.1) and G = 64: one short key
+    group per filtering event, 3119 events, padding slots in every tile.  State built by
+    logquant_prefill, one slice checked completely, then one fused decode step."""
+    import torch
+    from oracle import attention
+    wl = dict(inputs.WORKLOADS[3], F=84)
+    L = wl["L"]
+    dc = U.build_gpu_prefill(wl, 3, L)
+    E = (L - 3 * 42) // 42 + 1
+    assert (dc.c.n_fp, dc.c.n_q) == (L - E * 42, E * 64)
+    ocs = _check(dc, wl, 3, L, [(0, 2)])
+    K, V = inputs.batch_kv(3, L, L + 1, wl)
+    q = inputs.queries(3, 1, wl)
+    out = dc.decode_step(U.to_dev(K, "bf16"), U.to_dev(V, "bf16"), U.to_dev(q, "bf16"))
+    torch.cuda.synchronize()
+    out = out.float().cpu().numpy()
+    for (b, h), oc in ocs.items():
+        oc.append(K[b, h, 0], V[b, h, 0])
+        U.check_state(dc, oc, wl, b, h)
+        want = attention.decode_attention(oc, q[b, 4 * h:4 * h + 4], None)
+        U.assert_outputs_close(out[b, 4 * h:4 * h + 4], want, "bf16", "fused step (b=%d,h=%d)" % (b, h))
+
+
+def test_workload_4_shape_with_per_sequence_lengths():
+    """Workload 4's batch (64 rows x 8 kv heads) with row lengths between L/2 and L through
+    the per-sequence calls: prefill, a fused step for every row, and the append / compress /
+    attend sequence; three rows (the longest, the shortest, one in between) checked against
+    their own oracles."""
+    import torch
+    from oracle import attention
+    from oracle.cache import SliceCache
+    from paper_2503_19950_amd import binding
+    wl = dict(inputs.WORKLOADS[4])
+    B, L, W, gh = wl["B"], wl["L"], wl["F"] // 2, wl["Hq"] // wl["Hkv"]
+    lengths = [int(x) for x in np.random.default_rng(4).integers(L // 2, L + 1, size=B)]
+    lengths[5], lengths[40] = L, L // 2
+    lengths[22] = 3 * W + 9 * W - 2            # two tokens before its window fills
+    rows = [(5, 0), (40, 7), (22, 3)]
+    steps = 3
+    K, V = U.batch_kv_sampled(4, 0, L + steps, wl, rows)
+    Kd, Vd = U.to_dev(K, "f16"), U.to_dev(V, "f16")
+    cfg = binding.make_config(B, wl["Hq"], wl["Hkv"], wl["d"], wl["F"], wl["G"], "f16", U.q_capacity_for(wl, L + steps))
+    dc = binding.DeviceCacheSeq(cfg)
+    dc.prefill_seq(Kd[:, :, :L].contiguous(), Vd[:, :, :L].contiguous(), lengths)
+    ocs = {}
+    for (b, h) in rows:
+        oc = SliceCache(W, wl["G"], wl["d"], "f16")
+        oc.append_block(K[b, h, :lengths[b]], V[b, h, :lengths[b]])
+        U.check_state(dc, oc, wl, b, h, counts=dc.view(b))
+        ocs[(b, h)] = oc
+    print("  prefill: sampled rows bit-exact", flush=True)
+    kinds = []
+    for s in range(steps):
+        kn = torch.stack([Kd[b, :, lengths[b] + s:lengths[b] + s + 1] for b in range(B)]).contiguous()
+        vn = torch.stack([Vd[b, :, lengths[b] + s:lengths[b] + s + 1] for b in range(B)]).contiguous()
+        q = inputs.queries(4, s, wl)
+        if all(dc.n_fp[b] + 1 < 3 * W for b in range(B)):
+            out = dc.decode_step_seq(kn, vn, U.to_dev(q, "f16"))
+            kinds.append("fused")
+        else:
+            dc.append_seq(kn, vn)
+            dc.compress_seq()
+            out = dc.decode_attn_seq(U.to_dev(q, "f16"))
+            kinds.append("separate")
+        torch.cuda.synchronize()
+        o = out.float().cpu().numpy()
+        for (b, h), oc in ocs.items():
+            oc.append(K[b, h, lengths[b] + s], V[b, h, lengths[b] + s])
+            want = attention.decode_attention(oc, q[b, h * gh:(h + 1) * gh])
+            U.assert_outputs_close(o[b, h * gh:(h + 1) * gh], want, "f16", "step %d (b=%d,h=%d)" % (s, b, h))
+        print("  step", s, kinds[-1], "ok", flush=True)
+    assert "fused" in kinds and "separate" in kinds
+    for (b, h), oc in ocs.items():
+        U.check_state(dc, oc, wl, b, h, counts=dc.view(b))
