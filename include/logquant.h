@@ -17,8 +17,11 @@
  *     updated synchronously by the call that changes them.
  *   - Errors are return codes.  Argument and state errors are detected before
  *     anything is enqueued and leave the cache untouched.
- *   - T is the cache element type (fp16 or bf16); q, out, new tokens, scales
- *     and zero-points are all of type T.
+ *   - T is the cache element type (fp16 or bf16); q, out and new tokens are of type T.
+ *     Scales and zero-points are values of T (see the quantizer below) but are stored
+ *     as fp16 for either T, which is the form the decode kernel's matrix operands need:
+ *     for a bf16 cache the conversion is exact for values in fp16's normal range
+ *     (6.1e-5 <= |x| <= 65504), rounds to nearest below it and overflows above it.
  *
  * Physical layouts.  Row order inside either region carries no meaning for
  * attention (Eq. 3), so every buffer is stored in the order the decode kernel's
@@ -46,8 +49,8 @@
  *                     bits [p, p+4) with p = 4*((c%8)/2) + 16*(c%2)
  *   v_codes     u32   word  ((bh*(q_capacity/32) + t/32)*64 + 16*(k/8) + c%16)*2*NKC + c/16,
  *                     bits [p, p+4) with p = 4*((k%8)/2) + 16*(k%2)
- *   k_scale, k_zero   T   index (bh*(q_capacity/G) + t/G)*d + c      one per channel per G slots
- *   v_scale, v_zero   T   index ((bh*(q_capacity/32) + t/32)*NGC + c/G)*32 + kperm(t % 32)
+ *   k_scale, k_zero   f16 index (bh*(q_capacity/G) + t/G)*d + c      one per channel per G slots
+ *   v_scale, v_zero   f16 index ((bh*(q_capacity/32) + t/32)*NGC + c/G)*32 + kperm(t % 32)
  *   pos_q       i32   index b*q_capacity + t              absolute position of quantized slot t
  *
  * Slots 0..n_fp-1 of the fp region are in the logical order of Algorithm 1's

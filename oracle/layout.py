@@ -111,6 +111,8 @@ def gather_fp(flat, which, n, d):
     return flat[np.broadcast_to(idx, (n, d))]
 
 
+# Scales and zero-points are stored as fp16 bit patterns whatever the cache type (the
+# library's header says so); the scatter functions below only place 16-bit patterns.
 def scatter_k_meta(meta, d, G):
     """meta [n_q/G][d] -> flat (identity order: group-major, channel-minor)."""
     return np.ascontiguousarray(meta).ravel()

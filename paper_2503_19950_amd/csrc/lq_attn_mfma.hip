@@ -163,13 +163,13 @@ __device__ __forceinline__ half2_t pair_to_f16(uint32_t w) {
   if constexpr (BF16) return half2_t{(_Float16)lo_T<true>(w), (_Float16)hi_T<true>(w)};
   else return __builtin_bit_cast(half2_t, w);
 }
-// fp32 accumulate of a two-element dot product of T pairs (exact products)
-template <bool BF16>
-__device__ __forceinline__ float dot2_T(uint32_t a, uint32_t b, float c) {
-  if constexpr (BF16)
-    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c, false);
-  else
-    return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, a), __builtin_bit_cast(half2_t, b), c, false);
+// Scales and zero-points are stored as fp16 whatever the cache type (for a bf16 cache
+// converting them here cost a sixth of the tile loop's instructions): a stored pair is
+// an operand as it is.
+__device__ __forceinline__ half2_t meta_pair(uint32_t w) { return __builtin_bit_cast(half2_t, w); }
+// fp32 accumulate of a two-element dot product of fp16 pairs (exact products)
+__device__ __forceinline__ float dot2_h(half2_t a, half2_t b, float c) {
+  return __builtin_amdgcn_fdot2(a, b, c, false);
 }
 
 template <int CTRL>
@@ -538,10 +538,10 @@ attn_mfma_kernel(const AttnParams P) {
       load_v(A, ta, 1);
     }
 
-    // q of (head q4, channels 8*c8..+7): raw pairs for the bias dot products, and
+    // q of (head q4, channels 8*c8..+7): fp16 pairs for the bias dot products, and
     // fp16 pairs pre-multiplied by 2^(3-2v) (v = pair index) for the q*s operands
     uint32_t qraw[4];
-    half2_t qh[4];
+    half2_t qz[4], qh[4];
     {
       const int64_t qrow_q = ((int64_t)bh * P.gh + hsub * P.hb + (headq_ok ? q4 : 0)) * D;
       uint4 raw = *reinterpret_cast<const uint4*>(P.q + qrow_q + (prep ? 8 * c8 : 0));
@@ -551,6 +551,7 @@ attn_mfma_kernel(const AttnParams P) {
       for (int v = 0; v < 4; ++v) {
         const float f = __builtin_ldexpf(1.f, pos_exp<BITS>(v));
         qh[v] = half2_t{(_Float16)(lo_T<BF16>(qraw[v]) * f), (_Float16)(hi_T<BF16>(qraw[v]) * f)};
+        qz[v] = pair_to_f16<BF16>(qraw[v]);
       }
     }
     const float c21 = P.c * CODE_SCALE<BITS>;   // codes and the pre-scaled q*s together carry 1 / CODE_SCALE
@@ -590,8 +591,8 @@ attn_mfma_kernel(const AttnParams P) {
           uint32_t h[4], l[4];
 #pragma unroll
           for (int v = 0; v < 4; ++v) {
-            bp = dot2_T<BF16>(qraw[v], zw[v], bp);
-            const half2_t sh = pair_to_f16<BF16>(sw[v]);
+            bp = dot2_h(qz[v], meta_pair(zw[v]), bp);
+            const half2_t sh = meta_pair(sw[v]);
             const half2_t hi = qh[v] * sh;
             const half2_t lo = __builtin_elementwise_fma(qh[v], sh, -hi);
             h[v] = __builtin_bit_cast(uint32_t, hi);
@@ -687,8 +688,8 @@ attn_mfma_kernel(const AttnParams P) {
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
           const half2_t pp = __builtin_bit_cast(half2_t, ph[v]);
-          aw[v] = __builtin_bit_cast(uint32_t, pp * pair_to_f16<BF16>(vsw[v]));
-          st.zacc[v] = __builtin_amdgcn_fdot2(pp, pair_to_f16<BF16>(vzw[v]), st.zacc[v], false);
+          aw[v] = __builtin_bit_cast(uint32_t, pp * meta_pair(vsw[v]));
+          st.zacc[v] = __builtin_amdgcn_fdot2(pp, meta_pair(vzw[v]), st.zacc[v], false);
         }
         const uint4 a = make_uint4(aw[0], aw[1], aw[2], aw[3]);
 #pragma unroll

@@ -83,7 +83,7 @@ attn_ref_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_f
                                     : 4 * ((c & 7) >> 1) + 16 * (c & 1);
           const float code = (float)((k_codes[code_slice + w] >> bit) & cmask);
           const int64_t mi = kmeta_slice + (int64_t)(s / G) * d + c;
-          kx[e] = fmaf(code, t2f<BF16>(k_scale[mi]), t2f<BF16>(k_zero[mi]));
+          kx[e] = fmaf(code, t2f<false>(k_scale[mi]), t2f<false>(k_zero[mi]));   // parameters are stored as fp16
         }
         {  // value code, scale, zero
           const int k = kperm(s & 31);
@@ -93,7 +93,7 @@ attn_ref_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_f
                                     : 4 * ((k & 7) >> 1) + 16 * (k & 1);
           const float code = (float)((v_codes[code_slice + w] >> bit) & cmask);
           const int64_t mi = vmeta_slice + v_meta_index(s, c / G, ngc);
-          vx[e] = fmaf(code, t2f<BF16>(v_scale[mi]), t2f<BF16>(v_zero[mi]));
+          vx[e] = fmaf(code, t2f<false>(v_scale[mi]), t2f<false>(v_zero[mi]));
         }
       }
     }

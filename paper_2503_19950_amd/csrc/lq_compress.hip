@@ -11,6 +11,9 @@ namespace lq {
 // One group of values: zero z = min, scale s = T((max - min) / STEPS) with the
 // difference and the quotient correctly rounded to fp32 (the fp64 quotient
 // rounded once more to fp32 equals the IEEE fp32 quotient, 53 >= 2*24 + 2).
+// z and s (values of T) are what the codes are formed with; zt and st are what is
+// stored: the same two values as fp16 (bit-identical for an fp16 cache; for a bf16
+// cache exact whenever the value is in fp16's normal range).
 template <bool BF16, int BITS>
 __device__ __forceinline__ void group_params(float mn, float mx, float* z, float* s, uint16_t* zt,
                                              uint16_t* st) {
@@ -18,10 +21,10 @@ __device__ __forceinline__ void group_params(float mn, float mx, float* z, float
   if (mx == 0.f) mx = 0.f;
   const float diff = mx - mn;
   const float quo = (float)((double)diff / (double)((1 << BITS) - 1));
-  *st = f2t<BF16>(quo);
-  *s = t2f<BF16>(*st);
-  *zt = f2t<BF16>(mn);  // exact: mn is an element of T
-  *z = mn;
+  *s = t2f<BF16>(f2t<BF16>(quo));
+  *z = mn;                  // an element of T
+  *st = f2t<false>(*s);
+  *zt = f2t<false>(mn);
 }
 
 // Encoder of one group: round-half-up of (x - z)/s clamped to 0..2^BITS-1, by

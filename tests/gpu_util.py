@@ -76,12 +76,13 @@ def check_state(dc, oc, wl, b, h, counts=None):
         words = _np(buf, np.uint32)[bh * (qcap // 32) * 64 * nkc * (bits // 2):][:nw]
         want = layout.pack_codes(layout.to_slots(codes, W, G), which, bits=bits)   # padding slots: zero codes
         assert np.array_equal(words, want), "packed codes " + which
+    # scales and zero-points are values of T, stored as fp16 whatever T is
     for buf, meta, name in ((dc.k_scale, oc.K_scale, "k_scale"), (dc.k_zero, oc.K_zero, "k_zero")):
         got = _np(buf, np.uint16)[bh * (qcap // G) * d:][:n_q // G * d]
-        assert np.array_equal(got, inputs.to_bits16(meta, dt).ravel()), name
+        assert np.array_equal(got, inputs.to_bits16(meta, "f16").ravel()), name
     for buf, meta, name in ((dc.v_scale, oc.V_scale, "v_scale"), (dc.v_zero, oc.V_zero, "v_zero")):
         got = _np(buf, np.uint16)[bh * (qcap // 32) * ngc * 32:][:n_q // 32 * ngc * 32]
-        want = layout.scatter_v_meta(layout.to_slots(inputs.to_bits16(meta, dt), W, G), d, G)   # padding: zeros
+        want = layout.scatter_v_meta(layout.to_slots(inputs.to_bits16(meta, "f16"), W, G), d, G)   # padding: zeros
         assert np.array_equal(got, want), name
 
 
