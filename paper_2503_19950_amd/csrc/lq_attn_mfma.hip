@@ -516,7 +516,9 @@ attn_mfma_kernel(const AttnParams P) {
     // With few tiles per wavefront, or no more wavefronts than pools, there is nothing
     // to balance: the schedule is then static (tile wq + v * NWQ) and the atomic is
     // aimed out of range.
-    const bool dyn = P.dynamic && NWQ > NSUB && TQ >= 5 * NWQ;
+    // A single split has no last workgroup that could re-arm the pool counters for the
+    // next launch (it returns before the ticket): static as well.
+    const bool dyn = P.dynamic && P.splits > 1 && NWQ > NSUB && TQ >= 5 * NWQ;
     const int nsub = dyn ? NSUB : NWQ;
     const int sub = wq % nsub;
     int v_static = 0;

@@ -157,3 +157,23 @@ def test_fused_decode_step_equals_append_then_attend(name, wl, L0, steps):
             for (bb, h), oc in ocs.items():
                 want = attention.decode_attention(oc, q_np[bb, h * gh:(h + 1) * gh], None)
                 U.assert_outputs_close(o[bb, h * gh:(h + 1) * gh], want, dt, "step %d (b=%d,h=%d)" % (j, bb, h))
+
+
+def test_repeated_calls_with_one_split_and_many_tiles_per_wavefront():
+    """One workgroup per head group (no context split) with enough tiles per wavefront that
+    a multi-split launch would draw tiles from the pool counters: every call must find the
+    counters as the first one did.  (The shape is chosen so that the planner takes one
+    split; forcing 12 wavefronts per workgroup through the environment is covered by the
+    variant runs.)"""
+    import torch
+    wl = U.make_wl(B=16, Hq=16, Hkv=16, d=64, G=64, F=128)
+    L = 64 * 64 + 128 + 11
+    dc = U.build_gpu_prefill(wl, 190, L)
+    from paper_2503_19950_amd import binding
+    plan = binding.logquant_decode_plan(dc.cfg, dc.c.n_fp, dc.c.n_q)
+    import os
+    if os.environ.get("LOGQUANT_ATTN_WPB", "0") in ("0", "", "12") and not os.environ.get("LOGQUANT_ATTN_SPLITS"):
+        assert plan.splits == 1        # (other forced shapes split the context; the calls are checked all the same)
+    ocs = {(b, h): U.build_oracle(wl, 190, L, b, h) for (b, h) in [(0, 0), (7, 9), (15, 15)]}
+    for rep in range(3):
+        U.check_attention(dc, ocs, wl, inputs.queries(190, rep, wl))

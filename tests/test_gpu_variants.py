@@ -11,7 +11,7 @@ import pytest
 pytestmark = pytest.mark.gpu
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-CASES = "cfg1 or d64_gqa2_ragged or mha_d96_g64_bf16_midwindow or d128_g128_gqa8 or gqa3_odd_ratio or bits4_cfg1 " \
+CASES = "cfg1 or d64_gqa2_ragged or mha_d96_g64_bf16_midwindow or d128_g128_gqa8 or gqa3_odd_ratio or bits4_cfg1 or repeated_calls " \
         "or fused_decode_step"
 
 
