@@ -313,18 +313,24 @@ size_t logquant_seq_state_bytes(const lq_config* cfg) {
   return (size_t)s.B * sizeof(SeqState);
 }
 
-#define LQ_SEQ_PROLOGUE                                          \
-  Shape s;                                                       \
-  lq_status st_ = make_shape(cfg, &s);                           \
-  if (st_ != LQ_OK) return st_;                                  \
-  if (!seq_ptrs_ok(cache)) return LQ_ERR_NULL;                   \
-  if ((st_ = seq_state_ok(s, cache)) != LQ_OK) return st_;       \
-  std::vector<SeqState> host(s.B)
+// Common start of the per-sequence calls: shape, pointers, per-row counts; sizes the host
+// copy of the state array.
+static lq_status seq_begin(const lq_config* cfg, const lq_cache_seq* cache, Shape* s, std::vector<SeqState>* host) {
+  lq_status st = make_shape(cfg, s);
+  if (st != LQ_OK) return st;
+  if (!seq_ptrs_ok(cache)) return LQ_ERR_NULL;
+  if ((st = seq_state_ok(*s, cache)) != LQ_OK) return st;
+  host->assign(s->B, SeqState{});
+  return LQ_OK;
+}
 
 lq_status logquant_prefill_seq(const lq_config* cfg, lq_cache_seq* cache, const void* k, const void* v,
                                const int32_t* L, int32_t L_stride, void* stream) {
   if (!cfg || !cache || !k || !v || !L) return LQ_ERR_NULL;
-  LQ_SEQ_PROLOGUE;
+  Shape s;
+  std::vector<SeqState> host;
+  const lq_status st0 = seq_begin(cfg, cache, &s, &host);
+  if (st0 != LQ_OK) return st0;
   if (L_stride < 1) return LQ_ERR_SHAPE;
   std::vector<int> nf(s.B), nq(s.B);
   int Emax = 0, fmax = 0;
@@ -352,7 +358,10 @@ lq_status logquant_prefill_seq(const lq_config* cfg, lq_cache_seq* cache, const 
 lq_status logquant_append_seq(const lq_config* cfg, lq_cache_seq* cache, const void* k_new,
                               const void* v_new, const int32_t* active, void* stream) {
   if (!cfg || !cache || !k_new || !v_new) return LQ_ERR_NULL;
-  LQ_SEQ_PROLOGUE;
+  Shape s;
+  std::vector<SeqState> host;
+  const lq_status st0 = seq_begin(cfg, cache, &s, &host);
+  if (st0 != LQ_OK) return st0;
   int n_active = 0;
   for (int b = 0; b < s.B; ++b) {
     const int a = active ? (active[b] != 0) : 1;
@@ -373,7 +382,10 @@ lq_status logquant_append_seq(const lq_config* cfg, lq_cache_seq* cache, const v
 
 lq_status logquant_compress_seq(const lq_config* cfg, lq_cache_seq* cache, void* stream) {
   if (!cfg || !cache) return LQ_ERR_NULL;
-  LQ_SEQ_PROLOGUE;
+  Shape s;
+  std::vector<SeqState> host;
+  const lq_status st0 = seq_begin(cfg, cache, &s, &host);
+  if (st0 != LQ_OK) return st0;
   int n_items = 0;
   for (int b = 0; b < s.B; ++b) {
     host[b] = seq_entry(s, cache->n_fp[b], cache->n_q[b], cache->cur[b]);      // counts before the event
@@ -412,7 +424,10 @@ lq_status logquant_decode_plan_seq(const lq_config* cfg, const int32_t* n_fp, co
 lq_status logquant_decode_attn_seq(const lq_config* cfg, const lq_cache_seq* cache, const void* q,
                                    float softmax_scale, void* out, void* workspace, void* stream) {
   if (!cfg || !cache || !q || !out || !workspace) return LQ_ERR_NULL;
-  LQ_SEQ_PROLOGUE;
+  Shape s;
+  std::vector<SeqState> host;
+  const lq_status st0 = seq_begin(cfg, cache, &s, &host);
+  if (st0 != LQ_OK) return st0;
   for (int b = 0; b < s.B; ++b) {
     if (cache->n_fp[b] + cache->n_q[b] < 1) return LQ_ERR_STATE;
     host[b] = seq_entry(s, cache->n_fp[b], cache->n_q[b], cache->cur[b]);
@@ -433,7 +448,10 @@ lq_status logquant_decode_step_seq(const lq_config* cfg, lq_cache_seq* cache, co
                                    const void* v_new, const void* q, float softmax_scale, void* out,
                                    void* workspace, void* stream) {
   if (!cfg || !cache || !k_new || !v_new || !q || !out || !workspace) return LQ_ERR_NULL;
-  LQ_SEQ_PROLOGUE;
+  Shape s;
+  std::vector<SeqState> host;
+  const lq_status st0 = seq_begin(cfg, cache, &s, &host);
+  if (st0 != LQ_OK) return st0;
   std::vector<int> nf(s.B);
   for (int b = 0; b < s.B; ++b) {
     if (cache->n_fp[b] + 1 >= s.full) return LQ_ERR_STATE;   // some window would be full: separate calls
