@@ -199,3 +199,38 @@ def test_workload_4_shape_with_per_sequence_lengths():
     assert "fused" in kinds and "separate" in kinds
     for (b, h), oc in ocs.items():
         U.check_state(dc, oc, wl, b, h, counts=dc.view(b))
+
+
+def test_workload_3_shape_two_rows_of_different_length():
+    """Two rows of workload 3's shape, 131072 and 70001 tokens, through the per-sequence
+    calls: many context splits per head group, tiles drawn from the pool counters, each
+    row with its own tile count; several calls in a row."""
+    import torch
+    from oracle import attention
+    from oracle.cache import SliceCache
+    from paper_2503_19950_amd import binding
+    wl = dict(inputs.WORKLOADS[3], B=2)
+    L, W = wl["L"], wl["F"] // 2
+    lengths = [L, 70001]
+    rows = [(0, 3), (1, 6)]
+    K, V = U.batch_kv_sampled(3, 0, L, wl, rows)
+    cfg = binding.make_config(2, wl["Hq"], wl["Hkv"], wl["d"], wl["F"], wl["G"], "bf16", U.q_capacity_for(wl, L + 8))
+    dc = binding.DeviceCacheSeq(cfg)
+    dc.prefill_seq(U.to_dev(K, "bf16"), U.to_dev(V, "bf16"), lengths)
+    plan = binding.logquant_decode_plan_seq(cfg, list(dc.n_fp), list(dc.n_q))
+    assert plan.splits > 1
+    ocs = {}
+    for (b, h) in rows:
+        oc = SliceCache(W, wl["G"], wl["d"], "bf16")
+        oc.append_block(K[b, h, :lengths[b]], V[b, h, :lengths[b]])
+        U.check_state(dc, oc, wl, b, h, counts=dc.view(b))
+        ocs[(b, h)] = oc
+    for rep in range(3):
+        q = inputs.queries(3, rep, wl)
+        out = dc.decode_attn_seq(U.to_dev(q, "bf16"))
+        torch.cuda.synchronize()
+        o = out.float().cpu().numpy()
+        for (b, h), oc in ocs.items():
+            want = attention.decode_attention(oc, q[b, 4 * h:4 * h + 4])
+            U.assert_outputs_close(o[b, 4 * h:4 * h + 4], want, "bf16", "call %d (b=%d,h=%d)" % (rep, b, h))
+        print("  call", rep, "ok", flush=True)
