@@ -46,6 +46,9 @@ CASES = [
      [700, 191, 64 * 9], 40),
     ("w42_g64_padding_slots", U.make_wl(B=3, Hq=8, Hkv=2, d=128, G=64, F=84, dtype="bf16"), [500, 125, 3], 50),
     ("bits4_one_row_empty_prompt", U.make_wl(B=3, Hq=4, Hkv=2, d=64, G=32, F=64, bits=4), [0, 333, 96], 35),
+    # more rows than one hand-over launch carries (64)
+    ("b70_d64", U.make_wl(B=70, Hq=2, Hkv=1, d=64, G=32, F=64),
+     [int(x) for x in np.random.default_rng(70).integers(1, 400, size=70)], 34),
 ]
 
 
