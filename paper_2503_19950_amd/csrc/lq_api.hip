@@ -315,6 +315,16 @@ size_t logquant_seq_state_bytes(const lq_config* cfg) {
 
 // Common start of the per-sequence calls: shape, pointers, per-row counts; sizes the host
 // copy of the state array.
+// Makes the state reachable for the launch: in its arguments (small batches) or through
+// the device array, which is then filled first on the same stream.
+static hipError_t seq_hand_over(const lq_cache_seq* cache, const std::vector<SeqState>& host, hipStream_t st, SeqArg* arg) {
+  arg->dev = (const SeqState*)cache->seq_state;
+  arg->host = host.data();
+  arg->n = (int)host.size();
+  if (arg->in_args()) return hipSuccess;
+  return launch_seq_upload((SeqState*)cache->seq_state, host.data(), arg->n, st);
+}
+
 static lq_status seq_begin(const lq_config* cfg, const lq_cache_seq* cache, Shape* s, std::vector<SeqState>* host) {
   lq_status st = make_shape(cfg, s);
   if (st != LQ_OK) return st;
@@ -347,10 +357,10 @@ lq_status logquant_prefill_seq(const lq_config* cfg, lq_cache_seq* cache, const 
   }
   if (Emax == 0 && fmax == 0) return LQ_OK;   // every prompt is empty
   clear_stale_error();
-  SeqState* dev = (SeqState*)cache->seq_state;
-  if (launch_seq_upload(dev, host.data(), s.B, (hipStream_t)stream) != hipSuccess) return LQ_ERR_HIP;
+  SeqArg arg;
+  if (seq_hand_over(cache, host, (hipStream_t)stream, &arg) != hipSuccess) return LQ_ERR_HIP;
   const lq_cache view = seq_view(s, cache, nf.data(), nq.data());
-  if (launch_prefill(s, view, k, v, L_stride, Emax, fmax, (hipStream_t)stream, dev) != hipSuccess) return LQ_ERR_HIP;
+  if (launch_prefill(s, view, k, v, L_stride, Emax, fmax, (hipStream_t)stream, &arg) != hipSuccess) return LQ_ERR_HIP;
   for (int b = 0; b < s.B; ++b) { cache->n_fp[b] = nf[b]; cache->n_q[b] = nq[b]; }
   return LQ_OK;
 }
@@ -372,10 +382,10 @@ lq_status logquant_append_seq(const lq_config* cfg, lq_cache_seq* cache, const v
   }
   if (!n_active) return LQ_OK;
   clear_stale_error();
-  SeqState* dev = (SeqState*)cache->seq_state;
-  if (launch_seq_upload(dev, host.data(), s.B, (hipStream_t)stream) != hipSuccess) return LQ_ERR_HIP;
+  SeqArg arg;
+  if (seq_hand_over(cache, host, (hipStream_t)stream, &arg) != hipSuccess) return LQ_ERR_HIP;
   const lq_cache view = seq_view(s, cache, cache->n_fp, cache->n_q);
-  if (launch_append_seq(s, view, k_new, v_new, dev, (hipStream_t)stream) != hipSuccess) return LQ_ERR_HIP;
+  if (launch_append_seq(s, view, k_new, v_new, &arg, (hipStream_t)stream) != hipSuccess) return LQ_ERR_HIP;
   for (int b = 0; b < s.B; ++b) cache->n_fp[b] = host[b].n_fp;
   return LQ_OK;
 }
@@ -396,10 +406,10 @@ lq_status logquant_compress_seq(const lq_config* cfg, lq_cache_seq* cache, void*
   }
   if (!n_items) return LQ_OK;
   clear_stale_error();
-  SeqState* dev = (SeqState*)cache->seq_state;
-  if (launch_seq_upload(dev, host.data(), s.B, (hipStream_t)stream) != hipSuccess) return LQ_ERR_HIP;
+  SeqArg arg;
+  if (seq_hand_over(cache, host, (hipStream_t)stream, &arg) != hipSuccess) return LQ_ERR_HIP;
   const lq_cache view = seq_view(s, cache, cache->n_fp, cache->n_q);
-  if (launch_compress(s, view, (hipStream_t)stream, dev, n_items) != hipSuccess) return LQ_ERR_HIP;
+  if (launch_compress(s, view, (hipStream_t)stream, &arg, n_items) != hipSuccess) return LQ_ERR_HIP;
   for (int i = 0; i < n_items; ++i) {
     const int b = host[i].item;
     cache->cur[b] ^= 1;
@@ -436,10 +446,10 @@ lq_status logquant_decode_attn_seq(const lq_config* cfg, const lq_cache_seq* cac
   plan_seq(s, cache->n_fp, cache->n_q, &plan, host.data());
   if (!(softmax_scale > 0.f)) softmax_scale = 1.0f / sqrtf((float)s.d);
   clear_stale_error();
-  SeqState* dev = (SeqState*)cache->seq_state;
-  if (launch_seq_upload(dev, host.data(), s.B, (hipStream_t)stream) != hipSuccess) return LQ_ERR_HIP;
+  SeqArg arg;
+  if (seq_hand_over(cache, host, (hipStream_t)stream, &arg) != hipSuccess) return LQ_ERR_HIP;
   const lq_cache view = seq_view(s, cache, cache->n_fp, cache->n_q);
-  if (launch_decode_attn(s, view, q, softmax_scale, out, workspace, plan, (hipStream_t)stream, dev) != hipSuccess)
+  if (launch_decode_attn(s, view, q, softmax_scale, out, workspace, plan, (hipStream_t)stream, &arg) != hipSuccess)
     return LQ_ERR_HIP;
   return LQ_OK;
 }
@@ -463,10 +473,10 @@ lq_status logquant_decode_step_seq(const lq_config* cfg, lq_cache_seq* cache, co
   plan_seq(s, nf.data(), cache->n_q, &plan, host.data());
   if (!(softmax_scale > 0.f)) softmax_scale = 1.0f / sqrtf((float)s.d);
   clear_stale_error();
-  SeqState* dev = (SeqState*)cache->seq_state;
-  if (launch_seq_upload(dev, host.data(), s.B, (hipStream_t)stream) != hipSuccess) return LQ_ERR_HIP;
+  SeqArg arg;
+  if (seq_hand_over(cache, host, (hipStream_t)stream, &arg) != hipSuccess) return LQ_ERR_HIP;
   const lq_cache view = seq_view(s, cache, nf.data(), cache->n_q);
-  if (launch_decode_step(s, view, k_new, v_new, q, softmax_scale, out, workspace, plan, (hipStream_t)stream, dev) !=
+  if (launch_decode_step(s, view, k_new, v_new, q, softmax_scale, out, workspace, plan, (hipStream_t)stream, &arg) !=
       hipSuccess)
     return LQ_ERR_HIP;
   for (int b = 0; b < s.B; ++b) cache->n_fp[b] = nf[b];

@@ -29,9 +29,11 @@ __global__ void append_kernel(const uint16_t* __restrict__ k_new, const uint16_t
 __global__ void append_seq_kernel(const uint16_t* __restrict__ k_new, const uint16_t* __restrict__ v_new,
                                   uint16_t* k_fp0, uint16_t* v_fp0, int32_t* pos_fp0, uint16_t* k_fp1,
                                   uint16_t* v_fp1, int32_t* pos_fp1, const SeqState* __restrict__ seq,
-                                  int d, int cap, int Hkv) {
+                                  int mode, int d, int cap, int Hkv, const SeqInline S) {
   const int bh = blockIdx.y, c = threadIdx.x;
-  const SeqState sq = seq[bh / Hkv];
+  // argument block: nine pointers, four ints, then S
+  const SeqState sq = mode == 1 ? seq_load(seq_in_args(args_offset_after(9 * 8 + 4 * 4)), bh / Hkv) : seq[bh / Hkv];
+  (void)S;
   if (!sq.flag) return;
   uint16_t* k_fp = sq.cur ? k_fp1 : k_fp0;
   uint16_t* v_fp = sq.cur ? v_fp1 : v_fp0;
@@ -65,10 +67,13 @@ hipError_t launch_seq_upload(SeqState* dst, const SeqState* host, int n, hipStre
 }
 
 hipError_t launch_append_seq(const Shape& s, const lq_cache& c, const void* k_new, const void* v_new,
-                             const SeqState* seq, hipStream_t st) {
+                             const SeqArg* seq, hipStream_t st) {
+  SeqInline S;
+  fill_inline(&S, seq);
   hipLaunchKernelGGL(append_seq_kernel, dim3(1, s.B * s.Hkv), dim3(s.d), 0, st, (const uint16_t*)k_new,
                      (const uint16_t*)v_new, (uint16_t*)c.k_fp[0], (uint16_t*)c.v_fp[0], c.pos_fp[0],
-                     (uint16_t*)c.k_fp[1], (uint16_t*)c.v_fp[1], c.pos_fp[1], seq, s.d, s.cap, s.Hkv);
+                     (uint16_t*)c.k_fp[1], (uint16_t*)c.v_fp[1], c.pos_fp[1], seq->dev, seq_mode(seq), s.d,
+                     s.cap, s.Hkv, S);
   return launch_status(__func__);
 }
 

@@ -8,12 +8,12 @@
 namespace lq {
 
 hipError_t launch_decode_attn_ref(const Shape& s, const lq_cache& c, const void* q, float scale,
-                                  void* out, void* ws, int splits, hipStream_t st, const SeqState* seq);
+                                  void* out, void* ws, int splits, hipStream_t st, const SeqArg* seq);
 hipError_t launch_decode_attn_mfma(const Shape& s, const lq_cache& c, const void* q, float scale,
                                    void* out, void* ws, const lq_plan& plan, hipStream_t st,
-                                   const void* k_new, const void* v_new, const SeqState* seq);
+                                   const void* k_new, const void* v_new, const SeqArg* seq);
 hipError_t launch_append_seq(const Shape& s, const lq_cache& c, const void* k_new, const void* v_new,
-                             const SeqState* seq, hipStream_t st);
+                             const SeqArg* seq, hipStream_t st);
 
 static int env_int(const char* name, int dflt) {
   const char* v = getenv(name);
@@ -102,7 +102,7 @@ static bool plain_attention() {
 }
 
 hipError_t launch_decode_attn(const Shape& s, const lq_cache& c, const void* q, float scale,
-                              void* out, void* ws, const lq_plan& plan, hipStream_t st, const SeqState* seq) {
+                              void* out, void* ws, const lq_plan& plan, hipStream_t st, const SeqArg* seq) {
   if (plain_attention()) return launch_decode_attn_ref(s, c, q, scale, out, ws, plan.splits, st, seq);
   return launch_decode_attn_mfma(s, c, q, scale, out, ws, plan, st, nullptr, nullptr, seq);
 }
@@ -111,7 +111,7 @@ hipError_t launch_decode_attn(const Shape& s, const lq_cache& c, const void* q, 
 // k_new / v_new.
 hipError_t launch_decode_step(const Shape& s, const lq_cache& c, const void* k_new, const void* v_new,
                               const void* q, float scale, void* out, void* ws, const lq_plan& plan,
-                              hipStream_t st, const SeqState* seq) {
+                              hipStream_t st, const SeqArg* seq) {
   if (plain_attention()) {
     hipError_t e;
     if (seq) {

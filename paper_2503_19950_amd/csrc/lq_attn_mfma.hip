@@ -74,7 +74,8 @@ struct AttnParams {
   uint16_t* k_fp[2];      // [0]: the live fp buffer (the same for every sequence), or, with
   uint16_t* v_fp[2];      // per-sequence state, the two buffers, chosen by the sequence's `cur`
   int32_t* pos_fp[2];
-  const SeqState* seq;    // null: counts below hold for every sequence
+  const SeqState* seq;    // device array of per-sequence state (seq_mode 2)
+  int seq_mode;           // 0: counts below hold for every sequence; 1: state in the kernel arguments
   int Hkv;
   int cap, qcap, n_fp, n_q, gh, hb, splits, nwf;
   int W, Wq;          // of every Wq quantized slots (one filtering event) the first W hold tokens
@@ -341,9 +342,13 @@ __device__ __forceinline__ void online_softmax_rows(State<NNT>& st, const float*
 // GENERAL: the variant that also handles padding slots in the quantized region (group
 // size not dividing the window) and per-sequence counts; built for 8 wavefronts per
 // workgroup only.  The other instantiations carry neither check.
+// per-sequence state in the kernel arguments: only the general instantiation has any
+template <bool GENERAL> struct SeqArgs {};
+template <> struct SeqArgs<true> { SeqState e[SEQ_CHUNK]; };
+
 template <bool BF16, int D, int G, int NWB, int BITS, bool GENERAL = false>
 __global__ void __launch_bounds__(64 * NWB, NWB == 12 ? 3 : 2)
-attn_mfma_kernel(const AttnParams P) {
+attn_mfma_kernel(const AttnParams P, const SeqArgs<GENERAL> S) {
   constexpr int NKC = D / 32, NNT = D / 16, NGC = (D + G - 1) / G;
   constexpr int WPL = NKC * (BITS / 2);           // code words per lane and 32-slot block
   constexpr int NGRP = G < 64 ? 64 / G : 1;     // key groups per 64-token tile
@@ -376,7 +381,11 @@ attn_mfma_kernel(const AttnParams P) {
   if constexpr (GENERAL) {
     // per-sequence lengths: workgroups are dispatched in index order, so the rows are
     // taken longest first (seq[i].order = the row with the i-th most tokens)
-    if (P.seq) bh = P.seq[bh / P.Hkv].order * P.Hkv + bh % P.Hkv;
+    if (P.seq_mode) {
+      const int i = bh / P.Hkv;
+      bh = (P.seq_mode == 1 ? seq_in_args(args_offset_after(sizeof(AttnParams)))[i].order : P.seq[i].order) * P.Hkv +
+           bh % P.Hkv;   // (the argument block is P, then S)
+    }
   }
   const int q4 = lane >> 4, n16 = lane & 15, up = n16 >> 2, g = lane & 3;
   const bool head_ok = g < P.hb;
@@ -386,8 +395,9 @@ attn_mfma_kernel(const AttnParams P) {
   // read from the sequence's entry of the state array
   int n_fp = P.n_fp, n_q = P.n_q, nwf = P.nwf, n_tok_q = P.n_tok_q, cur = 0;
   if constexpr (GENERAL) {
-    if (P.seq) {
-      const SeqState sq = P.seq[bh / P.Hkv];
+    if (P.seq_mode) {
+      const SeqState sq = P.seq_mode == 1 ? seq_load(seq_in_args(args_offset_after(sizeof(AttnParams))), bh / P.Hkv)
+                                          : P.seq[bh / P.Hkv];
       n_fp = sq.n_fp; n_q = sq.n_q; nwf = sq.nwf; n_tok_q = sq.n_tok_q; cur = sq.cur;
     }
   }
@@ -1062,52 +1072,58 @@ hipError_t launch_combine(const Shape& s, const float* ws, void* out, int splits
 }
 
 template <bool BF16, int D, int NWB, int BITS>
-static hipError_t launch_mfma_dg(const Shape& s, const AttnParams& P, dim3 grid, hipStream_t st) {
+static hipError_t launch_mfma_dg(const Shape& s, const AttnParams& P, const SeqArg* seq, dim3 grid, hipStream_t st) {
   if constexpr (NWB == 8) {
-    if (s.Wq != s.W || P.seq) {
+    if (s.Wq != s.W || seq) {
+      SeqArgs<true> S;
+      if (seq && seq->in_args())
+        for (int i = 0; i < seq->n; ++i) S.e[i] = seq->host[i];
       switch (s.G) {
-        case 32: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 32, 8, BITS, true>), grid, dim3(512), 0, st, P); break;
-        case 64: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 64, 8, BITS, true>), grid, dim3(512), 0, st, P); break;
-        default: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 128, 8, BITS, true>), grid, dim3(512), 0, st, P); break;
+        case 32: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 32, 8, BITS, true>), grid, dim3(512), 0, st, P, S); break;
+        case 64: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 64, 8, BITS, true>), grid, dim3(512), 0, st, P, S); break;
+        default: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 128, 8, BITS, true>), grid, dim3(512), 0, st, P, S); break;
       }
       return launch_status(__func__);
     }
   }
+  const SeqArgs<false> S;
   switch (s.G) {
-    case 32: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 32, NWB, BITS>), grid, dim3(64 * NWB), 0, st, P); break;
-    case 64: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 64, NWB, BITS>), grid, dim3(64 * NWB), 0, st, P); break;
-    default: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 128, NWB, BITS>), grid, dim3(64 * NWB), 0, st, P); break;
+    case 32: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 32, NWB, BITS>), grid, dim3(64 * NWB), 0, st, P, S); break;
+    case 64: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 64, NWB, BITS>), grid, dim3(64 * NWB), 0, st, P, S); break;
+    default: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 128, NWB, BITS>), grid, dim3(64 * NWB), 0, st, P, S); break;
   }
   return launch_status(__func__);
 }
 
 template <bool BF16, int NWB, int BITS>
-static hipError_t launch_mfma_d(const Shape& s, const AttnParams& P, dim3 grid, hipStream_t st) {
+static hipError_t launch_mfma_d(const Shape& s, const AttnParams& P, const SeqArg* seq, dim3 grid, hipStream_t st) {
   switch (s.d) {
-    case 64: return launch_mfma_dg<BF16, 64, NWB, BITS>(s, P, grid, st);
-    case 96: return launch_mfma_dg<BF16, 96, NWB, BITS>(s, P, grid, st);
-    default: return launch_mfma_dg<BF16, 128, NWB, BITS>(s, P, grid, st);
+    case 64: return launch_mfma_dg<BF16, 64, NWB, BITS>(s, P, seq, grid, st);
+    case 96: return launch_mfma_dg<BF16, 96, NWB, BITS>(s, P, seq, grid, st);
+    default: return launch_mfma_dg<BF16, 128, NWB, BITS>(s, P, seq, grid, st);
   }
 }
 
 template <int NWB, int BITS>
-static hipError_t launch_mfma_t(const Shape& s, const AttnParams& P, dim3 grid, hipStream_t st) {
-  return s.bf16 ? launch_mfma_d<true, NWB, BITS>(s, P, grid, st) : launch_mfma_d<false, NWB, BITS>(s, P, grid, st);
+static hipError_t launch_mfma_t(const Shape& s, const AttnParams& P, const SeqArg* seq, dim3 grid, hipStream_t st) {
+  return s.bf16 ? launch_mfma_d<true, NWB, BITS>(s, P, seq, grid, st)
+                : launch_mfma_d<false, NWB, BITS>(s, P, seq, grid, st);
 }
 
 // seq == nullptr: every sequence has the counts of `c` and the live buffer c.cur;
 // otherwise the kernel reads counts, live buffer and fp-wavefront share per sequence
-// from seq[b] (c.n_fp / c.n_q are then the largest counts, which `plan` was made for).
+// from the state array (in its own arguments for small batches, else on the device;
+// c.n_fp / c.n_q are then the largest counts, which `plan` was made for).
 hipError_t launch_decode_attn_mfma(const Shape& s, const lq_cache& c, const void* q, float scale,
                                    void* out, void* ws, const lq_plan& plan, hipStream_t st,
-                                   const void* k_new, const void* v_new, const SeqState* seq) {
+                                   const void* k_new, const void* v_new, const SeqArg* seq) {
   AttnParams P;
   P.k_new = (const uint16_t*)k_new; P.v_new = (const uint16_t*)v_new;
   const int first = seq ? 0 : c.cur;
   P.k_fp[0] = (uint16_t*)c.k_fp[first]; P.k_fp[1] = (uint16_t*)c.k_fp[first ^ 1];
   P.v_fp[0] = (uint16_t*)c.v_fp[first]; P.v_fp[1] = (uint16_t*)c.v_fp[first ^ 1];
   P.pos_fp[0] = c.pos_fp[first]; P.pos_fp[1] = c.pos_fp[first ^ 1];
-  P.seq = seq;
+  P.seq = seq ? seq->dev : nullptr; P.seq_mode = seq_mode(seq);
   P.Hkv = s.Hkv;
   P.q = (const uint16_t*)q;
   P.k_codes = c.k_codes; P.v_codes = c.v_codes;
@@ -1126,12 +1142,12 @@ hipError_t launch_decode_attn_mfma(const Shape& s, const lq_cache& c, const void
   dim3 grid(plan.splits, s.B * s.Hkv * (s.gh / P.hb));
   if (s.Wq != s.W || seq) {   // padding slots, per-sequence counts: that kernel variant exists for 8 wavefronts only
     if (plan.waves_per_block != 8) return hipErrorInvalidConfiguration;
-    return s.bits == 4 ? launch_mfma_t<8, 4>(s, P, grid, st) : launch_mfma_t<8, 2>(s, P, grid, st);
+    return s.bits == 4 ? launch_mfma_t<8, 4>(s, P, seq, grid, st) : launch_mfma_t<8, 2>(s, P, seq, grid, st);
   }
-  if (plan.waves_per_block == 12 && s.bits == 2) return launch_mfma_t<12, 2>(s, P, grid, st);
+  if (plan.waves_per_block == 12 && s.bits == 2) return launch_mfma_t<12, 2>(s, P, seq, grid, st);
   if (plan.waves_per_block == 4)
-    return s.bits == 4 ? launch_mfma_t<4, 4>(s, P, grid, st) : launch_mfma_t<4, 2>(s, P, grid, st);
-  return s.bits == 4 ? launch_mfma_t<8, 4>(s, P, grid, st) : launch_mfma_t<8, 2>(s, P, grid, st);
+    return s.bits == 4 ? launch_mfma_t<4, 4>(s, P, seq, grid, st) : launch_mfma_t<4, 2>(s, P, seq, grid, st);
+  return s.bits == 4 ? launch_mfma_t<8, 4>(s, P, seq, grid, st) : launch_mfma_t<8, 2>(s, P, seq, grid, st);
 }
 
 }  // namespace lq

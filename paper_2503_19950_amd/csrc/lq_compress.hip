@@ -345,7 +345,8 @@ __device__ __forceinline__ void compact_rows(
 struct CompressParams {
   uint16_t *k_buf[2], *v_buf[2];   // the two fp buffers: `cur` is read, the other written
   int32_t* pos_buf[2];
-  const SeqState* seq;             // null: every sequence, with the counts below
+  const SeqState* seq;             // device array of per-sequence state (seq_mode 2)
+  int seq_mode;                    // 0: every sequence, with the counts below; 1: state in the kernel arguments
   int cur;
   uint32_t *k_codes, *v_codes;
   uint16_t *k_scale, *k_zero, *v_scale, *v_zero;
@@ -358,17 +359,21 @@ struct CompressParams {
 // x < ceil(W/G) quantize one key group each, the others move 32 kept rows each.
 // Dynamic LDS: G * (d + 4) uint16.
 template <bool BF16, int D, int G, int BITS>
-__global__ void __launch_bounds__(256) compress_kernel(const CompressParams P) {
+__global__ void __launch_bounds__(256) compress_kernel(const CompressParams P, const SeqInline S) {
   extern __shared__ uint16_t sm[];  // [G][d + 4]: the staged rows
   __shared__ float red[8 * 128];    // partial minima [4][d] and maxima [4][d] of the key channels
   __shared__ __attribute__((aligned(16))) uint8_t cb[QG_CODE_BYTES<D, G>];
   const int nq = (P.W + G - 1) / G;
   int bh = blockIdx.y, cur = P.cur, n_q = P.n_q;
-  if (P.seq) {   // per-sequence lengths: grid row -> (i-th sequence to compress, kv head); counts before the event
-    const int b = P.seq[blockIdx.y / P.Hkv].item;
+  if (P.seq_mode) {   // per-sequence lengths: grid row -> (i-th sequence to compress, kv head); counts before the event
+    const int i = blockIdx.y / P.Hkv;
+    const SeqArgsPtr in_args = seq_in_args(args_offset_after(sizeof(CompressParams)));   // = S
+    const int b = P.seq_mode == 1 ? in_args[i].item : P.seq[i].item;
+    const SeqState sq = P.seq_mode == 1 ? seq_load(in_args, b) : P.seq[b];
+    (void)S;
     bh = b * P.Hkv + blockIdx.y % P.Hkv;
-    cur = P.seq[b].cur;
-    n_q = P.seq[b].n_q;
+    cur = sq.cur;
+    n_q = sq.n_q;
   }
   // (selects between kernel arguments, not loads that depend on `cur`)
   const uint16_t* k_old = cur ? P.k_buf[1] : P.k_buf[0];
@@ -398,7 +403,8 @@ struct PrefillParams {
   const uint16_t *k, *v;          // [B*Hkv][L][d]
   uint16_t *k_buf[2], *v_buf[2];  // [0]: the buffer to fill (the same for every sequence), or, with
   int32_t* pos_buf[2];            // per-sequence state, the two buffers, chosen by the sequence's `cur`
-  const SeqState* seq;            // null: E and n_fp below hold for every sequence
+  const SeqState* seq;            // device array of per-sequence state (seq_mode 2)
+  int seq_mode;                   // 0: E and n_fp below hold for every sequence; 1: state in the kernel arguments
   uint32_t *k_codes, *v_codes;
   uint16_t *k_scale, *k_zero, *v_scale, *v_zero;
   int32_t* pos_q;
@@ -406,7 +412,7 @@ struct PrefillParams {
 };
 
 template <bool BF16, int D, int G, int BITS>
-__global__ void __launch_bounds__(256) prefill_kernel(const PrefillParams P) {
+__global__ void __launch_bounds__(256) prefill_kernel(const PrefillParams P, const SeqInline S) {
   extern __shared__ uint16_t sm[];
   __shared__ float red[8 * 128];
   __shared__ __attribute__((aligned(16))) uint8_t cb[QG_CODE_BYTES<D, G>];
@@ -414,8 +420,10 @@ __global__ void __launch_bounds__(256) prefill_kernel(const PrefillParams P) {
   const int tid = threadIdx.x, bh = blockIdx.y;
   const int per_event = (P.W + G - 1) / G;
   int E = P.E, n_fp = P.n_fp, cur = 0;
-  if (P.seq) {   // per-sequence prompt lengths: the grid is sized for the longest
-    const SeqState sq = P.seq[bh / P.Hkv];
+  if (P.seq_mode) {   // per-sequence prompt lengths: the grid is sized for the longest
+    const SeqState sq = P.seq_mode == 1 ? seq_load(seq_in_args(args_offset_after(sizeof(PrefillParams))), bh / P.Hkv)   // = S
+                                        : P.seq[bh / P.Hkv];
+    (void)S;
     E = sq.n_q / (per_event * G); n_fp = sq.n_fp; cur = sq.cur;
   }
   const int nqb = E * per_event;
@@ -470,48 +478,50 @@ __global__ void __launch_bounds__(256) prefill_kernel(const PrefillParams P) {
 // encoding and packing loops is then shifts and masks
 struct CompressLaunch {
   template <bool BF16, int D, int G, int BITS>
-  static void go(dim3 grid, size_t lds, hipStream_t st, const CompressParams& P) {
-    hipLaunchKernelGGL((compress_kernel<BF16, D, G, BITS>), grid, dim3(256), lds, st, P);
+  static void go(dim3 grid, size_t lds, hipStream_t st, const CompressParams& P, const SeqInline& S) {
+    hipLaunchKernelGGL((compress_kernel<BF16, D, G, BITS>), grid, dim3(256), lds, st, P, S);
   }
 };
 struct PrefillLaunch {
   template <bool BF16, int D, int G, int BITS>
-  static void go(dim3 grid, size_t lds, hipStream_t st, const PrefillParams& P) {
-    hipLaunchKernelGGL((prefill_kernel<BF16, D, G, BITS>), grid, dim3(256), lds, st, P);
+  static void go(dim3 grid, size_t lds, hipStream_t st, const PrefillParams& P, const SeqInline& S) {
+    hipLaunchKernelGGL((prefill_kernel<BF16, D, G, BITS>), grid, dim3(256), lds, st, P, S);
   }
 };
 template <class L, bool BF16, int D, class Params>
-static void dispatch_g(const Shape& s, dim3 grid, size_t lds, hipStream_t st, const Params& P) {
+static void dispatch_g(const Shape& s, dim3 grid, size_t lds, hipStream_t st, const Params& P, const SeqInline& S) {
   const int key = s.G * 8 + s.bits;
   switch (key) {
-    case 32 * 8 + 2: L::template go<BF16, D, 32, 2>(grid, lds, st, P); break;
-    case 64 * 8 + 2: L::template go<BF16, D, 64, 2>(grid, lds, st, P); break;
-    case 128 * 8 + 2: L::template go<BF16, D, 128, 2>(grid, lds, st, P); break;
-    case 32 * 8 + 4: L::template go<BF16, D, 32, 4>(grid, lds, st, P); break;
-    case 64 * 8 + 4: L::template go<BF16, D, 64, 4>(grid, lds, st, P); break;
-    default: L::template go<BF16, D, 128, 4>(grid, lds, st, P); break;
+    case 32 * 8 + 2: L::template go<BF16, D, 32, 2>(grid, lds, st, P, S); break;
+    case 64 * 8 + 2: L::template go<BF16, D, 64, 2>(grid, lds, st, P, S); break;
+    case 128 * 8 + 2: L::template go<BF16, D, 128, 2>(grid, lds, st, P, S); break;
+    case 32 * 8 + 4: L::template go<BF16, D, 32, 4>(grid, lds, st, P, S); break;
+    case 64 * 8 + 4: L::template go<BF16, D, 64, 4>(grid, lds, st, P, S); break;
+    default: L::template go<BF16, D, 128, 4>(grid, lds, st, P, S); break;
   }
 }
 template <class L, bool BF16, class Params>
-static void dispatch_d(const Shape& s, dim3 grid, size_t lds, hipStream_t st, const Params& P) {
+static void dispatch_d(const Shape& s, dim3 grid, size_t lds, hipStream_t st, const Params& P, const SeqInline& S) {
   switch (s.d) {
-    case 64: dispatch_g<L, BF16, 64>(s, grid, lds, st, P); break;
-    case 96: dispatch_g<L, BF16, 96>(s, grid, lds, st, P); break;
-    default: dispatch_g<L, BF16, 128>(s, grid, lds, st, P); break;
+    case 64: dispatch_g<L, BF16, 64>(s, grid, lds, st, P, S); break;
+    case 96: dispatch_g<L, BF16, 96>(s, grid, lds, st, P, S); break;
+    default: dispatch_g<L, BF16, 128>(s, grid, lds, st, P, S); break;
   }
 }
 template <class L, class Params>
-static void dispatch_dg(const Shape& s, dim3 grid, size_t lds, hipStream_t st, const Params& P) {
-  if (s.bf16) dispatch_d<L, true>(s, grid, lds, st, P);
-  else dispatch_d<L, false>(s, grid, lds, st, P);
+static void dispatch_dg(const Shape& s, dim3 grid, size_t lds, hipStream_t st, const Params& P, const SeqInline& S) {
+  if (s.bf16) dispatch_d<L, true>(s, grid, lds, st, P, S);
+  else dispatch_d<L, false>(s, grid, lds, st, P, S);
 }
 
-hipError_t launch_compress(const Shape& s, const lq_cache& c, hipStream_t st, const SeqState* seq, int n_items) {
+hipError_t launch_compress(const Shape& s, const lq_cache& c, hipStream_t st, const SeqArg* seq, int n_items) {
   CompressParams P;
+  SeqInline S;
+  fill_inline(&S, seq);
   for (int i = 0; i < 2; ++i) {
     P.k_buf[i] = (uint16_t*)c.k_fp[i]; P.v_buf[i] = (uint16_t*)c.v_fp[i]; P.pos_buf[i] = c.pos_fp[i];
   }
-  P.seq = seq; P.cur = c.cur;
+  P.seq = seq ? seq->dev : nullptr; P.seq_mode = seq_mode(seq); P.cur = c.cur;
   P.k_codes = c.k_codes; P.v_codes = c.v_codes;
   P.k_scale = (uint16_t*)c.k_scale; P.k_zero = (uint16_t*)c.k_zero;
   P.v_scale = (uint16_t*)c.v_scale; P.v_zero = (uint16_t*)c.v_zero;
@@ -519,20 +529,22 @@ hipError_t launch_compress(const Shape& s, const lq_cache& c, hipStream_t st, co
   P.d = s.d; P.G = s.G; P.W = s.W; P.cap = s.cap; P.qcap = s.qcap; P.n_q = c.n_q; P.Hkv = s.Hkv;
   const size_t lds = (size_t)s.G * (s.d + 4) * sizeof(uint16_t);
   dim3 grid(s.Wq / s.G + (2 * s.W + 31) / 32, (seq ? n_items : s.B) * s.Hkv);
-  dispatch_dg<CompressLaunch>(s, grid, lds, st, P);
+  dispatch_dg<CompressLaunch>(s, grid, lds, st, P, S);
   return launch_status(__func__);
 }
 
 hipError_t launch_prefill(const Shape& s, const lq_cache& c, const void* k, const void* v, int L, int E,
-                          int n_fp, hipStream_t st, const SeqState* seq) {
+                          int n_fp, hipStream_t st, const SeqArg* seq) {
   PrefillParams P;
+  SeqInline S;
+  fill_inline(&S, seq);
   P.k = (const uint16_t*)k; P.v = (const uint16_t*)v;
   const int first = seq ? 0 : c.cur;
   for (int i = 0; i < 2; ++i) {
     P.k_buf[i] = (uint16_t*)c.k_fp[first ^ i]; P.v_buf[i] = (uint16_t*)c.v_fp[first ^ i];
     P.pos_buf[i] = c.pos_fp[first ^ i];
   }
-  P.seq = seq;
+  P.seq = seq ? seq->dev : nullptr; P.seq_mode = seq_mode(seq);
   P.k_codes = c.k_codes; P.v_codes = c.v_codes;
   P.k_scale = (uint16_t*)c.k_scale; P.k_zero = (uint16_t*)c.k_zero;
   P.v_scale = (uint16_t*)c.v_scale; P.v_zero = (uint16_t*)c.v_zero;
@@ -541,7 +553,7 @@ hipError_t launch_prefill(const Shape& s, const lq_cache& c, const void* k, cons
   P.L = L; P.E = E; P.n_fp = n_fp;
   const size_t lds = (size_t)s.G * (s.d + 4) * sizeof(uint16_t);
   dim3 grid(E * (s.Wq / s.G) + (n_fp + 31) / 32, s.B * s.Hkv);
-  dispatch_dg<PrefillLaunch>(s, grid, lds, st, P);
+  dispatch_dg<PrefillLaunch>(s, grid, lds, st, P, S);
   return launch_status(__func__);
 }
 

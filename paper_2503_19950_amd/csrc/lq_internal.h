@@ -29,8 +29,41 @@ struct SeqState {
   int order;          // attention: the i-th entry names the row with the i-th most tokens
 };
 
-constexpr int SEQ_CHUNK = 64;   // entries per upload launch (2 KB of kernel arguments)
+constexpr int SEQ_CHUNK = 64;   // entries that fit a launch's own arguments (2 KB)
 hipError_t launch_seq_upload(SeqState* dst, const SeqState* host, int n, hipStream_t st);
+
+// How a launch gets the per-sequence state: batches of up to SEQ_CHUNK rows carry it in
+// their own kernel arguments (`host`), larger ones read the device array (`dev`), which
+// the caller of the launcher has filled with launch_seq_upload on the same stream.
+struct SeqArg {
+  const SeqState* dev;
+  const SeqState* host;
+  int n;
+  bool in_args() const { return n <= SEQ_CHUNK; }
+};
+struct SeqInline { SeqState e[SEQ_CHUNK]; };
+inline void fill_inline(SeqInline* S, const SeqArg* a) {
+  if (a && a->in_args())
+    for (int i = 0; i < a->n; ++i) S->e[i] = a->host[i];
+}
+// Kernel side: the state array inside the launch's own argument block.  It is read through
+// the argument segment's address (scalar loads at a run-time index); indexing the by-value
+// parameter itself makes the compiler copy all of it into private memory first.
+// `offset` = where the array parameter starts in the argument block.
+typedef const SeqState __attribute__((address_space(4))) * SeqArgsPtr;
+__device__ __forceinline__ SeqArgsPtr seq_in_args(size_t offset) {
+  typedef const char __attribute__((address_space(4))) * BytePtr;
+  return (SeqArgsPtr)((BytePtr)__builtin_amdgcn_kernarg_segment_ptr() + offset);
+}
+__device__ __forceinline__ SeqState seq_load(SeqArgsPtr p, int i) {
+  SeqState r;
+  r.n_fp = p[i].n_fp; r.n_q = p[i].n_q; r.cur = p[i].cur; r.nwf = p[i].nwf;
+  r.n_tok_q = p[i].n_tok_q; r.item = p[i].item; r.flag = p[i].flag; r.order = p[i].order;
+  return r;
+}
+constexpr size_t args_offset_after(size_t bytes_before) { return (bytes_before + 3) / 4 * 4; }   // SeqState is 4-byte aligned
+// kernel-side selector: 0 = no per-sequence state, 1 = in the kernel arguments, 2 = device array
+inline int seq_mode(const SeqArg* a) { return !a ? 0 : a->in_args() ? 1 : 2; }
 
 // Fills `s`; returns LQ_OK or the config error.  Pure host arithmetic.
 lq_status make_shape(const lq_config* cfg, Shape* s);
@@ -63,22 +96,22 @@ hipError_t launch_status(const char* what);
 hipError_t launch_append(const Shape& s, const lq_cache& c, const void* k_new, const void* v_new,
                          int n_new, hipStream_t st);
 hipError_t launch_append_seq(const Shape& s, const lq_cache& c, const void* k_new, const void* v_new,
-                             const SeqState* seq, hipStream_t st);
+                             const SeqArg* seq, hipStream_t st);
 // seq == nullptr: every sequence is compressed, from the counts of `c`.  Otherwise the
 // n_items sequences named by seq[0..n_items).item, each from its own counts.
-hipError_t launch_compress(const Shape& s, const lq_cache& c, hipStream_t st, const SeqState* seq = nullptr,
+hipError_t launch_compress(const Shape& s, const lq_cache& c, hipStream_t st, const SeqArg* seq = nullptr,
                            int n_items = 0);
 // seq == nullptr: one prompt length L for all.  Otherwise seq[b].flag is the prompt length of
 // sequence b (n_fp / n_q what it leads to), L the row stride of the prompt tensors and
 // E / n_fp the largest values over the batch (they size the grid).
 hipError_t launch_prefill(const Shape& s, const lq_cache& c, const void* k, const void* v, int L, int E,
-                          int n_fp, hipStream_t st, const SeqState* seq = nullptr);
+                          int n_fp, hipStream_t st, const SeqArg* seq = nullptr);
 hipError_t launch_decode_attn(const Shape& s, const lq_cache& c, const void* q, float scale,
                               void* out, void* ws, const lq_plan& plan, hipStream_t st,
-                              const SeqState* seq = nullptr);
+                              const SeqArg* seq = nullptr);
 hipError_t launch_decode_step(const Shape& s, const lq_cache& c, const void* k_new, const void* v_new,
                               const void* q, float scale, void* out, void* ws, const lq_plan& plan,
-                              hipStream_t st, const SeqState* seq = nullptr);
+                              hipStream_t st, const SeqArg* seq = nullptr);
 void plan_decode(const Shape& s, int n_fp, int n_q, lq_plan* plan, bool per_sequence = false);
 // Wavefronts (of the NW a head group has under `plan`) that walk n_fp fp rows when the
 // quantized region holds n_q slots.
