@@ -34,20 +34,24 @@ static double fp_unit_weight(const Shape& s) {
   return fp_unit_bytes / q_tile_bytes;
 }
 
+// Wavefronts for the fp rows: units of 32 rows are dealt out statically (a wavefront
+// takes every nwf-th unit), the quantized tiles are shared by the others.  Pick the
+// count that minimises the longer of the two sides, whole units per fp wavefront
+// counted (with 16 units, 9 wavefronts are no better than 8: some still take two).
 int fp_wave_share(const Shape& s, int NW, int n_fp, int n_q) {
   const int TQ = (n_q + 63) / 64, TF = (n_fp + 31) / 32;
-  const double r = fp_unit_weight(s);
-  const double units = TQ + r * TF;
-  int nwf = units > 0 ? (int)lround(NW * (r * TF) / units) : 0;
-  if (TF > 0) {
-    if (nwf < 1) nwf = 1;
-    if (nwf > TF) nwf = TF;
-  } else {
-    nwf = 0;
+  if (TF == 0) return 0;
+  if (TQ == 0) return NW;
+  const double r = fp_unit_weight(s);   // (measured: halving or doubling this weight changes nothing on the five workloads)
+  int best = 1;
+  double best_t = 1e300;
+  const int hi = TF < NW - 1 ? TF : NW - 1;
+  for (int n = 1; n <= hi; ++n) {
+    const double t_fp = (double)((TF + n - 1) / n) * r, t_q = (double)TQ / (NW - n);
+    const double t = t_fp > t_q ? t_fp : t_q;
+    if (t < best_t - 1e-9) { best_t = t; best = n; }
   }
-  if (TQ > 0 && nwf > NW - 1) nwf = NW - 1;
-  if (TQ == 0) nwf = NW;
-  return nwf;
+  return best;
 }
 
 void plan_decode(const Shape& s, int n_fp, int n_q, lq_plan* plan, bool per_sequence) {
