@@ -4,7 +4,7 @@
  * LogQuant (arXiv 2503.19950) keeps a log-sparse set of past tokens at original
  * precision (Algorithm 1, Sec. 2.5), quantizes every token that leaves that set
  * to 2 bits (Fig. 6 caption, Sec. 2.3; INT2 and group size G in Sec. 3.1, keys
- * per channel in Sec. 2.5), stores both regions one after the other without
+ * per channel in Sec. 2.5; 4 bits as the variant of Sec. 3.2.1), stores both regions one after the other without
  * regard to token positions (Sec. 2.4, Eq. 3) and attends over both with one
  * softmax (Eq. 2, with the 1/sqrt(d) of Eq. 6).
  *
@@ -13,8 +13,9 @@
  *     The library never allocates, frees or synchronises; work is enqueued on
  *     the given HIP stream (passed as void*, 0 = default stream).
  *   - lq_config and lq_cache are HOST structs.  Token counts live in the host
- *     struct (lock-step batch: every sequence has the same length) and are
- *     updated synchronously by the call that changes them.
+ *     struct (lock-step batch: every sequence has the same length; see lq_cache_seq
+ *     at the end for per-sequence lengths) and are updated synchronously by the call
+ *     that changes them.
  *   - Errors are return codes.  Argument and state errors are detected before
  *     anything is enqueued and leave the cache untouched.
  *   - T is the cache element type (fp16 or bf16); q, out and new tokens are of type T.
