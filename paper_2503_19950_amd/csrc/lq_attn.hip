@@ -69,7 +69,7 @@ void plan_decode(const Shape& s, int n_fp, int n_q, lq_plan* plan, bool per_sequ
   // padding slots in the quantized region, per-sequence counts: 8-wavefront kernel only
   const bool ragged = s.Wq != s.W || per_sequence;
   for (int wpb = 8; wpb >= 4; wpb -= 4) {
-    if (ragged && wpb != 8) continue;
+    if (ragged && wpb != 8) continue;   // (12 is derived from 8 below)
     if (!ragged && force_wpb && force_wpb != 12 && wpb != force_wpb) continue;
     const int slots = cus * (8 / wpb);
     int smax = (int)ceil(units / wpb);            // at least one unit per wavefront
@@ -87,7 +87,7 @@ void plan_decode(const Shape& s, int n_fp, int n_q, lq_plan* plan, bool per_sequ
   // than 8 with fewer than ~6 tiles per wavefront and slower than 4 when every
   // compute unit holds two workgroups anyway.  Only built for 2-bit codes (the 4-bit
   // tile does not fit 168 registers).
-  if (!ragged && s.bits == 2 && (force_wpb == 12 || (!force_wpb && best_wpb == 8 && units / (best_splits * 8.0) >= 6.0)))
+  if (s.bits == 2 && (force_wpb == 12 || (!force_wpb && best_wpb == 8 && units / (best_splits * 8.0) >= 6.0)))
     best_wpb = 12;
   const int splits = best_splits, WPB = best_wpb;
   const int NW = WPB * splits;

@@ -340,8 +340,8 @@ __device__ __forceinline__ void online_softmax_rows(State<NNT>& st, const float*
 // registers) for long contexts, where the extra wavefront hides more than the tighter
 // register budget costs.
 // GENERAL: the variant that also handles padding slots in the quantized region (group
-// size not dividing the window) and per-sequence counts; built for 8 wavefronts per
-// workgroup only.  The other instantiations carry neither check.
+// size not dividing the window) and per-sequence counts; built for 8 and 12 wavefronts
+// per workgroup.  The other instantiations carry neither check.
 // per-sequence state in the kernel arguments: only the general instantiation has any
 template <bool GENERAL> struct SeqArgs {};
 template <> struct SeqArgs<true> { SeqState e[SEQ_CHUNK]; };
@@ -1073,15 +1073,15 @@ hipError_t launch_combine(const Shape& s, const float* ws, void* out, int splits
 
 template <bool BF16, int D, int NWB, int BITS>
 static hipError_t launch_mfma_dg(const Shape& s, const AttnParams& P, const SeqArg* seq, dim3 grid, hipStream_t st) {
-  if constexpr (NWB == 8) {
+  if constexpr (NWB == 8 || NWB == 12) {
     if (s.Wq != s.W || seq) {
       SeqArgs<true> S;
       if (seq && seq->in_args())
         for (int i = 0; i < seq->n; ++i) S.e[i] = seq->host[i];
       switch (s.G) {
-        case 32: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 32, 8, BITS, true>), grid, dim3(512), 0, st, P, S); break;
-        case 64: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 64, 8, BITS, true>), grid, dim3(512), 0, st, P, S); break;
-        default: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 128, 8, BITS, true>), grid, dim3(512), 0, st, P, S); break;
+        case 32: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 32, NWB, BITS, true>), grid, dim3(64 * NWB), 0, st, P, S); break;
+        case 64: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 64, NWB, BITS, true>), grid, dim3(64 * NWB), 0, st, P, S); break;
+        default: hipLaunchKernelGGL((attn_mfma_kernel<BF16, D, 128, NWB, BITS, true>), grid, dim3(64 * NWB), 0, st, P, S); break;
       }
       return launch_status(__func__);
     }
@@ -1140,7 +1140,8 @@ hipError_t launch_decode_attn_mfma(const Shape& s, const lq_cache& c, const void
   static const int dynamic = [] { const char* v = getenv("LOGQUANT_ATTN_DYNAMIC"); return v && *v ? atoi(v) : 1; }();
   P.dynamic = dynamic;
   dim3 grid(plan.splits, s.B * s.Hkv * (s.gh / P.hb));
-  if (s.Wq != s.W || seq) {   // padding slots, per-sequence counts: that kernel variant exists for 8 wavefronts only
+  if (s.Wq != s.W || seq) {   // padding slots, per-sequence counts: that kernel variant exists for 8 and 12 wavefronts
+    if (plan.waves_per_block == 12 && s.bits == 2) return launch_mfma_t<12, 2>(s, P, seq, grid, st);
     if (plan.waves_per_block != 8) return hipErrorInvalidConfiguration;
     return s.bits == 4 ? launch_mfma_t<8, 4>(s, P, seq, grid, st) : launch_mfma_t<8, 2>(s, P, seq, grid, st);
   }

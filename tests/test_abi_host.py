@@ -187,11 +187,13 @@ def test_launch_plans_of_the_five_workloads():
     assert (p4.waves_per_block, p4.splits) == (4, 1)
     # 4-bit codes are not built for 12-wavefront workgroups
     assert B.logquant_decode_plan(_cfg(bits=4, **shapes[3][0]), 512, 130560).waves_per_block == 8
-    # neither is the variant that skips padding slots (window not a multiple of the group size)
+    # the variant that skips padding slots (window not a multiple of the group size) exists for 8 and
+    # 12 wavefronts (never 4): 12 when a wavefront gets six tiles or more, else 8
     rag = _cfg(fp_budget=84, group=64, dtype="bf16", q_capacity=3200 * 64)
-    assert B.logquant_decode_plan(rag, 100, 3118 * 64).waves_per_block == 8
+    assert B.logquant_decode_plan(rag, 100, 3118 * 64).waves_per_block == 12
     rag4 = _cfg(B=64, fp_budget=170, group=64, q_capacity=128 * 48)
-    assert B.logquant_decode_plan(rag4, 200, 128 * 46).waves_per_block == 8
+    assert B.logquant_decode_plan(rag4, 200, 128 * 46).waves_per_block == 12
+    assert B.logquant_decode_plan(rag4, 200, 128 * 8).waves_per_block == 8
 
 
 def test_plan_counts_live_slots_only_and_state_checks_use_slots():
@@ -234,7 +236,7 @@ def test_per_sequence_calls_check_their_arguments_without_a_gpu():
     assert B.logquant_compress_seq(cfg, cs) == B.LQ_ERR_CAPACITY
     # plan: made for the longest row with the general kernel variant (8 wavefronts), bytes summed over the rows
     p = B.logquant_decode_plan_seq(cfg, [10, 96, 50], [0, 64, 32])
-    assert p.waves_per_block == 8
+    assert p.waves_per_block == 8      # (12 for long rows, never 4)
     assert p.bytes_read == 8 * ((10 + 96 + 50) * 512 + (64 + 32) * 96)
     with pytest.raises(B.LogQuantError):
         B.logquant_decode_plan_seq(cfg, [0, 96, 50], [0, 64, 32])                                   # an empty row
