@@ -63,7 +63,7 @@ void plan_decode(const Shape& s, int n_fp, int n_q, lq_plan* plan, bool per_sequ
   static const int cus = env_int("LOGQUANT_ATTN_CUS", 256);
   static const int force_wpb = env_int("LOGQUANT_ATTN_WPB", 0);
   static const int force_splits = env_int("LOGQUANT_ATTN_SPLITS", 0);
-  const double fixed = 2.5, per_split = 0.02;
+  const double fixed = 2.5, per_split = 0.02, merge_tail = 1.5;
   int best_wpb = 8, best_splits = 1;
   double best = 1e300;
   // padding slots in the quantized region, per-sequence counts: 8-wavefront kernel only
@@ -78,7 +78,10 @@ void plan_decode(const Shape& s, int n_fp, int n_q, lq_plan* plan, bool per_sequ
     for (int sp = 1; sp <= smax; ++sp) {
       if (force_splits && sp != force_splits && force_splits <= smax) continue;
       const int rounds = (sp * groups + slots - 1) / slots;
-      const double t = rounds * (units / ((double)sp * wpb) + fixed) + per_split * sp;
+      // more than one split adds the cross-workgroup merge: a chain of memory round trips
+      // (store, ticket, fetch) worth about a tile and a half (measured on the smallest
+      // workload: 8.4 us with three splits, 6.8 us with one)
+      const double t = rounds * (units / ((double)sp * wpb) + fixed) + per_split * sp + (sp > 1 ? merge_tail : 0.0);
       if (t < best - 1e-9) { best = t; best_wpb = wpb; best_splits = sp; }
     }
   }
