@@ -111,7 +111,7 @@ def main():
     a = parse()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (the path shards by "
-              "kv head / batch row, see DESIGN.md)" % a.gpus, file=sys.stderr)
+              "kv head / batch row, each GPU running the same kernels on its slices)" % a.gpus, file=sys.stderr)
         sys.exit(2)
     import numpy as np
     import torch
