@@ -214,6 +214,7 @@ def main():
     attn = [(e0.elapsed_time(e1) * 1e3, nb) for k, e0, e1, nb in ev if k == "attn"]
     comp = [e0.elapsed_time(e1) * 1e3 for k, e0, e1, nb in ev if k == "compress"]
     attn_event_us = float(np.mean([t for t, _ in attn]))   # includes the event markers' own cost
+    attn_event_pct = [float(x) for x in np.percentile([t for t, _ in attn], [10, 50, 90])]
 
     # timed region 3: the attention launches alone, back to back on the launch stream,
     # rotating over the cache copies, one HIP event before and one after.  Kernel
@@ -256,7 +257,9 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,
                      "kernel": "decode attention", "us_per_launch": attn_us,
                      "algorithmic_bytes_per_launch": attn_bytes, "launches_timed": nb2b,
-                     "in_step_loop_event_pair_us": attn_event_us},
+                     "in_step_loop_event_pair_us": attn_event_us,
+                     "single_launch_event_pair_us_p10_p50_p90": attn_event_pct,
+                     "plain_copy_reference_GBps": plain_copy_reference()},
         "compress_us_per_call": float(np.mean(comp)) if comp else None,
         "token_heads_per_s": wl["B"] * wl["Hkv"] * L / (ms_per_step * 1e-3),
         "prefill": prefill,
@@ -363,6 +366,25 @@ def main_per_sequence(a, wl, steps):
                      "kernel": "decode attention (per-sequence counts; with the launch that hands them over)",
                      "us_per_launch": attn_us, "algorithmic_bytes_per_launch": float(plan.bytes_read),
                      "launches_timed": nb2b}}), flush=True)
+
+
+def plain_copy_reference():
+    """What plain streaming reaches on this machine, for scale: a device-to-device copy of 1 GiB
+    (four times the last-level cache), bytes read plus bytes written over time, best of 5."""
+    import torch
+    src = torch.ones(1 << 30, dtype=torch.uint8, device="cuda:0")
+    dst = torch.empty_like(src)
+    best = None
+    for i in range(7):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        dst.copy_(src)
+        e1.record()
+        torch.cuda.synchronize()
+        if i >= 2:
+            t = e0.elapsed_time(e1)
+            best = t if best is None else min(best, t)
+    return 2.0 * src.numel() / (best * 1e-3) / 1e9
 
 
 def read_traffic(workload_name):
