@@ -90,17 +90,35 @@ struct FpSource {
       dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
     }
   }
-  // source rows: logical slots 2jG .. 2jG + 2G - 1 (whole 32-slot tiles)
+  // The value rows are fetched into registers while the keys are being processed (the
+  // loads are issued before the key phase and first used after it) and written to LDS
+  // afterwards.  Source rows: logical slots 2jG .. 2jG + 2G - 1 (whole 32-slot tiles).
+  static constexpr int VLOADS = ((2 * G >> 5) * nnt * 64 + 255) / 256;
+  struct ValueRegs { uint4 v[VLOADS]; };
   template <bool FULL>
-  __device__ __forceinline__ void stage_values(uint16_t* sm, int ld) const {
-    for (int idx = threadIdx.x; idx < (2 * G >> 5) * nnt * 64; idx += 256) {
+  __device__ __forceinline__ ValueRegs load_values() const {
+    ValueRegs r;
+#pragma unroll
+    for (int it = 0; it < VLOADS; ++it) {
+      const int idx = threadIdx.x + 256 * it;
       const int lane = idx & 63, nt = (idx >> 6) % nnt, sb = idx / (64 * nnt);
-      const int qq = lane >> 4, n = lane & 15;
       const int tile = ((2 * j * G) >> 5) + sb;
       const int64_t src = (((int64_t)tile * nnt + nt) * 64 + lane) * 8;
-      uint4 v = make_uint4(0u, 0u, 0u, 0u);
-      if (FULL || (32 * tile < cap && 16 * sb < ng)) v = *reinterpret_cast<const uint4*>(v_fp + src);
-      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+      r.v[it] = make_uint4(0u, 0u, 0u, 0u);
+      if (idx < (2 * G >> 5) * nnt * 64 && (FULL || (32 * tile < cap && 16 * sb < ng)))
+        r.v[it] = *reinterpret_cast<const uint4*>(v_fp + src);
+    }
+    return r;
+  }
+  template <bool FULL>
+  __device__ __forceinline__ void store_values(const ValueRegs& r, uint16_t* sm, int ld) const {
+#pragma unroll
+    for (int it = 0; it < VLOADS; ++it) {
+      const int idx = threadIdx.x + 256 * it;
+      if (idx >= (2 * G >> 5) * nnt * 64) break;
+      const int lane = idx & 63, nt = (idx >> 6) % nnt, sb = idx / (64 * nnt);
+      const int qq = lane >> 4, n = lane & 15;
+      const uint32_t w[4] = {r.v[it].x, r.v[it].y, r.v[it].z, r.v[it].w};
 #pragma unroll
       for (int i = 1; i < 8; i += 2) {  // odd element <=> odd logical slot <=> evicted
         const int x = kperm_inv(8 * qq + i);
@@ -120,8 +138,35 @@ struct PromptSource {
   const int* posl;        // LDS: positions of the G rows
   template <bool FULL>
   __device__ __forceinline__ void stage_keys(uint16_t* sm, int ld) const { stage<FULL>(k, sm, ld); }
+  // value rows: into registers before the key phase, to LDS after it
+  static constexpr int VLOADS = (G * (d >> 3) + 255) / 256;
+  struct ValueRegs { uint4 v[VLOADS]; };
   template <bool FULL>
-  __device__ __forceinline__ void stage_values(uint16_t* sm, int ld) const { stage<FULL>(v, sm, ld); }
+  __device__ __forceinline__ ValueRegs load_values() const {
+    constexpr int octs = d >> 3;
+    ValueRegs r;
+#pragma unroll
+    for (int it = 0; it < VLOADS; ++it) {
+      const int idx = threadIdx.x + 256 * it;
+      const int oct = idx % octs, e = idx / octs;
+      r.v[it] = make_uint4(0u, 0u, 0u, 0u);   // rows past a short group: zeros
+      if (idx < G * octs && (FULL || posl[e] >= 0))
+        r.v[it] = *reinterpret_cast<const uint4*>(v + (int64_t)posl[e] * d + oct * 8);
+    }
+    return r;
+  }
+  template <bool FULL>
+  __device__ __forceinline__ void store_values(const ValueRegs& r, uint16_t* sm, int ld) const {
+    constexpr int octs = d >> 3;
+#pragma unroll
+    for (int it = 0; it < VLOADS; ++it) {
+      const int idx = threadIdx.x + 256 * it;
+      if (idx >= G * octs) break;
+      const int oct = idx % octs, e = idx / octs;
+      uint32_t* dst = reinterpret_cast<uint32_t*>(sm + e * ld + oct * 8);
+      dst[0] = r.v[it].x; dst[1] = r.v[it].y; dst[2] = r.v[it].z; dst[3] = r.v[it].w;
+    }
+  }
   template <bool FULL>
   __device__ __forceinline__ void stage(const uint16_t* x, uint16_t* sm, int ld) const {
     constexpr int octs = d >> 3;
@@ -163,41 +208,59 @@ __device__ __forceinline__ void quantize_group_t(
 
   // ---------------- keys ----------------
   src.template stage_keys<FULL>(sm, ld);
+  const typename Src::ValueRegs vregs = src.template load_values<FULL>();   // in flight during the key phase
   __syncthreads();
-  // per channel: 256 / d threads each scan a share of the G tokens, exchange their
-  // partial minima and maxima, and then encode their own share
+  // per pair of neighbouring channels: `parts` threads each scan a share of the G tokens
+  // (one 32-bit LDS read per token, kept in registers), exchange their partial minima
+  // and maxima, and then encode their own share.  The workgroup is bound by the number
+  // of LDS instructions, hence pairs, one pass over LDS, and two code bytes per write.
   {
-    constexpr int parts = 256 / d, per = G / parts;   // d in {64, 96, 128}: parts in {4, 2, 2} divide G
-    const int c = tid % d, part = tid / d;
+    constexpr int PAIRS = d / 2;
+    constexpr int parts = d == 96 ? 4 : 512 / d;      // threads per channel pair (d = 96: 192 threads work); divides G
+    constexpr int per = G / parts;                    // tokens per thread
+    static_assert(G % parts == 0 && parts * PAIRS <= 256 && 2 * parts * d <= 8 * 128, "key statistics split");
+    const int cp = tid % PAIRS, part = tid / PAIRS;
     const int e0 = part * per;
-    float mn = INFINITY, mx = -INFINITY;
+    uint32_t xv[per];
+    float mn[2] = {INFINITY, INFINITY}, mx[2] = {-INFINITY, -INFINITY};
     if (part < parts) {
-      const int e1 = FULL ? e0 + per : min(e0 + per, ng);
-      for (int e = e0; e < e1; ++e) {
-        const float x = t2f<BF16>(sm[e * ld + c]);
-        mn = fminf(mn, x);
-        mx = fmaxf(mx, x);
+#pragma unroll
+      for (int i = 0; i < per; ++i) {
+        xv[i] = *reinterpret_cast<const uint32_t*>(sm + (e0 + i) * ld + 2 * cp);
+        if (FULL || e0 + i < ng) {
+          const float x0 = t2f<BF16>((uint16_t)xv[i]), x1 = t2f<BF16>((uint16_t)(xv[i] >> 16));
+          mn[0] = fminf(mn[0], x0); mx[0] = fmaxf(mx[0], x0);
+          mn[1] = fminf(mn[1], x1); mx[1] = fmaxf(mx[1], x1);
+        }
       }
-      red[part * d + c] = mn;
-      red[(4 + part) * d + c] = mx;
+      *reinterpret_cast<float2*>(red + part * d + 2 * cp) = make_float2(mn[0], mn[1]);
+      *reinterpret_cast<float2*>(red + (parts + part) * d + 2 * cp) = make_float2(mx[0], mx[1]);
     }
     __syncthreads();
     if (part < parts) {
+#pragma unroll
       for (int pp = 0; pp < parts; ++pp) {
-        mn = fminf(mn, red[pp * d + c]);
-        mx = fmaxf(mx, red[(4 + pp) * d + c]);
+        const float2 a = *reinterpret_cast<const float2*>(red + pp * d + 2 * cp);
+        const float2 b = *reinterpret_cast<const float2*>(red + (parts + pp) * d + 2 * cp);
+        mn[0] = fminf(mn[0], a.x); mn[1] = fminf(mn[1], a.y);
+        mx[0] = fmaxf(mx[0], b.x); mx[1] = fmaxf(mx[1], b.y);
       }
-      float z, sc;
-      uint16_t zt, st;
-      group_params<BF16, BITS>(mn, mx, &z, &sc, &zt, &st);
+      float z0, s0, z1, s1;
+      uint16_t zt0, st0, zt1, st1;
+      group_params<BF16, BITS>(mn[0], mx[0], &z0, &s0, &zt0, &st0);
+      group_params<BF16, BITS>(mn[1], mx[1], &z1, &s1, &zt1, &st1);
       if (part == 0) {
-        const int64_t mi = ((int64_t)bh * (qcap / G) + q0 / G) * d + c;
-        k_scale[mi] = st;
-        k_zero[mi] = zt;
+        const int64_t mi = ((int64_t)bh * (qcap / G) + q0 / G) * d + 2 * cp;
+        *reinterpret_cast<uint32_t*>(k_scale + mi) = (uint32_t)st0 | ((uint32_t)st1 << 16);
+        *reinterpret_cast<uint32_t*>(k_zero + mi) = (uint32_t)zt0 | ((uint32_t)zt1 << 16);
       }
-      const Encoder<BITS> enc(z, sc);
-      for (int e = e0; e < e0 + per; ++e)
-        cb[e * KP + c] = (FULL || e < ng) ? (uint8_t)enc(t2f<BF16>(sm[e * ld + c])) : (uint8_t)0;
+      const Encoder<BITS> enc0(z0, s0), enc1(z1, s1);
+#pragma unroll
+      for (int i = 0; i < per; ++i) {
+        const uint32_t c0 = enc0(t2f<BF16>((uint16_t)xv[i])), c1 = enc1(t2f<BF16>((uint16_t)(xv[i] >> 16)));
+        *reinterpret_cast<uint16_t*>(cb + (e0 + i) * KP + 2 * cp) =
+            (FULL || e0 + i < ng) ? (uint16_t)(c0 | (c1 << 8)) : (uint16_t)0;
+      }
     }
   }
   __syncthreads();
@@ -225,26 +288,33 @@ __device__ __forceinline__ void quantize_group_t(
   __syncthreads();
 
   // ---------------- values ----------------
-  src.template stage_values<FULL>(sm, ld);
+  src.template store_values<FULL>(vregs, sm, ld);
   __syncthreads();
   // per (token, channel group): VP threads each scan a share of the channels; the
   // shares of one group sit in neighbouring lanes and are combined by lane shuffles
   {
     constexpr int vp = 2 * G * ngc > 256 ? 1 : 4 * G * ngc > 256 ? 2 : 8 * G * ngc > 256 ? 4 : 8;
     constexpr int PER = ((G < d ? G : d) + vp - 1) / vp;    // channels per thread in a full group
+    static_assert(PER % 4 == 0, "a thread's channels are read four at a time");
     for (int idx = tid; idx < G * ngc * vp; idx += 256) {   // a multiple of vp; all lanes of a group take the same trips
       const int part = idx % vp, e = (idx / vp) % G, gc = idx / (vp * G);
       const int lo = gc * G, hi = min(lo + G, d);
-      const int per = (hi - lo + vp - 1) / vp;              // fewer in the ragged last group
+      const int per = (hi - lo + vp - 1) / vp;              // fewer in the ragged last group (still a multiple of 4)
       const int c0 = lo + part * per, n = min(per, hi - c0);
-      const uint16_t* row = sm + e * ld + c0;
+      const uint16_t* row = sm + e * ld + c0;               // 8-byte aligned: ld and c0 are multiples of 4
       uint8_t* col = cb + c0 * VP + e;
+      // one pass over LDS, four channels per read; the values stay in registers for the encode
+      uint2 xv[PER / 4];
       float mn = INFINITY, mx = -INFINITY;
 #pragma unroll
-      for (int i = 0; i < PER; ++i) {
-        const float x = t2f<BF16>(row[i < n ? i : 0]);
-        mn = fminf(mn, i < n ? x : mn);
-        mx = fmaxf(mx, i < n ? x : mx);
+      for (int k = 0; k < PER / 4; ++k) {
+        xv[k] = *reinterpret_cast<const uint2*>(row + (4 * k < n ? 4 * k : 0));
+        if (4 * k < n) {
+          const float a = t2f<BF16>((uint16_t)xv[k].x), b = t2f<BF16>((uint16_t)(xv[k].x >> 16));
+          const float c = t2f<BF16>((uint16_t)xv[k].y), e4 = t2f<BF16>((uint16_t)(xv[k].y >> 16));
+          mn = fminf(fminf(mn, fminf(a, b)), fminf(c, e4));
+          mx = fmaxf(fmaxf(mx, fmaxf(a, b)), fmaxf(c, e4));
+        }
       }
       for (int o = 1; o < vp; o <<= 1) {
         mn = fminf(mn, __shfl_xor(mn, o));
@@ -260,8 +330,13 @@ __device__ __forceinline__ void quantize_group_t(
       }
       const Encoder<BITS> enc(z, sc);
 #pragma unroll
-      for (int i = 0; i < PER; ++i)
-        if (i < n) col[i * VP] = (uint8_t)enc(t2f<BF16>(row[i]));
+      for (int k = 0; k < PER / 4; ++k)
+        if (4 * k < n) {
+          col[(4 * k + 0) * VP] = (uint8_t)enc(t2f<BF16>((uint16_t)xv[k].x));
+          col[(4 * k + 1) * VP] = (uint8_t)enc(t2f<BF16>((uint16_t)(xv[k].x >> 16)));
+          col[(4 * k + 2) * VP] = (uint8_t)enc(t2f<BF16>((uint16_t)xv[k].y));
+          col[(4 * k + 3) * VP] = (uint8_t)enc(t2f<BF16>((uint16_t)(xv[k].y >> 16)));
+        }
     }
   }
   __syncthreads();
@@ -360,7 +435,7 @@ struct CompressParams {
 // Dynamic LDS: G * (d + 4) uint16.
 template <bool BF16, int D, int G, int BITS>
 __global__ void __launch_bounds__(256) compress_kernel(const CompressParams P, const SeqInline S) {
-  extern __shared__ uint16_t sm[];  // [G][d + 4]: the staged rows
+  extern __shared__ __attribute__((aligned(16))) uint16_t sm[];  // [G][d + 4]: the staged rows
   __shared__ float red[8 * 128];    // partial minima [4][d] and maxima [4][d] of the key channels
   __shared__ __attribute__((aligned(16))) uint8_t cb[QG_CODE_BYTES<D, G>];
   const int nq = (P.W + G - 1) / G;
@@ -413,7 +488,7 @@ struct PrefillParams {
 
 template <bool BF16, int D, int G, int BITS>
 __global__ void __launch_bounds__(256) prefill_kernel(const PrefillParams P, const SeqInline S) {
-  extern __shared__ uint16_t sm[];
+  extern __shared__ __attribute__((aligned(16))) uint16_t sm[];
   __shared__ float red[8 * 128];
   __shared__ __attribute__((aligned(16))) uint8_t cb[QG_CODE_BYTES<D, G>];
   __shared__ int posl[128];
