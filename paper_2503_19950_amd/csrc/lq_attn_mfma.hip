@@ -773,6 +773,20 @@ attn_mfma_kernel(const AttnParams P, const SeqArgs<GENERAL> S) {
       qreg[kc] = *reinterpret_cast<const uint4*>(P.q + qrow + 32 * kc + 8 * q4);
       if (!head_ok) qreg[kc] = make_uint4(0, 0, 0, 0);
     }
+    // Fused append: the wavefront that owns the unit receiving the new row fetches the row
+    // right away, so that it has arrived by the time that unit is processed.
+    const int new_unit = (n_fp - 1) >> 5, new_sx = (n_fp - 1) & 31, new_kx = kperm(new_sx);
+    const bool owner = P.k_new && new_unit >= wf && (new_unit - wf) % NWF == 0;
+    uint4 kn_r[NKC];
+    uint32_t vn_r[NNT];
+    if (owner) {
+      const uint16_t* kn = P.k_new + (int64_t)bh * D;
+      const uint16_t* vn = P.v_new + (int64_t)bh * D;
+#pragma unroll
+      for (int kc = 0; kc < NKC; ++kc) kn_r[kc] = *reinterpret_cast<const uint4*>(kn + 32 * kc + 8 * q4);
+#pragma unroll
+      for (int nt = 0; nt < NNT; ++nt) vn_r[nt] = vn[16 * nt + n16];
+    }
     for (int unit = wf; unit < TF; unit += NWF) {
       uint4 ka[2][NKC], va[NNT];
 #pragma unroll
@@ -784,29 +798,27 @@ attn_mfma_kernel(const AttnParams P, const SeqArgs<GENERAL> S) {
       for (int nt = 0; nt < NNT; ++nt)
         va[nt] = *reinterpret_cast<const uint4*>(vb + ((int64_t)unit * NNT + nt) * 512);
 
-      if (P.k_new && unit == (n_fp - 1) >> 5) {
+      if (owner && unit == new_unit) {
         // Fused append.  This wavefront is the only reader of the unit that receives
         // the new row: it takes the row from the caller's buffers instead of the cache
         // (whatever the loads above found in that slot is replaced) and stores it into
         // the cache for the steps to come (once per (b, kv head): head group 0).
-        const int sx = (n_fp - 1) & 31, uu_ = sx >> 4;
-        const uint16_t* kn = P.k_new + (int64_t)bh * D;
-        const uint16_t* vn = P.v_new + (int64_t)bh * D;
+        const int sx = new_sx, uu_ = sx >> 4;
         if (n16 == (sx & 15)) {
 #pragma unroll
           for (int kc = 0; kc < NKC; ++kc) {
-            const uint4 x = *reinterpret_cast<const uint4*>(kn + 32 * kc + 8 * q4);
+            const uint4 x = kn_r[kc];
             if (uu_ == 0) ka[0][kc] = x; else ka[1][kc] = x;
             if (hsub == 0)
               *reinterpret_cast<uint4*>(k_fp_w + fp_slice + lane * 8 + ((int64_t)(2 * unit + uu_) * NKC + kc) * 512) = x;
           }
         }
-        const int kx = kperm(sx);      // element kx & 7 of the lanes of token octet kx >> 3
+        const int kx = new_kx;         // element kx & 7 of the lanes of token octet kx >> 3
         if (q4 == (kx >> 3)) {
           const int sh = 16 * (kx & 1), wi = (kx & 7) >> 1;
 #pragma unroll
           for (int nt = 0; nt < NNT; ++nt) {
-            const uint32_t e = vn[16 * nt + n16];
+            const uint32_t e = vn_r[nt];
             uint32_t w[4] = {va[nt].x, va[nt].y, va[nt].z, va[nt].w};
 #pragma unroll
             for (int i = 0; i < 4; ++i)
