@@ -90,7 +90,10 @@ void plan_decode(const Shape& s, int n_fp, int n_q, lq_plan* plan, bool per_sequ
   // than 8 with fewer than ~6 tiles per wavefront and slower than 4 when every
   // compute unit holds two workgroups anyway.  Only built for 2-bit codes (with 4-bit
   // codes it was measured to make no difference: 37.3 against 37.2 us).
-  if (s.bits == 2 && (force_wpb == 12 || (!force_wpb && best_wpb == 8 && units / (best_splits * 8.0) >= 6.0)))
+  // (and only when the launch fits the chip in one round: with more workgroups than
+  // compute units, as in a batch of 64 rows with per-row counts, 8 is faster: 49 against 54 us)
+  if (s.bits == 2 && (force_wpb == 12 || (!force_wpb && best_wpb == 8 && units / (best_splits * 8.0) >= 6.0 &&
+                                          (int64_t)best_splits * groups <= cus)))
     best_wpb = 12;
   const int splits = best_splits, WPB = best_wpb;
   const int NW = WPB * splits;
