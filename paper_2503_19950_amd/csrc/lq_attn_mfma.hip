@@ -740,25 +740,55 @@ attn_mfma_kernel(const AttnParams P, const SeqArgs<GENERAL> S) {
     wave_lds_sync();
     // the accumulators of lane group q4 are the rows of channel group q4 (and of its
     // residual piece, q4 + NGC): sum_t p_t vz_t of that group, both pieces, per head
-    const int gq = q4 < NGC ? q4 : 0;
-    float zsv[4];
+    if constexpr (VPIECES == 2 && NGC == 2) {
+      // Two channel groups, two pieces: lane groups 0 and 2 hold the two pieces of
+      // channel group 0, lane groups 1 and 3 those of channel group 1.  One swap of
+      // the 32-lane halves of two registers sums the pieces of FOUR channel tiles at
+      // once - lane group 0 ends up with the total of tile a, 2 with that of tile b
+      // (both of channel group 0), 1 and 3 with tiles c and d of channel group 1 - and
+      // every lane group writes its own.
+      constexpr int T0 = G / 16;                 // channel tiles of group 0 (group 1: the rest, at most as many)
+      const int grp = q4 & 1;
+      float zsv[4];
 #pragma unroll
-    for (int gg = 0; gg < 4; ++gg) {
-      zsv[gg] = zs_lds[wave][gq][gg];
-      if constexpr (VPIECES == 2) zsv[gg] += zs_lds[wave][gq + NGC][gg];
-    }
+      for (int gg = 0; gg < 4; ++gg) zsv[gg] = zs_lds[wave][grp][gg] + zs_lds[wave][grp + NGC][gg];
 #pragma unroll
-    for (int nt = 0; nt < NNT; ++nt) {
-      const int gc = (16 * nt) / G;
+      for (int k = 0; k < (T0 + 1) / 2; ++k) {
+        constexpr int NONE = -1;
+        const int ta = 2 * k, tb = 2 * k + 1 < T0 ? 2 * k + 1 : NONE;
+        const int tc = T0 + 2 * k < NNT ? T0 + 2 * k : NONE, td = T0 + 2 * k + 1 < NNT ? T0 + 2 * k + 1 : NONE;
+        const int mine = grp ? (q4 >> 1 ? td : tc) : (q4 >> 1 ? tb : ta);
+#pragma unroll
+        for (int gg = 0; gg < 4; ++gg) {
+          const float xa = st.acc[ta][gg], xb = st.acc[tb == NONE ? ta : tb][gg];
+          const float xc = st.acc[tc == NONE ? ta : tc][gg], xd = st.acc[td == NONE ? ta : td][gg];
+          const unsigned X = __float_as_uint(grp ? xc : xa), Y = __float_as_uint(grp ? xd : xb);
+          const auto r = __builtin_amdgcn_permlane32_swap(X, Y, false, false);
+          const float tot = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+          if (mine != NONE) o_lds[wave][gg][16 * mine + n16] = tot * CODE_SCALE<BITS> + zsv[gg];
+        }
+      }
+    } else {
+      const int gq = q4 < NGC ? q4 : 0;
+      float zsv[4];
 #pragma unroll
       for (int gg = 0; gg < 4; ++gg) {
-        float a = st.acc[nt][gg];
-        if constexpr (VPIECES == 2) {   // add the residual piece's row: lane group q4 + NGC
-          float x, y;
-          if constexpr (NGC == 2) xor32_pair(a, &x, &y); else xor16_pair(a, &x, &y);
-          a = x + y;
+        zsv[gg] = zs_lds[wave][gq][gg];
+        if constexpr (VPIECES == 2) zsv[gg] += zs_lds[wave][gq + NGC][gg];
+      }
+#pragma unroll
+      for (int nt = 0; nt < NNT; ++nt) {
+        const int gc = (16 * nt) / G;
+#pragma unroll
+        for (int gg = 0; gg < 4; ++gg) {
+          float a = st.acc[nt][gg];
+          if constexpr (VPIECES == 2) {   // add the residual piece's row: lane group q4 + NGC
+            float x, y;
+            if constexpr (NGC == 2) xor32_pair(a, &x, &y); else xor16_pair(a, &x, &y);
+            a = x + y;
+          }
+          if (q4 == gc) o_lds[wave][gg][16 * nt + n16] = a * CODE_SCALE<BITS> + zsv[gg];
         }
-        if (q4 == gc) o_lds[wave][gg][16 * nt + n16] = a * CODE_SCALE<BITS> + zsv[gg];
       }
     }
   } else {
