@@ -304,7 +304,11 @@ __device__ __forceinline__ void online_softmax(State<NNT>& st, const float* s, f
 // row hold different tokens; s[u], u = 0..3, are this lane's tokens.  The output
 // accumulators and zacc are laid out by the output step: acc[nt][j] belongs to head
 // j, zacc to head g = lane & 3.
-template <int NNT>
+// ROUND_P: the probabilities come back already rounded to fp16, the form in which the
+// output step uses them, and the denominator sums these rounded values.  Numerator and
+// denominator then describe the same (slightly perturbed) weights, so that the rounding
+// cancels where one token dominates instead of scaling the whole output.
+template <int NNT, bool ROUND_P>
 __device__ __forceinline__ void online_softmax_rows(State<NNT>& st, const float* s, float* p, int g) {
   float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
   if (__any(mx > st.m + MAX_SLACK)) {
@@ -331,6 +335,7 @@ __device__ __forceinline__ void online_softmax_rows(State<NNT>& st, const float*
 #pragma unroll
   for (int u = 0; u < 4; ++u) {
     p[u] = __builtin_amdgcn_exp2f(s[u] - mref);
+    if constexpr (ROUND_P) p[u] = (float)(_Float16)p[u];
     st.l[u] += p[u];
   }
 }
@@ -433,8 +438,15 @@ attn_mfma_kernel(const AttnParams P, const SeqArgs<GENERAL> S) {
     // two channel groups there are rows to spare, and the probabilities enter in two
     // pieces: p rounded to fp16, and the residual of that rounding (rows up = piece *
     // NGC + channel group), so that only the rounding of the product p * vs remains.
-    // With three or four groups there is one piece (up = channel group).
+    // With three or four groups there is one piece (up = channel group); the softmax
+    // denominator then sums the rounded probabilities, so that the rounding does not
+    // bias the normalised weights.
     constexpr int VPIECES = NGC <= 2 ? 2 : 1;
+    // The operand p * vs is rounded to fp16.  Where the cache type is fp16 (whose output
+    // tolerance that rounding alone can use up when one token carries most of the weight
+    // and its code is large) the part the rounding drops is carried as well: in the
+    // residual rows when there are two pieces, in a second product otherwise.
+    constexpr bool PROD_LO = !BF16;
     const bool row_live = up < VPIECES * NGC;
     const int upc = row_live ? up % NGC : 0;          // channel group of this lane's row
     const bool tail_row = VPIECES == 2 && up >= NGC;  // this lane feeds the residual piece
@@ -583,6 +595,7 @@ attn_mfma_kernel(const AttnParams P, const SeqArgs<GENERAL> S) {
     // probabilities: written per (head q4, token), read per (head g, token octet q4);
     // lanes of absent channel groups read the zero row
     const uint16_t* p_rd = &p_lds[wave][0][!row_live ? 4 : tail_row ? 5 + g : g][4 * q4];
+    const uint16_t* p_hd = &p_lds[wave][0][!row_live ? 4 : g][4 * q4];
     uint16_t* p_wr = &p_lds[wave][0][q4][n16];
     {
       for (int e = 0; e < NGRP; ++e)
@@ -664,7 +677,7 @@ attn_mfma_kernel(const AttnParams P, const SeqArgs<GENERAL> S) {
           if (r >= P.W) s[u] = DEAD_LOGIT;
         }
       }
-      online_softmax_rows<NNT>(st, s, p, g);
+      online_softmax_rows<NNT, VPIECES == 1>(st, s, p, g);
 
       // ---- hand the probabilities (fp16) to the lanes that feed the output step
 #pragma unroll
@@ -682,6 +695,12 @@ attn_mfma_kernel(const AttnParams P, const SeqArgs<GENERAL> S) {
         const uint2 pa = *reinterpret_cast<const uint2*>(p_rd + ks * (9 * 32));        // tokens 4*q4 .. +3
         const uint2 pb = *reinterpret_cast<const uint2*>(p_rd + ks * (9 * 32) + 16);   // tokens 16 + 4*q4 .. +3
         const uint32_t ph[4] = {pa.x, pa.y, pb.x, pb.y};      // slots (0,1) (2,3) (4,5) (6,7)
+        uint32_t hd[4] = {pa.x, pa.y, pb.x, pb.y};            // the head piece of the same slots
+        if constexpr (PROD_LO && VPIECES == 2) {
+          const uint2 ha = *reinterpret_cast<const uint2*>(p_hd + ks * (9 * 32));
+          const uint2 hb = *reinterpret_cast<const uint2*>(p_hd + ks * (9 * 32) + 16);
+          hd[0] = ha.x; hd[1] = ha.y; hd[2] = hb.x; hd[3] = hb.y;
+        }
         uint4 vsr = cur.vs[ks], vzr = cur.vz[ks];
         if (partial) {   // slots beyond n_q hold unspecified bits: keep them out of the sums
           uint32_t keep[4];
@@ -696,11 +715,24 @@ attn_mfma_kernel(const AttnParams P, const SeqArgs<GENERAL> S) {
           vzr.x &= keep[0]; vzr.y &= keep[1]; vzr.z &= keep[2]; vzr.w &= keep[3];
         }
         const uint32_t vsw[4] = {vsr.x, vsr.y, vsr.z, vsr.w}, vzw[4] = {vzr.x, vzr.y, vzr.z, vzr.w};
-        uint32_t aw[4];
+        uint32_t aw[4], al[4];
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
           const half2_t pp = __builtin_bit_cast(half2_t, ph[v]);
-          aw[v] = __builtin_bit_cast(uint32_t, pp * meta_pair(vsw[v]));
+          const half2_t sv = meta_pair(vsw[v]);
+          if constexpr (!PROD_LO) {
+            aw[v] = __builtin_bit_cast(uint32_t, pp * sv);
+          } else if constexpr (VPIECES == 2) {
+            // head rows: p_hi * vs rounded; residual rows: what that rounding dropped plus p_lo * vs
+            const half2_t hh = __builtin_bit_cast(half2_t, hd[v]);
+            const half2_t hi = hh * sv;
+            const half2_t lo = __builtin_elementwise_fma(pp, sv, __builtin_elementwise_fma(hh, sv, -hi));
+            aw[v] = __builtin_bit_cast(uint32_t, tail_row ? lo : hi);
+          } else {
+            const half2_t hi = pp * sv;
+            aw[v] = __builtin_bit_cast(uint32_t, hi);
+            al[v] = __builtin_bit_cast(uint32_t, __builtin_elementwise_fma(pp, sv, -hi));
+          }
           st.zacc[v] = __builtin_amdgcn_fdot2(pp, meta_pair(vzw[v]), st.zacc[v], false);
         }
         const uint4 a = make_uint4(aw[0], aw[1], aw[2], aw[3]);
@@ -708,6 +740,8 @@ attn_mfma_kernel(const AttnParams P, const SeqArgs<GENERAL> S) {
         for (int nt = 0; nt < NNT; ++nt) {
           const uint4 b = operand_codes<BITS>(cur.vc[ks].w, nt);
           st.acc[nt] = mfma_f16(a, b, st.acc[nt]);
+          if constexpr (PROD_LO && VPIECES == 1)   // no spare rows: the dropped part takes a product of its own
+            st.acc[nt] = mfma_f16(make_uint4(al[0], al[1], al[2], al[3]), b, st.acc[nt]);
         }
         load_v(cur, tn, ks);
       }

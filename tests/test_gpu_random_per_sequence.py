@@ -1,0 +1,83 @@
+"""Seeded sweep of the per-sequence entry points over configurations the hand-picked cases
+do not cover: every head dimension, group size, cache type and code width, windows the
+group size does or does not divide, grouped-query ratios, and rows whose prompt lengths
+are drawn around their own window boundaries (Algorithm 1 runs per sequence, Sec. 2.5).
+Each case builds its state with logquant_prefill_seq, continues with decode steps (fused
+while no row is about to filter, separate calls otherwise) and is compared row by row
+with an oracle cache of that row (state bit for bit, outputs to tolerance)."""
+import numpy as np
+import pytest
+
+from paper_2503_19950_amd import inputs
+from tests import gpu_util as U
+from tests.test_gpu_per_sequence import _check_outputs, _new, _oracles
+
+pytestmark = pytest.mark.gpu
+
+
+def _cases():
+    rng = np.random.default_rng(20250321)
+    out = []
+    for i in range(14):
+        d = int(rng.choice([64, 96, 128]))
+        G = int(rng.choice([32, 64, 128]))
+        if i % 2:
+            W = int(rng.integers(1, 2 * G))
+            if W % G == 0:
+                W += 1
+        else:
+            W = G * int(rng.choice([1, 1, 2]))
+        gh = int(rng.choice([1, 2, 3, 4, 8]))
+        Hkv = int(rng.choice([1, 2, 3]))
+        B = int(rng.integers(2, 7))
+        bits = int(rng.choice([2, 2, 4]))
+        dtype = str(rng.choice(["f16", "bf16"]))
+        lengths = []
+        for b in range(B):
+            events = int(rng.integers(0, 6))
+            lengths.append(int(rng.integers(0, 3 * W)) if events == 0 else 3 * W + (events - 1) * W + int(rng.integers(0, W)))
+        if max(lengths) == 0:
+            lengths[0] = 1
+        wl = U.make_wl(B=B, Hq=gh * Hkv, Hkv=Hkv, d=d, G=G, F=2 * W, dtype=dtype, bits=bits,
+                       dist=str(rng.choice(["normal", "laplace"])), sinks=int(rng.choice([0, 0, 4])))
+        steps = int(rng.integers(2, min(2 * W, 24) + 2))
+        out.append(("%02d_d%d_g%d_w%d_gh%d_hkv%d_b%d_%s_bits%d" % (i, d, G, W, gh, Hkv, B, dtype, bits), wl, lengths, steps))
+    return out
+
+
+CASES = _cases()
+
+
+@pytest.mark.parametrize("name,wl,lengths,steps", CASES, ids=[c[0] for c in CASES])
+def test_random_per_sequence_configuration(name, wl, lengths, steps):
+    import torch
+    seed_id = 800 + int(name[:2])
+    print("case", name, lengths, steps, flush=True)
+    dt, W, B = wl["dtype"], wl["F"] // 2, wl["B"]
+    Lmax = max(lengths)
+    K, V = inputs.batch_kv(seed_id, 0, Lmax + steps, wl)
+    Kd, Vd = U.to_dev(K, dt), U.to_dev(V, dt)
+    dc = _new(wl, Lmax + steps, poison=True)
+    dc.prefill_seq(Kd[:, :, :Lmax].contiguous(), Vd[:, :, :Lmax].contiguous(), lengths)
+    ocs = _oracles(wl, K, V, lengths)
+    for (b, h), oc in ocs.items():
+        U.check_state(dc, oc, wl, b, h, counts=dc.view(b))
+    if min(lengths) > 0:
+        q = inputs.queries(seed_id, 999, wl)
+        _check_outputs(dc.decode_attn_seq(U.to_dev(q, dt)), ocs, wl, q, "after prefill")
+    for s in range(steps):
+        kn = torch.stack([Kd[b, :, lengths[b] + s:lengths[b] + s + 1] for b in range(B)]).contiguous()
+        vn = torch.stack([Vd[b, :, lengths[b] + s:lengths[b] + s + 1] for b in range(B)]).contiguous()
+        q = inputs.queries(seed_id, s, wl)
+        if all(dc.n_fp[b] + 1 < 3 * W for b in range(B)):
+            out = dc.decode_step_seq(kn, vn, U.to_dev(q, dt))
+        else:
+            dc.append_seq(kn, vn)
+            dc.compress_seq()
+            out = dc.decode_attn_seq(U.to_dev(q, dt))
+        torch.cuda.synchronize()
+        for (b, h), oc in ocs.items():
+            oc.append(K[b, h, lengths[b] + s], V[b, h, lengths[b] + s])
+        _check_outputs(out, ocs, wl, q, "step %d" % s)
+    for (b, h), oc in ocs.items():
+        U.check_state(dc, oc, wl, b, h, counts=dc.view(b))
