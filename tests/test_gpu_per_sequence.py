@@ -1,6 +1,8 @@
 """GPU parity of the per-sequence entry points (Algorithm 1 runs per sequence, Sec. 2.5:
 in a batch of sequences of different lengths every row fills its window and runs its
 filtering events at its own pace).  Every row is compared with an oracle cache of its own."""
+import os
+
 import numpy as np
 import pytest
 
@@ -136,7 +138,12 @@ def test_equal_lengths_give_the_lock_step_result_bit_for_bit():
     q = U.to_dev(inputs.queries(760, 0, wl), "f16")
     oa, ob = a.decode_attn(q), b.decode_attn_seq(q)
     torch.cuda.synchronize()
-    assert torch.equal(oa, ob)
+    if os.environ.get("LOGQUANT_ATTN_WPB") == "4":
+        # a forced 4-wavefront shape applies to the lock-step launch only (the per-sequence kernel
+        # is built for 8 and 12 wavefronts): the tiles are then summed in another order
+        assert (oa.float() - ob.float()).abs().max().item() <= U.TOL["f16"] / 2
+    else:
+        assert torch.equal(oa, ob)
 
 
 def test_error_codes():
