@@ -53,7 +53,10 @@ def _cases(seed=20250319):
     return out
 
 
-CASES = _cases()
+# plus one case of another seed with large logits and few tokens sharing the weight, which exceeded the
+# fp16 tolerance while q*s entered the matrix unit as two 11-bit pieces
+# (its name keeps its own number: the data seed is derived from it)
+CASES = _cases() + [_cases(112)[2]]
 
 
 @pytest.mark.parametrize("name,wl,L,steps", CASES, ids=[c[0] for c in CASES])

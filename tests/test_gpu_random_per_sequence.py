@@ -45,7 +45,11 @@ def _cases(seed=20250321):
     return out
 
 
-CASES = _cases()
+# plus two cases of other seeds whose logits are large (30-40 nats from terms that sum to over 100 in
+# magnitude: Laplace keys, outlier channels, sink rows) with two or three tokens sharing the weight:
+# they exceeded the fp16 tolerance while q*s entered the matrix unit as two 11-bit pieces
+# (their names keep their own number: the data seed is derived from it)
+CASES = _cases() + [_cases(105)[10], _cases(131)[10]]
 
 
 @pytest.mark.parametrize("name,wl,lengths,steps", CASES, ids=[c[0] for c in CASES])
