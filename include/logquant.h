@@ -205,7 +205,7 @@ lq_status logquant_prefill_positions(int32_t W, int32_t L, int32_t *pos_fp, int3
  *   workspace : DEVICE, logquant_workspace_bytes(cfg) bytes, prepared once with
  *               logquant_workspace_init; not shared between concurrent calls.
  * Requires n_fp + n_q >= 1 (else LQ_ERR_STATE).  The cache is not modified.
- * Finite inputs only; 32 |q_c s_c| (a query element times a key scale) is assumed to stay
+ * Finite inputs only; 8 |q_c s_c| (a query element times a key scale) is assumed to stay
  * below fp16 range (65504). */
 lq_status logquant_decode_attn(const lq_config *cfg, const lq_cache *cache, const void *q,
                                float softmax_scale, void *out, void *workspace,

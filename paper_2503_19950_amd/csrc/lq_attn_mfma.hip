@@ -10,7 +10,7 @@
 //               matrix instruction: row 4*head + piece (piece 3 is zero).
 //               The code tile is the B operand, 16 tokens per instruction.  Lane
 //               (row group q4, column n16) of the result then holds, for head q4 and
-//               token n16, the pieces in three registers: an add and an fma give the logit.
+//               token n16, the pieces in three registers: two adds give the logit.
 //               sum_c q_c z_c is a per-group bias.  (A single fp16 rounding of
 //               q_c s_c is not enough: with outlier channels its error alone moves
 //               the logits by ~1e-2.)
@@ -622,8 +622,8 @@ attn_mfma_kernel(const AttnParams P, const SeqArgs<GENERAL> S) {
           // below the largest, while a code's bits lie up to 9 bits below its nominal
           // exponent: measured, an 11-bit operand loses its low bits as soon as another
           // channel of the block has a q*s a few times larger.  A six-bit piece has 5 bits
-          // of room more, and the two small pieces (scaled by 2^8 to stay in the normal
-          // range; 4 |8 q s| < 65504 is assumed) lose nothing that matters.
+          // of room more, and the two small pieces lose nothing that matters (they may be
+          // subnormal themselves: single products of two subnormals were measured exact).
           uint32_t h[4], r[4], l[4];
 #pragma unroll
           for (int v = 0; v < 4; ++v) {
@@ -633,9 +633,8 @@ attn_mfma_kernel(const AttnParams P, const SeqArgs<GENERAL> S) {
             const half2_t hi = qh[v] * sh;
             const half2_t lo = __builtin_elementwise_fma(qh[v], sh, -hi);
             h[v] = __builtin_bit_cast(uint32_t, hi) & 0xFFE0FFE0u;
-            const half2_t rest = hi - __builtin_bit_cast(half2_t, h[v]);
-            r[v] = __builtin_bit_cast(uint32_t, rest * half2_t{(_Float16)256, (_Float16)256});
-            l[v] = __builtin_bit_cast(uint32_t, lo * half2_t{(_Float16)256, (_Float16)256});
+            r[v] = __builtin_bit_cast(uint32_t, hi - __builtin_bit_cast(half2_t, h[v]));
+            l[v] = __builtin_bit_cast(uint32_t, lo);
           }
           if (prep) {
             *reinterpret_cast<uint4*>(qs_wr + e * (QS_ROWS * QS_ROW)) = make_uint4(h[0], h[1], h[2], h[3]);
@@ -673,7 +672,7 @@ attn_mfma_kernel(const AttnParams P, const SeqArgs<GENERAL> S) {
       // this lane: head q4, token 16*u + n16 of the tile; the three pieces are rows j = 0, 1, 2
       float s[4], p[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) s[u] = fmaf(fmaf(Du[u][1] + Du[u][2], 0.00390625f, Du[u][0]), c21, bo[u]);
+      for (int u = 0; u < 4; ++u) s[u] = fmaf(Du[u][0] + (Du[u][1] + Du[u][2]), c21, bo[u]);
       const bool partial = 64 * t + 64 > n_q;
       if (partial) {
 #pragma unroll
