@@ -21,19 +21,18 @@ T_K, T_V, T_Q, T_OUTLIER_K, T_OUTLIER_V = 0, 1, 2, 3, 4
 # B, Hq, Hkv, d, L (tokens in the cache when the decode step is measured),
 # dtype, G (group size), F (fp budget = 2W), dist, and the structure knobs:
 #   four key channels per kv head are always scaled x10 (outlier channels);
-#   v_outliers: also scale four value channels x10;
+#   v_outliers: also scale four (independently drawn) value channels x10;
 #   sinks: number of leading positions whose KEY rows are scaled x5 (tokens that
 #          attract attention); sink_v: scale their value rows as well.
-# The five workloads keep V at unit scale: with x10 / x5 structure on V the outputs
-# reach tens, where rounding the output to bf16 alone (half an ulp = 2^-9 relative)
-# exceeds the 1e-2 absolute tolerance the outputs are held to.
+# Workload 3 carries the structure on both tensors, as its text states ("K,V ~ N(0,1) plus
+# outlier channels x10 and a few per-token attention-sink rows scaled x5").
 WORKLOADS = {
     1: dict(name="cfg1_small_L512", B=1, Hq=32, Hkv=8, d=128, L=512, dtype="f16", G=32, F=128,
             dist="normal", v_outliers=False, sinks=0),
     2: dict(name="cfg2_llama3_8b_B8_L8192", B=8, Hq=32, Hkv=8, d=128, L=8192, dtype="f16", G=32,
             F=256, dist="normal", v_outliers=False, sinks=0),
     3: dict(name="cfg3_long_context_L131072", B=1, Hq=32, Hkv=8, d=128, L=131072, dtype="bf16",
-            G=64, F=512, dist="normal", v_outliers=False, sinks=4),
+            G=64, F=512, dist="normal", v_outliers=True, sinks=4, sink_v=True),
     4: dict(name="cfg4_batch64_L4096_128steps", B=64, Hq=32, Hkv=8, d=128, L=4096, dtype="f16",
             G=32, F=256, dist="normal", v_outliers=False, sinks=0, steps=128),
     5: dict(name="cfg5_mha_d96_L32768", B=16, Hq=32, Hkv=32, d=96, L=32768, dtype="bf16", G=64,
@@ -100,6 +99,8 @@ def slice_kv(cfg_id, b, h, t0, t1, wl=None):
             x[:, outlier_channels(cfg_id, h, d, T_OUTLIER_K if tensor == T_K else T_OUTLIER_V)] *= 10.0
         if wl["sinks"] and t0 < wl["sinks"] and (tensor == T_K or wl.get("sink_v", False)):
             x[:max(0, min(wl["sinks"], t1) - t0)] *= 5.0
+        if wl.get("gain", 1.0) != 1.0:      # whole tensor scaled (test cases at the edge of the value range)
+            x *= np.float32(wl["gain"])
         out.append(to_T(x, wl["dtype"]))
     return out[0], out[1]
 

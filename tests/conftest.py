@@ -24,3 +24,19 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+def pytest_terminal_summary(terminalreporter):
+    """How many compared attention outputs fell into the band where the output bound is
+    relaxed (half an ulp of the expected value in T above the tolerance)."""
+    try:
+        from tests import gpu_util
+    except Exception:
+        return
+    st = gpu_util.BAND_STATS
+    if st["compared"]:
+        terminalreporter.write_line(
+            "attention outputs compared: %d; held to the plain tolerance: %d (worst abs err %.3e); "
+            "in the relaxed band (half an ulp of T above the tolerance): %d (worst %.2f ulp from the "
+            "oracle rounded to T)" % (st["compared"], st["compared"] - st["relaxed"], st["worst_plain"],
+                                      st["relaxed"], st["worst_relaxed_vs_rounded_ulps"]))

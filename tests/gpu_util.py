@@ -8,7 +8,7 @@ from paper_2503_19950_amd import inputs
 from paper_2503_19950_amd.binding import to_dev, torch_dtype  # noqa: F401  (used by the tests through this module)
 
 TOL = {"f16": 2e-3, "bf16": 1e-2}      # max-abs tolerance on attention outputs
-HALF_ULP = {"f16": 2.0 ** -11, "bf16": 2.0 ** -8}   # worst relative half-ulp of the output type
+MANT_BITS = {"f16": 11, "bf16": 8}     # significand bits of the output type (half an ulp of x: 2^(floor(log2 |x|) - bits))
 
 
 def make_wl(**kw):
@@ -86,15 +86,10 @@ def check_state(dc, oc, wl, b, h, counts=None):
         assert np.array_equal(got, want), name
 
 
-def check_attention(dc, oc_by_slice, wl, q_np, scale=0.0, large_outputs=False):
+def check_attention(dc, oc_by_slice, wl, q_np, scale=0.0):
     """Run logquant_decode_attn for the whole batch; compare the heads of the given
-    (b, h) slices with the oracle.  Returns the largest abs error seen.
-
-    The bound is the max-abs tolerance TOL.  The output is delivered in T, and where
-    half an ulp of the expected value is itself more than half of TOL (|o| > 1.28 in
-    bf16, > 2.05 in fp16) no result in T can be held to TOL: there, and everywhere
-    when `large_outputs` is set (inputs built to give outputs far above 1), the bound
-    adds that half ulp."""
+    (b, h) slices with the oracle (bound: assert_outputs_close).  Returns the largest
+    abs error seen."""
     dt = wl["dtype"]
     gh = wl["Hq"] // wl["Hkv"]
     out = dc.decode_attn(to_dev(q_np, dt), softmax_scale=scale)
@@ -106,20 +101,93 @@ def check_attention(dc, oc_by_slice, wl, q_np, scale=0.0, large_outputs=False):
     for (b, h), oc in oc_by_slice.items():
         want = attention.decode_attention(oc, q_np[b, h * gh:(h + 1) * gh], scale if scale > 0 else None)
         worst = max(worst, assert_outputs_close(out[b, h * gh:(h + 1) * gh], want, dt,
-                                                "attention (b=%d,h=%d)" % (b, h), large_outputs))
+                                                "attention (b=%d,h=%d)" % (b, h)))
     return worst
 
 
-def assert_outputs_close(got, want, dt, where, large_outputs=False):
-    """The output bound described in check_attention; returns the largest abs error."""
+# running totals over a test session: elements compared, and of those the ones that fell
+# into the band where the bound is relaxed (printed by conftest at the end of the run)
+BAND_STATS = {"compared": 0, "relaxed": 0, "worst_plain": 0.0, "worst_relaxed_vs_rounded_ulps": 0.0}
+
+
+def half_ulp_in_T(x, dt):
+    """Half a unit in the last place of |x| as a value of T (normal range)."""
+    e = np.floor(np.log2(np.maximum(np.abs(x), 2.0 ** -14)))
+    return 2.0 ** (e - MANT_BITS[dt])
+
+
+# Relative size of what the kernel's own arithmetic contributes before the output is rounded to
+# T (fp32 logits of tens of nats carry ~1e-5 nats of rounding noise, which moves an output by
+# about that fraction of the spread of the value rows; bf16 caches also round the products
+# p * vs once to fp16).  Only used to find the one band where the stated tolerance leaves less
+# room than that beside the rounding to T itself: fp16 outputs with 4 <= |o| < 8, where half an
+# ulp is 1.953e-3 of the 2e-3.
+COMPUTE_NOISE = {"f16": 2.0 ** -15, "bf16": 2.0 ** -12}
+
+
+def output_bound(want, dt):
+    """Elementwise bound on |output - oracle| (see assert_outputs_close), the mask of the
+    elements where it is relaxed by half an ulp, and that half ulp."""
+    want = np.asarray(want, np.float64)
+    hu = half_ulp_in_T(want, dt)
+    relaxed = hu > TOL[dt]
+    noise = COMPUTE_NOISE[dt] * np.abs(want)
+    no_room = ~relaxed & (TOL[dt] - hu < noise)
+    return TOL[dt] + np.where(relaxed, hu, 0.0) + np.where(no_room, noise, 0.0), relaxed, hu
+
+
+def assert_outputs_close(got, want, dt, where):
+    """Attention outputs against the oracle's fp64 result: max-abs error <= TOL (2e-3 for
+    fp16, 1e-2 for bf16) for every element whose half ulp in T is at most TOL, i.e.
+    wherever a correctly rounded result of type T meets the tolerance (bf16 |o| < 4,
+    fp16 |o| < 8).  Only above that, where no value of T can be held to TOL, the bound
+    adds that half ulp, and the result must also lie within one ulp of the oracle's value
+    rounded to T.  One band is left with less room than fp32 arithmetic needs beside the
+    rounding to T (fp16, 4 <= |o| < 8: 4.7e-5); there the bound is TOL + 2^-15 |o|
+    (at most 2.25e-3).  Returns the largest abs error."""
+    got = np.asarray(got, np.float64)
+    want = np.asarray(want, np.float64)
     diff = np.abs(got - want)
-    half_ulp = HALF_ULP[dt] * np.abs(want)
-    if not large_outputs:
-        half_ulp = np.where(half_ulp > TOL[dt] / 2, half_ulp, 0.0)
-    bad = diff > TOL[dt] + half_ulp
+    bound, relaxed, hu = output_bound(want, dt)
+    BAND_STATS["compared"] += diff.size
+    BAND_STATS["relaxed"] += int(relaxed.sum())
+    if (~relaxed).any():
+        BAND_STATS["worst_plain"] = max(BAND_STATS["worst_plain"], float(diff[~relaxed].max()))
+    bad = diff > bound
     assert not bad.any(), "%s: abs err %.3e at |o| = %.3f, tolerance %.1e" % (
         where, diff[bad].max(), np.abs(want)[bad].max(), TOL[dt])
+    if relaxed.any():
+        want_T = inputs.to_T(want.astype(np.float32), dt).astype(np.float64)
+        ulps = np.abs(got - want_T)[relaxed] / (2.0 * hu[relaxed])
+        BAND_STATS["worst_relaxed_vs_rounded_ulps"] = max(BAND_STATS["worst_relaxed_vs_rounded_ulps"],
+                                                          float(ulps.max()))
+        assert ulps.max() <= 1.0, "%s: %.2f ulp from the oracle rounded to %s at |o| = %.3f" % (
+            where, ulps.max(), dt, np.abs(want)[relaxed][ulps.argmax()])
+        BAND_STATS["calls_with_relaxed"] = BAND_STATS.get("calls_with_relaxed", 0) + 1
+        if BAND_STATS["calls_with_relaxed"] <= 12 or relaxed.sum() > diff.size // 4:
+            print("  %s: %d of %d outputs have half an ulp above the tolerance (|o| up to %.1f); there: max err %.3e "
+                  "against fp64, %.2f ulp against the oracle rounded to %s" % (
+                      where, int(relaxed.sum()), diff.size, np.abs(want).max(), diff[relaxed].max(), ulps.max(), dt),
+                  flush=True)
     return float(diff.max())
+
+
+def same_up_to_order_noise(x, y, dt, where, noise=2e-5):
+    """Two outputs of the HIP path for the same mathematical input that differ only in the
+    order of the fp32 sums (row order in memory, number of context splits): before the
+    rounding to T they differ by fp32 noise relative to the largest summands, after it by
+    at most that noise plus one unit in the last place of T.  Bound per element:
+    ulp_T(|o|) + noise * max(1, max |o| of the head).  Returns (largest excess over one ulp
+    in units of the noise allowance, number of elements that differ)."""
+    x = np.asarray(x, np.float64)
+    y = np.asarray(y, np.float64)
+    ulp = 2.0 * half_ulp_in_T(np.maximum(np.abs(x), np.abs(y)), dt)
+    allow = noise * np.maximum(1.0, np.abs(x).max(axis=-1, keepdims=True))
+    excess = (np.abs(x - y) - ulp) / allow
+    assert (excess <= 1.0).all(), "%s: |diff| %.3e at |o| = %.3e (one ulp there: %.3e, noise allowance %.1e)" % (
+        where, np.abs(x - y).ravel()[excess.argmax()], np.abs(x).ravel()[excess.argmax()], ulp.ravel()[excess.argmax()],
+        allow.max())
+    return float(excess.max()), int((x != y).sum())
 
 
 def batch_kv_sampled(seed_id, t0, t1, wl, distinct):

@@ -70,12 +70,14 @@ def test_workload_3_long_context_l131072():
 
 def test_workload_4_batch64_128_decode_steps():
     """Start from L = 4096, then 128 decode steps (append one token, attend); the window
-    fills at the last step and compress runs.  Attention is checked at steps 1, 127
-    and 128 (after the compress) for the sampled slices, the state after step 128."""
+    fills at the last step and compress runs.  Attention is checked against the oracle at
+    EVERY step for four seeded (batch row, kv head) slices, the state after step 128."""
     import torch
+    from oracle import attention
     wl = dict(inputs.WORKLOADS[4])
     L0, steps = wl["L"], wl["steps"]
-    slices = [(0, 0), (17, 3), (63, 7)]
+    rng = np.random.default_rng(4)
+    slices = [(0, 0), (63, 7)] + [(int(rng.integers(1, 63)), int(rng.integers(0, 8))) for _ in range(2)]
     dc = U.build_gpu_sampled(wl, 4, L0, slices, q_capacity=(L0 + steps) // 128 * 128 + 256)
     assert (dc.c.n_fp, dc.c.n_q) == (256, 3840)
     K, V = U.batch_kv_sampled(4, L0, L0 + steps, wl, slices)
@@ -83,25 +85,28 @@ def test_workload_4_batch64_128_decode_steps():
     ocs = {s: U.build_oracle(wl, 4, L0, *s) for s in slices}
     gh = wl["Hq"] // wl["Hkv"]
     events = 0
+    outs, qs = [], []
     for step in range(1, steps + 1):
         j = step - 1
         dc.append(Kd[:, :, j:j + 1].contiguous(), Vd[:, :, j:j + 1].contiguous())
-        for (b, h), oc in ocs.items():
-            oc.append(K[b, h, j], V[b, h, j])
         if dc.c.n_fp == 3 * (wl["F"] // 2):
             dc.compress()
             events += 1
         q = inputs.queries(4, step, wl)
-        out = dc.decode_attn(U.to_dev(q, "f16"))
-        if step in (1, steps - 1, steps):
-            from oracle import attention
-            torch.cuda.synchronize()
-            o = out.float().cpu().numpy()
-            for (b, h), oc in ocs.items():
-                want = attention.decode_attention(oc, q[b, h * gh:(h + 1) * gh])
-                err = np.abs(o[b, h * gh:(h + 1) * gh] - want).max()
-                assert err <= U.TOL["f16"], (step, b, h, err)
-            print("  step", step, "attention ok", flush=True)
+        qs.append(q)
+        outs.append(dc.decode_attn(U.to_dev(q, "f16")))
+    torch.cuda.synchronize()
+    worst = 0.0
+    for step in range(1, steps + 1):
+        j = step - 1
+        o = outs[j].float().cpu().numpy()
+        for (b, h), oc in ocs.items():
+            oc.append(K[b, h, j], V[b, h, j])
+            want = attention.decode_attention(oc, qs[j][b, h * gh:(h + 1) * gh])
+            worst = max(worst, U.assert_outputs_close(o[b, h * gh:(h + 1) * gh], want, "f16",
+                                                      "step %d (b=%d,h=%d)" % (step, b, h)))
+        if step % 32 == 0:
+            print("  steps up to", step, "attention ok, worst abs err %.3e" % worst, flush=True)
     assert events == 1 and (dc.c.n_fp, dc.c.n_q) == (256, 3968)
     for (b, h), oc in ocs.items():
         U.check_state(dc, oc, wl, b, h)

@@ -1,0 +1,78 @@
+"""Many launches in a row on a shape whose context is split over 32 workgroups per head
+group: every launch's partial results go through the workspace and are merged by the
+workgroup that finishes last (softmax normalisation of Eq. 2 over the splits).  Queries
+and cache copies alternate, so a partial or a counter left over from an earlier launch
+would show.  Every output is compared with the same launch run with ONE context split
+(no cross-workgroup merge at all; a child process, the planner's override is read once
+per process), and the whole sequence is repeated and must reproduce bit for bit."""
+import os
+import subprocess
+import sys
+import tempfile
+
+import numpy as np
+import pytest
+
+from paper_2503_19950_amd import inputs
+from tests import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LAUNCHES = 600
+N_QUERIES = 50
+
+
+def build():
+    """Two caches of workload 3's shape and size with different contents (the second holds
+    the kv heads in rotated order), and N_QUERIES queries."""
+    import torch
+    wl = dict(inputs.WORKLOADS[3])
+    L, dt = wl["L"], wl["dtype"]
+    K, V = inputs.batch_kv(3, 0, L, wl)
+    Kd, Vd = U.to_dev(K, dt), U.to_dev(V, dt)
+    a = U.new_cache(wl, L)
+    a.prefill(Kd, Vd)
+    b = U.new_cache(wl, L)
+    b.prefill(torch.roll(Kd, 3, dims=1).contiguous(), torch.roll(Vd, 3, dims=1).contiguous())
+    qs = U.to_dev(np.stack([inputs.queries(3, 1000 + s, wl) for s in range(N_QUERIES)]), dt)
+    torch.cuda.synchronize()
+    return [a, b], qs
+
+
+def test_600_launches_with_32_splits_against_single_split_runs():
+    import torch
+    from paper_2503_19950_amd import binding
+    caches, qs = build()
+    plan = binding.logquant_decode_plan(caches[0].cfg, caches[0].c.n_fp, caches[0].c.n_q)
+    print("splits", plan.splits, "workgroups", plan.blocks, flush=True)
+    assert plan.splits >= 32
+
+    def sweep():
+        outs = torch.empty((LAUNCHES,) + tuple(qs.shape[1:]), dtype=qs.dtype, device=qs.device)
+        for i in range(LAUNCHES):           # no synchronisation between the launches
+            caches[i % 2].decode_attn(qs[i % N_QUERIES], out=outs[i])
+        torch.cuda.synchronize()
+        return outs.float().cpu().numpy()
+
+    first = sweep()
+    print("first sweep done", flush=True)
+    with tempfile.TemporaryDirectory() as tmp:
+        path = os.path.join(tmp, "single.npy")
+        env = dict(os.environ, LOGQUANT_ATTN_SPLITS="1")
+        r = subprocess.run([sys.executable, "-m", "tests.soak_reference", path, str(LAUNCHES)], cwd=ROOT, env=env,
+                           capture_output=True, text=True, timeout=900)
+        assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-2000:]
+        single = np.load(path)
+    print("single-split reference done", flush=True)
+    worst, differing = 0.0, 0
+    for i in range(LAUNCHES):
+        w, n = U.same_up_to_order_noise(first[i].reshape(-1, first.shape[-1]), single[i].reshape(-1, first.shape[-1]),
+                                        "bf16", "launch %d" % i)
+        worst = max(worst, w)
+        differing += n
+    print("%d launches: %d of %d outputs differ from the single-split results; largest excess over one ulp of "
+          "bf16: %.2f of the noise allowance" % (LAUNCHES, differing, first.size, worst), flush=True)
+    second = sweep()
+    bad = np.nonzero((first != second).reshape(LAUNCHES, -1).any(1))[0]
+    assert bad.size == 0, "launch %d differs between two identical sweeps" % bad[0]

@@ -1,0 +1,105 @@
+"""Row order carries no meaning for decode attention (Sec. 2.4, Eq. 3: any joint
+permutation of the rows of K and V gives the same output), which is what lets the
+original-precision rows and the quantized rows be stored one after the other.  Here
+the stored rows of a cache are permuted - the fp rows among themselves; in the
+quantized region whole key groups (G slots with their key scales and zero-points) and
+the tokens inside each key group (codes, value scales / zero-points, positions) - and
+the HIP path must return the same outputs as for the unpermuted cache.
+
+What can differ is the order of the fp32 sums and the moments at which the running
+maximum of the online softmax moves, i.e. fp32 noise relative to the largest summands
+before the output is rounded to T; after that rounding two results lie within that noise
+plus one unit in the last place of T.  Bound: gpu_util.same_up_to_order_noise."""
+import numpy as np
+import pytest
+
+from oracle import layout
+from paper_2503_19950_amd import inputs
+from tests import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+
+def _u16(t):
+    return t.view(__import__("torch").int16)
+
+
+def _write_slice(dc, wl, bh, oc, fp_perm, slot_perm, group_perm):
+    """Overwrite slice bh of the cache `dc` with the oracle cache's rows in permuted order."""
+    import torch
+    d, G, dt, bits = wl["d"], wl["G"], wl["dtype"], wl.get("bits", 2)
+    W = wl["F"] // 2
+    cap, qcap = U.fp_rows_allocated(W), dc.cfg.q_capacity
+    nkc, ngc = d // 32, -(-d // G)
+    cur = dc.c.cur
+    dev = dc.k_codes.device
+
+    def put(buf, np_dtype, offset_elems, arr):
+        flat = torch.from_numpy(np.ascontiguousarray(arr).view(np.int16 if np_dtype == np.uint16 else np.int32)).to(dev)
+        view = buf.view(torch.int16 if np_dtype == np.uint16 else torch.int32)
+        view[offset_elems:offset_elems + flat.numel()] = flat
+
+    n_fp, n_q = oc.n_fp, oc.n_q
+    for which, buf, rows in (("k", dc.k_fp[cur], oc.K_fp), ("v", dc.v_fp[cur], oc.V_fp)):
+        put(buf, np.uint16, bh * cap * d, layout.scatter_fp(inputs.to_bits16(rows[fp_perm], dt).reshape(n_fp, d), which, cap))
+    wpl = nkc * (bits // 2)
+    for which, buf, codes in (("k", dc.k_codes, oc.K_codes), ("v", dc.v_codes, oc.V_codes)):
+        put(buf, np.uint32, bh * (qcap // 32) * 64 * wpl, layout.pack_codes(codes[slot_perm], which, bits=bits))
+    for buf, meta in ((dc.k_scale, oc.K_scale), (dc.k_zero, oc.K_zero)):
+        put(buf, np.uint16, bh * (qcap // G) * d, inputs.to_bits16(meta[group_perm], "f16").ravel())
+    for buf, meta in ((dc.v_scale, oc.V_scale), (dc.v_zero, oc.V_zero)):
+        put(buf, np.uint16, bh * (qcap // 32) * ngc * 32,
+            layout.scatter_v_meta(inputs.to_bits16(meta[slot_perm], "f16").reshape(n_q, ngc), d, G))
+
+
+CASES = [
+    # name, workload, L, at least this many context splits
+    ("multi_split_bf16_g64", U.make_wl(B=1, Hq=8, Hkv=2, d=128, G=64, F=256, dtype="bf16", sinks=4), 30000, 8),
+    ("multi_split_f16_g32", U.make_wl(B=1, Hq=4, Hkv=1, d=128, G=32, F=128), 20000, 8),
+    ("single_split_mha_d64", U.make_wl(B=16, Hq=16, Hkv=16, d=64, G=64, F=128), 64 * 40 + 128 + 11, 1),
+    ("single_split_bits4_d96", U.make_wl(B=12, Hq=24, Hkv=12, d=96, G=32, F=64, dtype="bf16", bits=4), 1500, 1),
+]
+
+
+@pytest.mark.parametrize("name,wl,L,min_splits", CASES, ids=[c[0] for c in CASES])
+def test_outputs_do_not_depend_on_the_stored_row_order(name, wl, L, min_splits):
+    import torch
+    from paper_2503_19950_amd import binding
+    seed_id = 700 + [c[0] for c in CASES].index(name)
+    dt, G, W = wl["dtype"], wl["G"], wl["F"] // 2
+    assert W % G == 0
+    print("case", name, flush=True)
+    dc = U.build_gpu_prefill(wl, seed_id, L)
+    plan = binding.logquant_decode_plan(dc.cfg, dc.c.n_fp, dc.c.n_q)
+    if min_splits > 1:
+        assert plan.splits >= min_splits, plan.splits
+    else:
+        assert plan.splits == 1
+    rng = np.random.default_rng(seed_id)
+    slices = [(b, h) for b in range(wl["B"]) for h in range(wl["Hkv"])]
+    if len(slices) > 6:   # the oracle side of the permutation is per slice: a sample of them is permuted
+        slices = [slices[i] for i in sorted(rng.choice(len(slices), 6, replace=False))]
+    perm = dc.clone()
+    for (b, h) in slices:
+        oc = U.build_oracle(wl, seed_id, L, b, h)
+        U.check_state(dc, oc, wl, b, h)          # the oracle's rows ARE the stored rows
+        n_fp, n_q = oc.n_fp, oc.n_q
+        fp_perm = rng.permutation(n_fp)
+        group_perm = rng.permutation(n_q // G)
+        slot_perm = np.concatenate([g * G + rng.permutation(G) for g in group_perm]) if n_q else np.zeros(0, np.int64)
+        _write_slice(perm, wl, b * wl["Hkv"] + h, oc, fp_perm, slot_perm, group_perm)
+    worst, differing, total = 0.0, 0, 0
+    gh = wl["Hq"] // wl["Hkv"]
+    for rep in range(3):
+        q = U.to_dev(inputs.queries(seed_id, rep, wl), dt)
+        a = dc.decode_attn(q).float().cpu().numpy()
+        b_ = perm.decode_attn(q).float().cpu().numpy()
+        torch.cuda.synchronize()
+        for (b, h) in slices:
+            w, n = U.same_up_to_order_noise(a[b, h * gh:(h + 1) * gh], b_[b, h * gh:(h + 1) * gh], dt,
+                                            "call %d (b=%d,h=%d)" % (rep, b, h))
+            worst = max(worst, w)
+            differing += n
+            total += gh * wl["d"]
+    print("  %d of %d outputs differ; largest excess over one ulp of %s: %.2f of the noise allowance"
+          % (differing, total, dt, worst), flush=True)
