@@ -172,21 +172,25 @@ def assert_outputs_close(got, want, dt, where):
     return float(diff.max())
 
 
-def same_up_to_order_noise(x, y, dt, where, noise=2e-5):
+def same_up_to_order_noise(x, y, dt, where):
     """Two outputs of the HIP path for the same mathematical input that differ only in the
-    order of the fp32 sums (row order in memory, number of context splits): before the
-    rounding to T they differ by fp32 noise relative to the largest summands, after it by
-    at most that noise plus one unit in the last place of T.  Bound per element:
-    ulp_T(|o|) + noise * max(1, max |o| of the head).  Returns (largest excess over one ulp
-    in units of the noise allowance, number of elements that differ)."""
+    order in which the rows are visited (row order in memory, number of context splits).
+    What depends on that order: the order of the fp32 sums, and the moments at which the
+    running maximum of the online softmax moves, which decide how the probabilities (and,
+    for bf16 caches, the products p * vs) are rounded to fp16 - all of it part of the
+    kernel's arithmetic noise COMPUTE_NOISE, relative to the magnitude of the head's values.
+    Bound per element: ulp_T(|o|) + 4 * COMPUTE_NOISE * max(1, max |o| of the head), i.e.
+    1.2e-4 (fp16) / 9.8e-4 (bf16) for outputs of order one: a sixteenth / a tenth of the
+    output tolerance.  Returns (largest excess over one ulp as a fraction of that
+    allowance, number of elements that differ)."""
     x = np.asarray(x, np.float64)
     y = np.asarray(y, np.float64)
     ulp = 2.0 * half_ulp_in_T(np.maximum(np.abs(x), np.abs(y)), dt)
-    allow = noise * np.maximum(1.0, np.abs(x).max(axis=-1, keepdims=True))
+    allow = 4.0 * COMPUTE_NOISE[dt] * np.maximum(1.0, np.abs(x).max(axis=-1, keepdims=True)) * np.ones_like(x)
     excess = (np.abs(x - y) - ulp) / allow
-    assert (excess <= 1.0).all(), "%s: |diff| %.3e at |o| = %.3e (one ulp there: %.3e, noise allowance %.1e)" % (
-        where, np.abs(x - y).ravel()[excess.argmax()], np.abs(x).ravel()[excess.argmax()], ulp.ravel()[excess.argmax()],
-        allow.max())
+    i = excess.argmax()
+    assert excess.ravel()[i] <= 1.0, "%s: |diff| %.3e at |o| = %.3e (one ulp there: %.3e, noise allowance %.1e)" % (
+        where, np.abs(x - y).ravel()[i], np.abs(x).ravel()[i], ulp.ravel()[i], allow.ravel()[i])
     return float(excess.max()), int((x != y).sum())
 
 

@@ -4,7 +4,8 @@ workgroup that finishes last (softmax normalisation of Eq. 2 over the splits).  
 and cache copies alternate, so a partial or a counter left over from an earlier launch
 would show.  Every output is compared with the same launch run with ONE context split
 (no cross-workgroup merge at all; a child process, the planner's override is read once
-per process), and the whole sequence is repeated and must reproduce bit for bit."""
+per process), and the whole sequence is repeated and must reproduce up to the order of the
+sums."""
 import os
 import subprocess
 import sys
@@ -73,6 +74,9 @@ def test_600_launches_with_32_splits_against_single_split_runs():
         differing += n
     print("%d launches: %d of %d outputs differ from the single-split results; largest excess over one ulp of "
           "bf16: %.2f of the noise allowance" % (LAUNCHES, differing, first.size, worst), flush=True)
+    # the same sweep again: which wavefront takes which tile depends on timing (tiles are drawn
+    # from pool counters), so two runs agree up to the order of the sums, not bit for bit
     second = sweep()
-    bad = np.nonzero((first != second).reshape(LAUNCHES, -1).any(1))[0]
-    assert bad.size == 0, "launch %d differs between two identical sweeps" % bad[0]
+    for i in range(LAUNCHES):
+        U.same_up_to_order_noise(first[i].reshape(-1, first.shape[-1]), second[i].reshape(-1, first.shape[-1]),
+                                 "bf16", "second sweep, launch %d" % i)

@@ -7,9 +7,10 @@ the tokens inside each key group (codes, value scales / zero-points, positions) 
 the HIP path must return the same outputs as for the unpermuted cache.
 
 What can differ is the order of the fp32 sums and the moments at which the running
-maximum of the online softmax moves, i.e. fp32 noise relative to the largest summands
-before the output is rounded to T; after that rounding two results lie within that noise
-plus one unit in the last place of T.  Bound: gpu_util.same_up_to_order_noise."""
+maximum of the online softmax moves (which decide how intermediate values are rounded
+to fp16): the kernel's own arithmetic noise before the output is rounded to T; after that
+rounding two results lie within that noise plus one unit in the last place of T.  Bound:
+gpu_util.same_up_to_order_noise."""
 import numpy as np
 import pytest
 
