@@ -211,6 +211,22 @@ lq_status logquant_decode_attn(const lq_config *cfg, const lq_cache *cache, cons
                                float softmax_scale, void *out, void *workspace,
                                void *stream);
 
+/* logquant_decode_attn for callers that cannot allocate device memory or hand over a
+ * workspace (code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): the same kernels, with the scratch that `workspace` provides (counters and
+ * the partial results of the context splits) taken from a device array inside the
+ * library, 12 MiB per GPU the library runs on, held until the process ends.  The call
+ * allocates and frees nothing.  Same arguments, requirements and results as
+ * logquant_decode_attn otherwise.
+ * Limits: B*Hq <= 3640 (4 MiB of counters) and logquant_workspace_bytes(cfg) minus its
+ * counter part <= 8 MiB; a larger config returns LQ_ERR_CAPACITY before anything is
+ * launched.  All calls on one GPU share the one array: calls that overlap in time on
+ * one GPU (two streams, two threads) race and give undefined results, and the first call
+ * on a GPU also enqueues the one-off clearing of the counters on `stream`, so later calls
+ * on other streams must be ordered after it. */
+lq_status logquant_decode_attn_static(const lq_config *cfg, const lq_cache *cache, const void *q,
+                                      float softmax_scale, void *out, void *stream);
+
 /* One decode step in one launch: logquant_append of one new token per sequence
  * (Algorithm 1, the append branch) followed by logquant_decode_attn over the cache
  * including that token (Eq. 2; Sec. 2.4), with the same results as the two calls.

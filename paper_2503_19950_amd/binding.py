@@ -56,8 +56,8 @@ class lq_plan(C.Structure):
 
 
 EXPORTS = ("logquant_sizes", "logquant_workspace_bytes", "logquant_workspace_init", "logquant_append", "logquant_compress",
-           "logquant_prefill", "logquant_prefill_positions", "logquant_decode_attn", "logquant_decode_step",
-           "logquant_decode_plan",
+           "logquant_prefill", "logquant_prefill_positions", "logquant_decode_attn", "logquant_decode_attn_static",
+           "logquant_decode_step", "logquant_decode_plan",
            "logquant_seq_state_bytes", "logquant_prefill_seq", "logquant_append_seq", "logquant_compress_seq",
            "logquant_decode_attn_seq", "logquant_decode_step_seq", "logquant_decode_plan_seq",
            "logquant_status_string")
@@ -87,6 +87,9 @@ _lib.logquant_prefill_positions.restype = C.c_int
 _lib.logquant_decode_attn.argtypes = [C.POINTER(lq_config), C.POINTER(lq_cache), C.c_void_p, C.c_float,
                                       C.c_void_p, C.c_void_p, C.c_void_p]
 _lib.logquant_decode_attn.restype = C.c_int
+_lib.logquant_decode_attn_static.argtypes = [C.POINTER(lq_config), C.POINTER(lq_cache), C.c_void_p, C.c_float,
+                                             C.c_void_p, C.c_void_p]
+_lib.logquant_decode_attn_static.restype = C.c_int
 _lib.logquant_decode_step.argtypes = [C.POINTER(lq_config), C.POINTER(lq_cache), C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]
 _lib.logquant_decode_step.restype = C.c_int
@@ -181,6 +184,10 @@ def logquant_prefill_positions(W, L):
 def logquant_decode_attn(cfg, cache, q, softmax_scale, out, workspace, stream=0):
     return _lib.logquant_decode_attn(_p(cfg), _p(cache), _ptr(q), float(softmax_scale), _ptr(out),
                                      _ptr(workspace), stream)
+
+
+def logquant_decode_attn_static(cfg, cache, q, softmax_scale, out, stream=0):
+    return _lib.logquant_decode_attn_static(_p(cfg), _p(cache), _ptr(q), float(softmax_scale), _ptr(out), stream)
 
 
 def logquant_decode_step(cfg, cache, k_new, v_new, q, softmax_scale, out, workspace, stream=0):

@@ -4,6 +4,7 @@
 #include <stdio.h>
 
 #include <algorithm>
+#include <mutex>
 #include <vector>
 
 #include "lq_device.h"
@@ -213,8 +214,63 @@ lq_status logquant_decode_attn(const lq_config* cfg, const lq_cache* cache, cons
   plan_decode(s, cache->n_fp, cache->n_q, &plan);
   if (!(softmax_scale > 0.f)) softmax_scale = 1.0f / sqrtf((float)s.d);
   clear_stale_error();
-  if (launch_decode_attn(s, *cache, q, softmax_scale, out, workspace, plan, (hipStream_t)stream) !=
+  if (launch_decode_attn(s, *cache, q, softmax_scale, out, split_workspace(s, workspace), plan, (hipStream_t)stream) !=
       hipSuccess)
+    return LQ_ERR_HIP;
+  return LQ_OK;
+}
+
+// ---- decode attention for callers that cannot allocate -------------------------------
+// The scratch that logquant_decode_attn takes as `workspace` (ticket and tile-pool counters,
+// partial softmax states of the context splits) lives in a device array of the library
+// itself: a counter area of fixed size at its start, the partials behind it.  The counter
+// area never holds anything but counters, whatever configuration a call has, and every call
+// leaves its counters at zero, so it is cleared once per device, by the first call there.
+namespace {
+constexpr size_t STATIC_COUNTER_BYTES = (size_t)4 << 20;
+constexpr size_t STATIC_PARTIAL_BYTES = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char scratch[STATIC_COUNTER_BYTES + STATIC_PARTIAL_BYTES];
+constexpr int STATIC_MAX_DEVICES = 64;
+std::mutex scratch_mutex;
+void* scratch_ptr[STATIC_MAX_DEVICES];        // per device: the device address of `scratch` there
+bool scratch_cleared[STATIC_MAX_DEVICES];
+}  // namespace
+
+lq_status logquant_decode_attn_static(const lq_config* cfg, const lq_cache* cache, const void* q,
+                                      float softmax_scale, void* out, void* stream) {
+  if (!cfg || !cache || !q || !out) return LQ_ERR_NULL;
+  Shape s;
+  lq_status st = make_shape(cfg, &s);
+  if (st != LQ_OK) return st;
+  if (!cache_ptrs_ok(cache)) return LQ_ERR_NULL;
+  if ((st = cache_state_ok(s, cache)) != LQ_OK) return st;
+  if (cache->n_fp + cache->n_q < 1) return LQ_ERR_STATE;
+  const size_t partial_bytes = logquant_workspace_bytes(cfg) - counter_bytes(s);
+  if (counter_bytes(s) > STATIC_COUNTER_BYTES || partial_bytes > STATIC_PARTIAL_BYTES) return LQ_ERR_CAPACITY;
+  lq_plan plan;
+  plan_decode(s, cache->n_fp, cache->n_q, &plan);
+  if (!(softmax_scale > 0.f)) softmax_scale = 1.0f / sqrtf((float)s.d);
+  clear_stale_error();
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= STATIC_MAX_DEVICES) return LQ_ERR_HIP;
+  void* base = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+      // the array's name is a host-side handle: its address on the current device comes from the runtime
+      void* p = nullptr;
+      if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return LQ_ERR_HIP;
+      scratch_ptr[dev] = p;
+    }
+    base = scratch_ptr[dev];
+    if (!scratch_cleared[dev]) {
+      if (launch_zero_ints((int*)base, (int)(STATIC_COUNTER_BYTES / sizeof(int)), (hipStream_t)stream) != hipSuccess)
+        return LQ_ERR_HIP;
+      scratch_cleared[dev] = true;
+    }
+  }
+  const Workspace ws{(int*)base, (float*)((char*)base + STATIC_COUNTER_BYTES)};
+  if (launch_decode_attn(s, *cache, q, softmax_scale, out, ws, plan, (hipStream_t)stream) != hipSuccess)
     return LQ_ERR_HIP;
   return LQ_OK;
 }
@@ -235,7 +291,7 @@ lq_status logquant_decode_step(const lq_config* cfg, lq_cache* cache, const void
   plan_decode(s, after.n_fp, after.n_q, &plan);
   if (!(softmax_scale > 0.f)) softmax_scale = 1.0f / sqrtf((float)s.d);
   clear_stale_error();
-  if (launch_decode_step(s, after, k_new, v_new, q, softmax_scale, out, workspace, plan,
+  if (launch_decode_step(s, after, k_new, v_new, q, softmax_scale, out, split_workspace(s, workspace), plan,
                          (hipStream_t)stream) != hipSuccess)
     return LQ_ERR_HIP;
   cache->n_fp = after.n_fp;
@@ -449,7 +505,7 @@ lq_status logquant_decode_attn_seq(const lq_config* cfg, const lq_cache_seq* cac
   SeqArg arg;
   if (seq_hand_over(cache, host, (hipStream_t)stream, &arg) != hipSuccess) return LQ_ERR_HIP;
   const lq_cache view = seq_view(s, cache, cache->n_fp, cache->n_q);
-  if (launch_decode_attn(s, view, q, softmax_scale, out, workspace, plan, (hipStream_t)stream, &arg) != hipSuccess)
+  if (launch_decode_attn(s, view, q, softmax_scale, out, split_workspace(s, workspace), plan, (hipStream_t)stream, &arg) != hipSuccess)
     return LQ_ERR_HIP;
   return LQ_OK;
 }
@@ -476,7 +532,7 @@ lq_status logquant_decode_step_seq(const lq_config* cfg, lq_cache_seq* cache, co
   SeqArg arg;
   if (seq_hand_over(cache, host, (hipStream_t)stream, &arg) != hipSuccess) return LQ_ERR_HIP;
   const lq_cache view = seq_view(s, cache, nf.data(), cache->n_q);
-  if (launch_decode_step(s, view, k_new, v_new, q, softmax_scale, out, workspace, plan, (hipStream_t)stream, &arg) !=
+  if (launch_decode_step(s, view, k_new, v_new, q, softmax_scale, out, split_workspace(s, workspace), plan, (hipStream_t)stream, &arg) !=
       hipSuccess)
     return LQ_ERR_HIP;
   for (int b = 0; b < s.B; ++b) cache->n_fp[b] = nf[b];

@@ -84,10 +84,13 @@ __global__ void zero_kernel(int* p, int n) {
   if (i < n) p[i] = 0;
 }
 
-hipError_t launch_workspace_init(const Shape& s, void* ws, hipStream_t st) {
-  const int n = (int)(counter_bytes(s) / sizeof(int));
-  hipLaunchKernelGGL(zero_kernel, dim3((n + 255) / 256), dim3(256), 0, st, (int*)ws, n);
+hipError_t launch_zero_ints(int* p, int n, hipStream_t st) {
+  hipLaunchKernelGGL(zero_kernel, dim3((n + 255) / 256), dim3(256), 0, st, p, n);
   return launch_status(__func__);
+}
+
+hipError_t launch_workspace_init(const Shape& s, void* ws, hipStream_t st) {
+  return launch_zero_ints((int*)ws, (int)(counter_bytes(s) / sizeof(int)), st);
 }
 
 hipError_t launch_append(const Shape& s, const lq_cache& c, const void* k_new, const void* v_new,

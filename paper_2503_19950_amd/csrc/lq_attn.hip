@@ -8,9 +8,9 @@
 namespace lq {
 
 hipError_t launch_decode_attn_ref(const Shape& s, const lq_cache& c, const void* q, float scale,
-                                  void* out, void* ws, int splits, hipStream_t st, const SeqArg* seq);
+                                  void* out, const Workspace& ws, int splits, hipStream_t st, const SeqArg* seq);
 hipError_t launch_decode_attn_mfma(const Shape& s, const lq_cache& c, const void* q, float scale,
-                                   void* out, void* ws, const lq_plan& plan, hipStream_t st,
+                                   void* out, const Workspace& ws, const lq_plan& plan, hipStream_t st,
                                    const void* k_new, const void* v_new, const SeqArg* seq);
 hipError_t launch_append_seq(const Shape& s, const lq_cache& c, const void* k_new, const void* v_new,
                              const SeqArg* seq, hipStream_t st);
@@ -112,7 +112,7 @@ static bool plain_attention() {
 }
 
 hipError_t launch_decode_attn(const Shape& s, const lq_cache& c, const void* q, float scale,
-                              void* out, void* ws, const lq_plan& plan, hipStream_t st, const SeqArg* seq) {
+                              void* out, const Workspace& ws, const lq_plan& plan, hipStream_t st, const SeqArg* seq) {
   if (plain_attention()) return launch_decode_attn_ref(s, c, q, scale, out, ws, plan.splits, st, seq);
   return launch_decode_attn_mfma(s, c, q, scale, out, ws, plan, st, nullptr, nullptr, seq);
 }
@@ -120,7 +120,7 @@ hipError_t launch_decode_attn(const Shape& s, const lq_cache& c, const void* q, 
 // `c` already counts the new row (n_fp includes it); the row itself is still only in
 // k_new / v_new.
 hipError_t launch_decode_step(const Shape& s, const lq_cache& c, const void* k_new, const void* v_new,
-                              const void* q, float scale, void* out, void* ws, const lq_plan& plan,
+                              const void* q, float scale, void* out, const Workspace& ws, const lq_plan& plan,
                               hipStream_t st, const SeqArg* seq) {
   if (plain_attention()) {
     hipError_t e;

@@ -1205,7 +1205,7 @@ static hipError_t launch_mfma_t(const Shape& s, const AttnParams& P, const SeqAr
 // from the state array (in its own arguments for small batches, else on the device;
 // c.n_fp / c.n_q are then the largest counts, which `plan` was made for).
 hipError_t launch_decode_attn_mfma(const Shape& s, const lq_cache& c, const void* q, float scale,
-                                   void* out, void* ws, const lq_plan& plan, hipStream_t st,
+                                   void* out, const Workspace& ws, const lq_plan& plan, hipStream_t st,
                                    const void* k_new, const void* v_new, const SeqArg* seq) {
   AttnParams P;
   P.k_new = (const uint16_t*)k_new; P.v_new = (const uint16_t*)v_new;
@@ -1219,8 +1219,8 @@ hipError_t launch_decode_attn_mfma(const Shape& s, const lq_cache& c, const void
   P.k_codes = c.k_codes; P.v_codes = c.v_codes;
   P.k_scale = (const uint16_t*)c.k_scale; P.k_zero = (const uint16_t*)c.k_zero;
   P.v_scale = (const uint16_t*)c.v_scale; P.v_zero = (const uint16_t*)c.v_zero;
-  P.counters = (int*)ws;
-  P.ws = (float*)((char*)ws + counter_bytes(s));
+  P.counters = ws.counters;
+  P.ws = ws.partials;
   P.out = (uint16_t*)out;
   P.cap = s.cap; P.qcap = s.qcap; P.n_fp = c.n_fp; P.n_q = c.n_q; P.gh = s.gh;
   P.W = s.W; P.Wq = s.Wq; P.n_tok_q = quantized_tokens(s, c.n_q);

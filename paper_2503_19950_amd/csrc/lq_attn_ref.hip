@@ -150,14 +150,14 @@ static hipError_t launch_ref_t(const Shape& s, const lq_cache& c, const void* q,
 }
 
 hipError_t launch_decode_attn_ref(const Shape& s, const lq_cache& c, const void* q, float scale,
-                                  void* out, void* ws_all, int splits, hipStream_t st, const SeqArg* arg) {
+                                  void* out, const Workspace& ws_all, int splits, hipStream_t st, const SeqArg* arg) {
   // this kernel reads per-sequence state from the device array only: fill it here when
   // the batch is small enough that the caller left it to the launch's arguments
   const SeqState* seq = arg ? arg->dev : nullptr;
   if (arg && arg->in_args() &&
       launch_seq_upload(const_cast<SeqState*>(arg->dev), arg->host, arg->n, st) != hipSuccess)
     return hipErrorLaunchFailure;
-  void* ws = (char*)ws_all + counter_bytes(s);
+  void* ws = ws_all.partials;
   const int hb = s.gh % 4 == 0 ? 4 : (s.gh % 2 == 0 ? 2 : 1);
   hipError_t e;
   if (s.bf16) {

@@ -80,6 +80,16 @@ inline size_t counter_bytes(const Shape& s) {
   return (size_t)s.B * s.Hkv * s.gh * CTR_LINES * CTR_LINE * sizeof(int);
 }
 hipError_t launch_workspace_init(const Shape& s, void* ws, hipStream_t st);
+// The two parts of a workspace as the attention launchers take them.
+struct Workspace {
+  int* counters;
+  float* partials;
+};
+inline Workspace split_workspace(const Shape& s, void* ws) {
+  return Workspace{(int*)ws, (float*)((char*)ws + counter_bytes(s))};
+}
+// `n` ints at `p` set to zero by a small kernel (safe to record into a HIP graph).
+hipError_t launch_zero_ints(int* p, int n, hipStream_t st);
 
 // Bytes one decode step reads from the cache (live slots only).
 int64_t cache_bytes_read(const Shape& s, int n_fp, int n_q);
@@ -107,10 +117,10 @@ hipError_t launch_compress(const Shape& s, const lq_cache& c, hipStream_t st, co
 hipError_t launch_prefill(const Shape& s, const lq_cache& c, const void* k, const void* v, int L, int E,
                           int n_fp, hipStream_t st, const SeqArg* seq = nullptr);
 hipError_t launch_decode_attn(const Shape& s, const lq_cache& c, const void* q, float scale,
-                              void* out, void* ws, const lq_plan& plan, hipStream_t st,
+                              void* out, const Workspace& ws, const lq_plan& plan, hipStream_t st,
                               const SeqArg* seq = nullptr);
 hipError_t launch_decode_step(const Shape& s, const lq_cache& c, const void* k_new, const void* v_new,
-                              const void* q, float scale, void* out, void* ws, const lq_plan& plan,
+                              const void* q, float scale, void* out, const Workspace& ws, const lq_plan& plan,
                               hipStream_t st, const SeqArg* seq = nullptr);
 void plan_decode(const Shape& s, int n_fp, int n_q, lq_plan* plan, bool per_sequence = false);
 // Wavefronts (of the NW a head group has under `plan`) that walk n_fp fp rows when the

@@ -241,3 +241,21 @@ def test_per_sequence_calls_check_their_arguments_without_a_gpu():
     assert p.bytes_read == 8 * ((10 + 96 + 50) * 512 + (64 + 32) * 96)
     with pytest.raises(B.LogQuantError):
         B.logquant_decode_plan_seq(cfg, [0, 96, 50], [0, 64, 32])                                   # an empty row
+
+
+def test_static_scratch_entry_point_rejects_configs_beyond_its_array():
+    """logquant_decode_attn_static: argument errors and the size limit are reported before
+    any HIP call (no GPU needed)."""
+    cfg = B.make_config(1, 32, 8, 128, 512, 64, "bf16", 4096)
+    assert B.logquant_decode_attn_static(None, None, None, 0.0, None) == B.LQ_ERR_NULL
+    cache = B.lq_cache()
+    assert B.logquant_decode_attn_static(cfg, cache, 1, 0.0, 1) == B.LQ_ERR_NULL      # null cache buffers
+    big = B.make_config(128, 32, 8, 128, 256, 32, "f16", 4096)     # B * Hq = 4096 > 3640: counters beyond 4 MiB
+    for name, _ in B.lq_cache._fields_[:10]:
+        if name in ("k_fp", "v_fp", "pos_fp"):
+            getattr(cache, name)[0] = 1
+            getattr(cache, name)[1] = 1
+        else:
+            setattr(cache, name, 1)
+    cache.n_fp, cache.n_q = 10, 0
+    assert B.logquant_decode_attn_static(big, cache, 1, 0.0, 1) == B.LQ_ERR_CAPACITY
