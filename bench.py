@@ -38,6 +38,11 @@ def parse():
     ap.add_argument("--unfused", action="store_true",
                     help="time the step as separate append and attention launches instead of logquant_decode_step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-per-config", action="store_true",
+                    help="skip the attention / compress legs of the other four BASELINE.json configs")
+    ap.add_argument("--plain-valu", action="store_true",
+                    help="time the plain vector-unit attention kernel of liblogquant_plain.so instead of the product's "
+                         "(matrix unit or vector unit: the measurement behind that choice)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 256 MiB device copy a few times (reference for HBM counters)")
     return ap.parse_args()
@@ -107,6 +112,131 @@ def build_states(wl, cfg_id, copies):
     return cfg, caches, prefill
 
 
+def filler_kv_device(wl, cfg_id, L):
+    """[B][Hkv][L][d] K and V on the device in which eight seeded slices repeat (drawing
+    every slice of the big batches on the host would take minutes; what is timed does not
+    depend on the values)."""
+    import torch
+    from paper_2503_19950_amd import inputs
+    from paper_2503_19950_amd.binding import to_dev
+    B, H, d, dt = wl["B"], wl["Hkv"], wl["d"], wl["dtype"]
+    n = min(8, B * H)
+    Ks, Vs = [], []
+    for i in range(n):
+        k, v = inputs.slice_kv(cfg_id, i // H, i % H, 0, L, wl)
+        Ks.append(to_dev(k, dt))
+        Vs.append(to_dev(v, dt))
+    idx = torch.arange(B * H, device="cuda:0") % n
+    K = torch.stack(Ks)[idx].reshape(B, H, L, d).contiguous()
+    V = torch.stack(Vs)[idx].reshape(B, H, L, d).contiguous()
+    return K, V
+
+
+def time_launches(fn, n, stream, warm=20):
+    """fn(i) enqueues launch i; returns microseconds per launch over n back-to-back launches
+    between one HIP event before and one after, on `stream`."""
+    import torch
+    for i in range(warm):
+        fn(i)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for i in range(n):
+        fn(i)
+    e1.record(stream)
+    e1.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / n
+
+
+def compress_leg(binding, cfg, wl, dc, stream, calls=24):
+    """logquant_compress on a full window, timed on its own: the counts are put back to
+    n_fp = 3W before every call (the call only depends on the counts; the rows beyond the
+    live ones hold whatever the buffers held).  Returns (us per call, bytes moved per call)."""
+    import torch
+    W = wl["F"] // 2
+    Wq = slots_per_event(wl)
+    saved = dc.counts()
+    cur, n_fp, n_q = saved
+    sh = stream.cuda_stream
+    ts = []
+    for i in range(calls + 4):
+        dc.set_counts((cur, 3 * W, n_q))
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        st = binding.logquant_compress(cfg, dc.c, dc.workspace, sh)
+        e1.record(stream)
+        assert st == 0, binding.logquant_status_string(st)
+        if i >= 4:
+            ts.append((e0, e1))
+    torch.cuda.synchronize()
+    dc.set_counts(saved)
+    us = float(sorted(e0.elapsed_time(e1) * 1e3 for e0, e1 in ts)[len(ts) // 2])
+    d, G, bits = wl["d"], wl["G"], wl.get("bits", 2)
+    per_slice = 3 * W * 4 * d + W * (d * bits // 4 + 4 * -(-d // G)) + Wq // G * 4 * d + 2 * W * 4 * d
+    return us, wl["B"] * wl["Hkv"] * per_slice
+
+
+def read_ceiling(binding, nbytes, copies, stream, launches=200):
+    """Pure reading of as many bytes as one attention launch reads, rotating over `copies`
+    buffers: the measured HBM ceiling at this size (GB/s)."""
+    import torch
+    n = max(2, copies)
+    bufs = [torch.ones(max(16, int(nbytes)) // 16 * 16, dtype=torch.uint8, device="cuda:0") for _ in range(n)]
+    sink = torch.zeros(8192, dtype=torch.int32, device="cuda:0")
+    sh = stream.cuda_stream
+    torch.cuda.synchronize()
+
+    def fn(i):
+        st = binding.logquant_read_probe(bufs[i % n], bufs[0].numel(), sink, sh)
+        assert st == 0
+    us = time_launches(fn, launches, stream)
+    return {"us_per_launch": us, "bytes": int(bufs[0].numel()), "GBps": bufs[0].numel() / (us * 1e-6) / 1e9}
+
+
+def attention_config_leg(binding, wl, cfg_id, stream, launches=200):
+    """One of the other benchmark configs at its full size, in the launch shape the
+    library picks: decode attention back to back over a rotation of cache copies, and the
+    compress call on a full window.  States come from logquant_prefill on filler slices."""
+    import torch
+    W, L, dt = wl["F"] // 2, wl["L"], wl["dtype"]
+    qcap = q_capacity(wl)
+    cfg = binding.make_config(wl["B"], wl["Hq"], wl["Hkv"], wl["d"], wl["F"], wl["G"], dt, qcap, wl.get("bits", 2))
+    K, V = filler_kv_device(wl, cfg_id, L)
+    first = binding.DeviceCache(cfg)
+    first.prefill(K, V)
+    del K, V
+    plan = binding.logquant_decode_plan(cfg, first.c.n_fp, first.c.n_q)
+    copies = max(2, min(16, -(-(1 << 30) // max(1, plan.bytes_read))))
+    caches = [first] + [first.clone() for _ in range(copies - 1)]
+    from paper_2503_19950_amd import inputs
+    from paper_2503_19950_amd.binding import to_dev
+    q = to_dev(inputs.queries(cfg_id, 0, wl), dt)
+    out = torch.empty_like(q)
+    sh = stream.cuda_stream
+    torch.cuda.synchronize()
+
+    def fn(i):
+        dc = caches[i % copies]
+        st = binding.logquant_decode_attn(cfg, dc.c, q, 0.0, out, dc.workspace, sh)
+        assert st == 0
+    us = time_launches(fn, launches, stream)
+    comp_us, comp_bytes = compress_leg(binding, cfg, wl, caches[0], stream)
+    gbps = plan.bytes_read / (us * 1e-6) / 1e9
+    rec = {"workload": wl["name"], "B": wl["B"], "Hq": wl["Hq"], "Hkv": wl["Hkv"], "d": wl["d"], "L": L, "dtype": dt,
+           "group": wl["G"], "fp_budget": wl["F"], "n_fp": first.c.n_fp, "n_q": first.c.n_q,
+           "attn_blocks": plan.blocks, "attn_splits": plan.splits, "waves_per_block": plan.waves_per_block,
+           "cache_copies_rotated": copies, "launches_timed": launches,
+           "us_per_launch": us, "algorithmic_bytes": int(plan.bytes_read), "GBps": gbps, "frac": gbps / HBM_PEAK_GBS,
+           "kv_tokens_per_s": wl["B"] * L / (us * 1e-6),
+           "compress_us": comp_us, "compress_bytes": int(comp_bytes), "compress_GBps": comp_bytes / (comp_us * 1e-6) / 1e9}
+    if plan.bytes_read < (8 << 20):
+        rec["note"] = "latency-bound: %.1f MB per launch; a fraction of HBM peak says nothing here" % (plan.bytes_read / 1e6)
+    elif wl["B"] * wl["Hkv"] < 64:
+        rec["compress_note"] = "compress moves %.1f MB: launch-latency-bound" % (comp_bytes / 1e6)
+    del caches, first
+    torch.cuda.empty_cache()
+    return rec
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -129,7 +259,10 @@ def main():
     steps = a.steps or W
     if a.per_sequence:
         return main_per_sequence(a, wl, steps)
-    plan0 = None
+    # everything is enqueued on one non-default stream (default priority); the events that time
+    # the kernels are recorded on that same stream
+    stream = torch.cuda.Stream()
+    torch.cuda.set_stream(stream)
     # enough copies that the rotation's footprint is >= 1 GiB (4x the 256 MB last-level cache)
     cfg_probe = binding.make_config(wl["B"], wl["Hq"], wl["Hkv"], wl["d"], wl["F"], wl["G"], dt,
                                     q_capacity(wl), a.bits)
@@ -147,14 +280,18 @@ def main():
     newV = to_dev(newV, dt).permute(2, 0, 1, 3).unsqueeze(3).contiguous()
     qs = to_dev(np.stack([inputs.queries(a.workload, s, wl) for s in range(n_in)]), dt)
     out = torch.empty_like(qs[0])
-    stream = torch.cuda.current_stream()
     sh = stream.cuda_stream
+    torch.cuda.synchronize()
 
     fused = not a.unfused
+    attend = binding.logquant_decode_attn
+    if a.plain_valu:
+        from paper_2503_19950_amd import plain_reference
+        attend = plain_reference.logquant_plain_decode_attn
+        fused = False
 
     def run(n, record):
-        """n steps; returns per-kernel event pairs when record is True (then with the
-        separate append / compress / attention calls, so that each can be bracketed)."""
+        """n steps of the hot path; with record, HIP events around every attention launch."""
         ev = []
         n_compress = 0
         visits = [0] * len(caches)
@@ -171,24 +308,17 @@ def main():
             st = binding.logquant_append(cfg, dc.c, newK[j], newV[j], 1, sh)
             assert st == 0, binding.logquant_status_string(st)
             if dc.c.n_fp == 3 * W:
-                if record:
-                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    e0.record(stream)
                 st = binding.logquant_compress(cfg, dc.c, dc.workspace, sh)
                 assert st == 0, binding.logquant_status_string(st)
                 n_compress += 1
-                if record:
-                    e1.record(stream)
-                    ev.append(("compress", e0, e1, 0))
             if record:
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                nbytes = binding.logquant_decode_plan(cfg, dc.c.n_fp, dc.c.n_q).bytes_read
                 e0.record(stream)
-            st = binding.logquant_decode_attn(cfg, dc.c, qs[s], 0.0, out, dc.workspace, sh)
+            st = attend(cfg, dc.c, qs[s], 0.0, out, dc.workspace, sh)
             assert st == 0, binding.logquant_status_string(st)
             if record:
                 e1.record(stream)
-                ev.append(("attn", e0, e1, nbytes))
+                ev.append((e0, e1))
         return ev, n_compress
 
     saved = [dc.counts() for dc in caches]
@@ -197,7 +327,7 @@ def main():
     for dc, c in zip(caches, saved):
         dc.set_counts(c)
 
-    # timed region 1: the whole hot path, K steps, wall clock
+    # timed region 1: the whole hot path, K steps, wall clock between two synchronisations
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     _, n_compress = run(steps, False)
@@ -207,41 +337,37 @@ def main():
     for dc, c in zip(caches, saved):
         dc.set_counts(c)
 
-    # timed region 2: the same K steps with HIP events around every attention / compress
-    # launch (same stream), for the per-kernel durations the roofline is computed from
-    ev, _ = run(steps, True)
+    # timed region 2: single attention launches bracketed by an event pair each (the pair costs
+    # a few microseconds itself): spread of single launches
+    ev, _ = run(min(steps, 64), True)
     torch.cuda.synchronize()
-    attn = [(e0.elapsed_time(e1) * 1e3, nb) for k, e0, e1, nb in ev if k == "attn"]
-    comp = [e0.elapsed_time(e1) * 1e3 for k, e0, e1, nb in ev if k == "compress"]
-    attn_event_us = float(np.mean([t for t, _ in attn]))   # includes the event markers' own cost
-    attn_event_pct = [float(x) for x in np.percentile([t for t, _ in attn], [10, 50, 90])]
-
-    # timed region 3: the attention launches alone, back to back on the launch stream,
-    # rotating over the cache copies, one HIP event before and one after.  Kernel
-    # durations measured this way agree with rocprofv3's kernel trace (an event pair
-    # around every single launch adds several microseconds of marker cost), so the
-    # roofline figures are taken from here.
+    attn_event_pct = [float(x) for x in np.percentile([e0.elapsed_time(e1) * 1e3 for e0, e1 in ev], [10, 50, 90])]
     for dc, c in zip(caches, saved):
         dc.set_counts(c)
+
+    # timed region 3: the attention launches alone, back to back on the launch stream, rotating
+    # over the cache copies, one HIP event before and one after.  Kernel durations measured
+    # this way agree with rocprofv3's kernel trace; the roofline figures are taken from here.
     nb2b = max(200, steps)
-    for s in range(20):
-        binding.logquant_decode_attn(cfg, caches[s % len(caches)].c, qs[0], 0.0, out,
-                                     caches[s % len(caches)].workspace, sh)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record(stream)
-    for s in range(nb2b):
-        dc = caches[s % len(caches)]
-        binding.logquant_decode_attn(cfg, dc.c, qs[0], 0.0, out, dc.workspace, sh)
-    e1.record(stream)
-    torch.cuda.synchronize()
-    b2b_us = e0.elapsed_time(e1) * 1e3 / nb2b
-    b2b_bytes = float(np.mean([binding.logquant_decode_plan(cfg, caches[s % len(caches)].c.n_fp,
-                                                            caches[s % len(caches)].c.n_q).bytes_read
-                               for s in range(nb2b)]))
-    attn_us, attn_bytes = b2b_us, b2b_bytes
+
+    def attn_fn(i):
+        dc = caches[i % len(caches)]
+        st = attend(cfg, dc.c, qs[0], 0.0, out, dc.workspace, sh)
+        assert st == 0
+    attn_us = time_launches(attn_fn, nb2b, stream)
+    attn_bytes = float(np.mean([binding.logquant_decode_plan(cfg, caches[s % len(caches)].c.n_fp,
+                                                             caches[s % len(caches)].c.n_q).bytes_read
+                                for s in range(nb2b)]))
     achieved = attn_bytes / (attn_us * 1e-6) / 1e9
 
+    # timed region 4: logquant_compress on a full window, on its own
+    comp_us, comp_bytes = compress_leg(binding, cfg, wl, caches[1], stream)
+
+    # the machine's pure-read ceiling at this size, live
+    ceiling = read_ceiling(binding, attn_bytes, len(caches), stream)
+
     plan = binding.logquant_decode_plan(cfg, caches[1].c.n_fp, caches[1].c.n_q)
+    counters = stored_counters(wl["name"])
     result = {
         "metric": "decode-attn effective KV tokens/sec",
         "value": wl["B"] * L / (ms_per_step * 1e-3),
@@ -252,15 +378,23 @@ def main():
         "config": {"workload": wl["name"], "B": wl["B"], "Hq": wl["Hq"], "Hkv": wl["Hkv"],
                    "d": wl["d"], "L": L, "group": wl["G"], "fp_budget": wl["F"], "bits": wl["bits"],
                    "cache_copies_rotated": len(caches), "compress_events_in_timed_region": n_compress,
-                   "fused_append": not a.unfused, "attn_blocks": plan.blocks, "attn_splits": plan.splits},
+                   "fused_append": fused, "attn_blocks": plan.blocks, "attn_splits": plan.splits,
+                   "stream": "non-default", "attention_kernel": "plain vector-unit" if a.plain_valu else "matrix-instruction"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": read_traffic(wl["name"]),
+                     "traffic_source": "stored: profiles/decode_attn_%s_hbm_traffic.txt (rocprofv3 --pmc runs)" % wl["name"],
                      "kernel": "decode attention", "us_per_launch": attn_us,
                      "algorithmic_bytes_per_launch": attn_bytes, "launches_timed": nb2b,
-                     "in_step_loop_event_pair_us": attn_event_us,
                      "single_launch_event_pair_us_p10_p50_p90": attn_event_pct,
-                     "plain_copy_reference_GBps": plain_copy_reference()},
-        "compress_us_per_call": float(np.mean(comp)) if comp else None,
+                     "measured_read_ceiling": ceiling,
+                     "frac_of_measured_read_ceiling": achieved / ceiling["GBps"],
+                     "other_roofs": counters},
+        "compress_us_per_call": comp_us,
+        "compress": {"us_per_call": comp_us, "bytes_moved": int(comp_bytes), "GBps": comp_bytes / (comp_us * 1e-6) / 1e9,
+                     "calls_timed": 24,
+                     "note": "latency-bound at this batch (%.1f MB per call)" % (comp_bytes / 1e6) if comp_bytes < (32 << 20) else None},
+        "kv_tokens_per_s_attention_only": wl["B"] * L / (attn_us * 1e-6),
         "token_heads_per_s": wl["B"] * wl["Hkv"] * L / (ms_per_step * 1e-3),
         "prefill": prefill,
         "state_build_s": t_build,
@@ -272,7 +406,15 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         result["calibration_copy_bytes"] = 256 << 20
-    result["roofline"]["traffic"] = read_traffic(wl["name"])
+    del caches
+    torch.cuda.empty_cache()
+    if not a.no_per_config and not a.plain_valu and a.bits == 2 and not a.fp_budget:
+        per = []
+        for w in (1, 2, 4, 5):
+            if w == a.workload:
+                continue
+            per.append(attention_config_leg(binding, dict(inputs.WORKLOADS[w], bits=2), w, stream))
+        result["per_config"] = per
     if not a.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, a.workload)
     print(json.dumps(result), flush=True)
@@ -368,23 +510,28 @@ def main_per_sequence(a, wl, steps):
                      "launches_timed": nb2b}}), flush=True)
 
 
-def plain_copy_reference():
-    """What plain streaming reaches on this machine, for scale: a device-to-device copy of 1 GiB
-    (four times the last-level cache), bytes read plus bytes written over time, best of 5."""
-    import torch
-    src = torch.ones(1 << 30, dtype=torch.uint8, device="cuda:0")
-    dst = torch.empty_like(src)
-    best = None
-    for i in range(7):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        dst.copy_(src)
-        e1.record()
-        torch.cuda.synchronize()
-        if i >= 2:
-            t = e0.elapsed_time(e1)
-            best = t if best is None else min(best, t)
-    return 2.0 * src.numel() / (best * 1e-3) / 1e9
+def stored_counters(workload_name):
+    """Instruction-issue roofs of the attention kernel from the stored rocprofv3 --pmc summary
+    (profiles/decode_attn_<workload>_instruction_counters.txt): the time the vector and the
+    matrix instructions of one launch take if nothing else limits them (256 compute units x
+    4 SIMDs, 2.4 GHz, 4 cycles per vector instruction), beside the HBM roofs above."""
+    path = os.path.join(ROOT, "profiles", "decode_attn_%s_instruction_counters.txt" % workload_name)
+    vals = {}
+    try:
+        for line in open(path):
+            parts = line.split()
+            if len(parts) == 2 and parts[0].startswith("SQ_"):
+                vals[parts[0]] = float(parts[1])
+    except OSError:
+        return None
+    if "SQ_INSTS_VALU" not in vals:
+        return None
+    simds, hz = 1024.0, 2.4e9
+    out = {"source": "stored: profiles/decode_attn_%s_instruction_counters.txt" % workload_name,
+           "valu_issue_us": vals["SQ_INSTS_VALU"] * 4.0 / simds / hz * 1e6}
+    if "SQ_VALU_MFMA_BUSY_CYCLES" in vals:
+        out["mfma_busy_us"] = vals["SQ_VALU_MFMA_BUSY_CYCLES"] / simds / hz * 1e6
+    return out
 
 
 def read_traffic(workload_name):

@@ -239,7 +239,15 @@ lq_status logquant_decode_step(const lq_config *cfg, lq_cache *cache, const void
                                void *workspace, void *stream);
 
 /* Launch shape logquant_decode_attn would use for these counts (HOST out), so a
- * harness can report bytes per launch; pure host arithmetic. */
+ * harness can report bytes per launch; pure host arithmetic.
+ * The planner reads four environment variables, once per process, as overrides for
+ * experiments and for the tests that force every kernel shape (unset or 0: the planner
+ * decides; results do not depend on them beyond the order of the fp32 sums):
+ *   LOGQUANT_ATTN_WPB      wavefronts per workgroup: 4, 8 or 12
+ *   LOGQUANT_ATTN_SPLITS   context splits per (batch row, kv head, head group)
+ *   LOGQUANT_ATTN_CUS      compute units to plan for (default 256)
+ *   LOGQUANT_ATTN_DYNAMIC  0: static tile schedule (default 1: tiles drawn from pool
+ *                          counters when a wavefront has five or more) */
 typedef struct {
   int32_t blocks;           /* workgroups of the attention kernel                    */
   int32_t waves_per_block;
@@ -303,6 +311,14 @@ lq_status logquant_decode_step_seq(const lq_config *cfg, lq_cache_seq *cache, co
  * bytes_read summed over the rows; fp_waves is the longest row's share. */
 lq_status logquant_decode_plan_seq(const lq_config *cfg, const int32_t *n_fp, const int32_t *n_q,
                                    lq_plan *out);
+
+/* Measurement helper (not a step of the method): one streaming read of `bytes` bytes of
+ * DEVICE memory at `buf` (16-byte aligned, bytes >= 16; a tail of bytes % 16 is not read),
+ * enqueued on `stream`.  `sink`: DEVICE, 8192 uint32 words the kernel folds what it read
+ * into (so that the reads cannot be optimised away).  The benchmark uses it to report what
+ * plain reading reaches for the byte count of one decode-attention launch (the HBM roofline
+ * of Sec. 3.2.4's memory-bound decode step, measured rather than nominal). */
+lq_status logquant_read_probe(const void *buf, size_t bytes, void *sink, void *stream);
 
 const char *logquant_status_string(lq_status s);
 

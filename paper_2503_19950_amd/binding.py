@@ -60,7 +60,7 @@ EXPORTS = ("logquant_sizes", "logquant_workspace_bytes", "logquant_workspace_ini
            "logquant_decode_step", "logquant_decode_plan",
            "logquant_seq_state_bytes", "logquant_prefill_seq", "logquant_append_seq", "logquant_compress_seq",
            "logquant_decode_attn_seq", "logquant_decode_step_seq", "logquant_decode_plan_seq",
-           "logquant_status_string")
+           "logquant_read_probe", "logquant_status_string")
 
 if not os.path.exists(LIB_PATH):
     raise ImportError("liblogquant.so is not built: run `python -m paper_2503_19950_amd.build` "
@@ -114,6 +114,8 @@ _lib.logquant_decode_step_seq.argtypes = [C.POINTER(lq_config), C.POINTER(lq_cac
 _lib.logquant_decode_step_seq.restype = C.c_int
 _lib.logquant_decode_plan_seq.argtypes = [C.POINTER(lq_config), _I32P, _I32P, C.POINTER(lq_plan)]
 _lib.logquant_decode_plan_seq.restype = C.c_int
+_lib.logquant_read_probe.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+_lib.logquant_read_probe.restype = C.c_int
 _lib.logquant_status_string.argtypes = [C.c_int]
 _lib.logquant_status_string.restype = C.c_char_p
 
@@ -242,6 +244,10 @@ def logquant_decode_plan_seq(cfg, n_fp, n_q):
     if st != LQ_OK:
         raise LogQuantError(st, "logquant_decode_plan_seq")
     return out
+
+
+def logquant_read_probe(buf, nbytes, sink, stream=0):
+    return _lib.logquant_read_probe(_ptr(buf), int(nbytes), _ptr(sink), stream)
 
 
 def torch_dtype(dtype):

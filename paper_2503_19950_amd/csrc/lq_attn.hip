@@ -7,13 +7,9 @@
 
 namespace lq {
 
-hipError_t launch_decode_attn_ref(const Shape& s, const lq_cache& c, const void* q, float scale,
-                                  void* out, const Workspace& ws, int splits, hipStream_t st, const SeqArg* seq);
 hipError_t launch_decode_attn_mfma(const Shape& s, const lq_cache& c, const void* q, float scale,
                                    void* out, const Workspace& ws, const lq_plan& plan, hipStream_t st,
                                    const void* k_new, const void* v_new, const SeqArg* seq);
-hipError_t launch_append_seq(const Shape& s, const lq_cache& c, const void* k_new, const void* v_new,
-                             const SeqArg* seq, hipStream_t st);
 
 static int env_int(const char* name, int dflt) {
   const char* v = getenv(name);
@@ -105,15 +101,8 @@ void plan_decode(const Shape& s, int n_fp, int n_q, lq_plan* plan, bool per_sequ
   plan->bytes_read = cache_bytes_read(s, n_fp, n_q);
 }
 
-// LOGQUANT_ATTN_PLAIN=1 selects the plain one-token-at-a-time kernel (cross-check).
-static bool plain_attention() {
-  static const int plain = env_int("LOGQUANT_ATTN_PLAIN", 0);
-  return plain != 0;
-}
-
 hipError_t launch_decode_attn(const Shape& s, const lq_cache& c, const void* q, float scale,
                               void* out, const Workspace& ws, const lq_plan& plan, hipStream_t st, const SeqArg* seq) {
-  if (plain_attention()) return launch_decode_attn_ref(s, c, q, scale, out, ws, plan.splits, st, seq);
   return launch_decode_attn_mfma(s, c, q, scale, out, ws, plan, st, nullptr, nullptr, seq);
 }
 
@@ -122,18 +111,6 @@ hipError_t launch_decode_attn(const Shape& s, const lq_cache& c, const void* q, 
 hipError_t launch_decode_step(const Shape& s, const lq_cache& c, const void* k_new, const void* v_new,
                               const void* q, float scale, void* out, const Workspace& ws, const lq_plan& plan,
                               hipStream_t st, const SeqArg* seq) {
-  if (plain_attention()) {
-    hipError_t e;
-    if (seq) {
-      e = launch_append_seq(s, c, k_new, v_new, seq, st);   // entries already count the new row
-    } else {
-      lq_cache before = c;
-      before.n_fp -= 1;
-      e = launch_append(s, before, k_new, v_new, 1, st);
-    }
-    if (e != hipSuccess) return e;
-    return launch_decode_attn_ref(s, c, q, scale, out, ws, plan.splits, st, seq);
-  }
   return launch_decode_attn_mfma(s, c, q, scale, out, ws, plan, st, k_new, v_new, seq);
 }
 

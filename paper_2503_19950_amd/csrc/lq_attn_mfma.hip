@@ -1103,64 +1103,6 @@ attn_mfma_kernel(const AttnParams P, const SeqArgs<GENERAL> S) {
   }
 }
 
-// Log-sum-exp merge of the splits' partials (softmax normalisation of Eq. 2).
-// One workgroup per (batch row, query head); threads = channels x PARTS, each part
-// takes every PARTS-th split.
-template <bool BF16>
-__global__ void __launch_bounds__(512)
-combine_kernel(const float* __restrict__ ws, uint16_t* __restrict__ out, int d, int gh, int splits) {
-  __shared__ float w_s[256];        // weight of each split (splits <= 256)
-  __shared__ float red[512];
-  __shared__ float stat[2];
-  const int bhq = blockIdx.x, tid = threadIdx.x;
-  const int bh = bhq / gh, g = bhq % gh;
-  const int64_t stride = (int64_t)gh * (d + 4);
-  const float* base = ws + ((int64_t)bh * splits * gh + g) * (d + 4);
-  // weights: w_s = 2^(m_s - M); L = sum_s w_s l_s
-  float m = -INFINITY, l = 0.f;
-  if (tid < splits) { m = base[tid * stride + d]; l = base[tid * stride + d + 1]; }
-  red[tid] = m;
-  __syncthreads();
-  for (int k = 256; k >= 1; k >>= 1) {
-    if (tid < k) red[tid] = fmaxf(red[tid], red[tid + k]);
-    __syncthreads();
-  }
-  const float M = red[0];
-  __syncthreads();
-  const float w = (tid < splits && m != -INFINITY) ? exp2f(m - M) : 0.f;
-  if (tid < 256) w_s[tid] = w;
-  red[tid] = w * l;
-  __syncthreads();
-  for (int k = 256; k >= 1; k >>= 1) {
-    if (tid < k) red[tid] += red[tid + k];
-    __syncthreads();
-  }
-  if (tid == 0) stat[0] = red[0];
-  __syncthreads();
-  const float L = stat[0];
-  __syncthreads();
-  const int parts = 512 / d;
-  const int c = tid % d, part = tid / d;
-  float acc = 0.f;
-  if (part < parts) {
-#pragma unroll 8
-    for (int s = part; s < splits; s += parts) acc = fmaf(w_s[s], base[s * stride + c], acc);
-  }
-  red[tid] = acc;
-  __syncthreads();
-  if (tid < d) {
-    float o = 0.f;
-    for (int pth = 0; pth < parts; ++pth) o += red[pth * d + tid];
-    out[(int64_t)bhq * d + tid] = f2t<BF16>(o / L);
-  }
-}
-
-hipError_t launch_combine(const Shape& s, const float* ws, void* out, int splits, hipStream_t st) {
-  auto kern = s.bf16 ? combine_kernel<true> : combine_kernel<false>;
-  hipLaunchKernelGGL(kern, dim3(s.B * s.Hq), dim3(512), 0, st, ws, (uint16_t*)out, s.d, s.gh, splits);
-  return launch_status(__func__);
-}
-
 template <bool BF16, int D, int NWB, int BITS>
 static hipError_t launch_mfma_dg(const Shape& s, const AttnParams& P, const SeqArg* seq, dim3 grid, hipStream_t st) {
   if constexpr (NWB == 8 || NWB == 12) {

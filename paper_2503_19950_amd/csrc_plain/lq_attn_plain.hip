@@ -1,11 +1,17 @@
 // Decode attention, plain formulation (Eq. 2 with Eq. 6's 1/sqrt(d); Sec. 2.4: one
-// softmax over the original-precision rows and the dequantized rows).  One
-// wavefront walks tokens one at a time, lanes own channels, the running
-// (max, sum, output) triple is merged across wavefronts and context splits.
-// Slow and simple: it reads every element through the layout index functions.
-// Kept as the cross-check of the matrix-instruction kernel.
-#include "lq_device.h"
-#include "lq_internal.h"
+// softmax over the original-precision rows and the dequantized rows) on the vector unit.
+// One wavefront walks tokens one at a time, lanes own channels, the running
+// (max, sum, output) triple is merged across wavefronts and context splits by a second
+// launch.  Slow and simple: it reads every element through the layout index functions.
+//
+// NOT part of the product library: this file is built into liblogquant_plain.so, which
+// only the tests (cross-check of the matrix-instruction kernel) and the benchmark's
+// --plain-valu measurement (matrix unit against vector unit) load.  It takes shapes,
+// plans and the workspace layout from liblogquant.so.
+#include <math.h>
+
+#include "../csrc/lq_device.h"
+#include "../csrc/lq_internal.h"
 
 namespace lq {
 
@@ -132,45 +138,108 @@ attn_ref_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_f
   }
 }
 
-hipError_t launch_combine(const Shape& s, const float* ws, void* out, int splits, hipStream_t st);
+// Log-sum-exp merge of the splits' partials (softmax normalisation of Eq. 2).
+// One workgroup per (batch row, query head); threads = channels x PARTS, each part
+// takes every PARTS-th split.
+template <bool BF16>
+__global__ void __launch_bounds__(512)
+combine_kernel(const float* __restrict__ ws, uint16_t* __restrict__ out, int d, int gh, int splits) {
+  __shared__ float w_s[256];        // weight of each split (splits <= 256)
+  __shared__ float red[512];
+  __shared__ float stat[2];
+  const int bhq = blockIdx.x, tid = threadIdx.x;
+  const int bh = bhq / gh, g = bhq % gh;
+  const int64_t stride = (int64_t)gh * (d + 4);
+  const float* base = ws + ((int64_t)bh * splits * gh + g) * (d + 4);
+  // weights: w_s = 2^(m_s - M); L = sum_s w_s l_s
+  float m = -INFINITY, l = 0.f;
+  if (tid < splits) { m = base[tid * stride + d]; l = base[tid * stride + d + 1]; }
+  red[tid] = m;
+  __syncthreads();
+  for (int k = 256; k >= 1; k >>= 1) {
+    if (tid < k) red[tid] = fmaxf(red[tid], red[tid + k]);
+    __syncthreads();
+  }
+  const float M = red[0];
+  __syncthreads();
+  const float w = (tid < splits && m != -INFINITY) ? exp2f(m - M) : 0.f;
+  if (tid < 256) w_s[tid] = w;
+  red[tid] = w * l;
+  __syncthreads();
+  for (int k = 256; k >= 1; k >>= 1) {
+    if (tid < k) red[tid] += red[tid + k];
+    __syncthreads();
+  }
+  if (tid == 0) stat[0] = red[0];
+  __syncthreads();
+  const float L = stat[0];
+  __syncthreads();
+  const int parts = 512 / d;
+  const int c = tid % d, part = tid / d;
+  float acc = 0.f;
+  if (part < parts) {
+#pragma unroll 8
+    for (int s = part; s < splits; s += parts) acc = fmaf(w_s[s], base[s * stride + c], acc);
+  }
+  red[tid] = acc;
+  __syncthreads();
+  if (tid < d) {
+    float o = 0.f;
+    for (int pth = 0; pth < parts; ++pth) o += red[pth * d + tid];
+    out[(int64_t)bhq * d + tid] = f2t<BF16>(o / L);
+  }
+}
+
+static hipError_t launch_combine(const Shape& s, const float* ws, void* out, int splits, hipStream_t st) {
+  auto kern = s.bf16 ? combine_kernel<true> : combine_kernel<false>;
+  hipLaunchKernelGGL(kern, dim3(s.B * s.Hq), dim3(512), 0, st, ws, (uint16_t*)out, s.d, s.gh, splits);
+  return launch_status(__func__);
+}
 
 template <bool BF16, int HB>
-static hipError_t launch_ref_t(const Shape& s, const lq_cache& c, const void* q, float scale,
-                               void* ws, int splits, hipStream_t st, const SeqState* seq) {
+static hipError_t launch_plain_t(const Shape& s, const lq_cache& c, const void* q, float scale,
+                                 void* ws, int splits, hipStream_t st) {
   dim3 grid(splits, s.B * s.Hkv * (s.gh / HB));
-  const int first = seq ? 0 : c.cur;
   hipLaunchKernelGGL((attn_ref_kernel<BF16, HB>), grid, dim3(256), 0, st, (const uint16_t*)q,
-                     (const uint16_t*)c.k_fp[first], (const uint16_t*)c.v_fp[first],
-                     (const uint16_t*)c.k_fp[first ^ 1], (const uint16_t*)c.v_fp[first ^ 1], seq, c.k_codes,
-                     c.v_codes, (const uint16_t*)c.k_scale, (const uint16_t*)c.k_zero,
+                     (const uint16_t*)c.k_fp[c.cur], (const uint16_t*)c.v_fp[c.cur],
+                     (const uint16_t*)c.k_fp[c.cur ^ 1], (const uint16_t*)c.v_fp[c.cur ^ 1], (const SeqState*)nullptr,
+                     c.k_codes, c.v_codes, (const uint16_t*)c.k_scale, (const uint16_t*)c.k_zero,
                      (const uint16_t*)c.v_scale, (const uint16_t*)c.v_zero, (float*)ws, s.d, s.G,
                      s.cap, s.qcap, c.n_fp, c.n_q, s.gh, splits, scale * 1.4426950408889634f, s.bits,
                      s.W, s.Wq, s.Hkv);
   return launch_status(__func__);
 }
 
-hipError_t launch_decode_attn_ref(const Shape& s, const lq_cache& c, const void* q, float scale,
-                                  void* out, const Workspace& ws_all, int splits, hipStream_t st, const SeqArg* arg) {
-  // this kernel reads per-sequence state from the device array only: fill it here when
-  // the batch is small enough that the caller left it to the launch's arguments
-  const SeqState* seq = arg ? arg->dev : nullptr;
-  if (arg && arg->in_args() &&
-      launch_seq_upload(const_cast<SeqState*>(arg->dev), arg->host, arg->n, st) != hipSuccess)
-    return hipErrorLaunchFailure;
-  void* ws = ws_all.partials;
+}  // namespace lq
+
+using namespace lq;
+
+// Same arguments, requirements and results as logquant_decode_attn (lock-step batch); the
+// context is cut into the number of splits the product's planner picks.
+extern "C" lq_status logquant_plain_decode_attn(const lq_config* cfg, const lq_cache* cache, const void* q,
+                                                float softmax_scale, void* out, void* workspace, void* stream) {
+  if (!cfg || !cache || !q || !out || !workspace) return LQ_ERR_NULL;
+  Shape s;
+  lq_status st = make_shape(cfg, &s);
+  if (st != LQ_OK) return st;
+  if (cache->n_fp + cache->n_q < 1) return LQ_ERR_STATE;
+  lq_plan plan;
+  plan_decode(s, cache->n_fp, cache->n_q, &plan);
+  if (!(softmax_scale > 0.f)) softmax_scale = 1.0f / sqrtf((float)s.d);
+  clear_stale_error();
+  void* ws = split_workspace(s, workspace).partials;
   const int hb = s.gh % 4 == 0 ? 4 : (s.gh % 2 == 0 ? 2 : 1);
+  hipStream_t hs = (hipStream_t)stream;
   hipError_t e;
   if (s.bf16) {
-    e = hb == 4 ? launch_ref_t<true, 4>(s, c, q, scale, ws, splits, st, seq)
-        : hb == 2 ? launch_ref_t<true, 2>(s, c, q, scale, ws, splits, st, seq)
-                  : launch_ref_t<true, 1>(s, c, q, scale, ws, splits, st, seq);
+    e = hb == 4 ? launch_plain_t<true, 4>(s, *cache, q, softmax_scale, ws, plan.splits, hs)
+        : hb == 2 ? launch_plain_t<true, 2>(s, *cache, q, softmax_scale, ws, plan.splits, hs)
+                  : launch_plain_t<true, 1>(s, *cache, q, softmax_scale, ws, plan.splits, hs);
   } else {
-    e = hb == 4 ? launch_ref_t<false, 4>(s, c, q, scale, ws, splits, st, seq)
-        : hb == 2 ? launch_ref_t<false, 2>(s, c, q, scale, ws, splits, st, seq)
-                  : launch_ref_t<false, 1>(s, c, q, scale, ws, splits, st, seq);
+    e = hb == 4 ? launch_plain_t<false, 4>(s, *cache, q, softmax_scale, ws, plan.splits, hs)
+        : hb == 2 ? launch_plain_t<false, 2>(s, *cache, q, softmax_scale, ws, plan.splits, hs)
+                  : launch_plain_t<false, 1>(s, *cache, q, softmax_scale, ws, plan.splits, hs);
   }
-  if (e != hipSuccess) return e;
-  return launch_combine(s, (const float*)ws, out, splits, st);
+  if (e != hipSuccess) return LQ_ERR_HIP;
+  return launch_combine(s, (const float*)ws, out, plan.splits, hs) == hipSuccess ? LQ_OK : LQ_ERR_HIP;
 }
-
-}  // namespace lq

@@ -1,7 +1,7 @@
 """The launch planner picks the workgroup shape of the attention kernel (4, 8 or 12
 wavefronts) from the workload; small test cases only ever get one of them.  Here a few
-parity cases are run again in child processes with each shape forced, and with the plain
-one-token-at-a-time kernel (the environment knobs are read once per process)."""
+parity cases are run again in child processes with each shape forced (the planner's
+environment overrides are read once per process)."""
 import os
 import subprocess
 import sys
@@ -15,8 +15,7 @@ CASES = "cfg1 or d64_gqa2_ragged or mha_d96_g64_bf16_midwindow or d128_g128_gqa8
         "or fused_decode_step"
 
 
-@pytest.mark.parametrize("knob", ["LOGQUANT_ATTN_WPB=12", "LOGQUANT_ATTN_WPB=4", "LOGQUANT_ATTN_PLAIN=1",
-                                  "LOGQUANT_ATTN_DYNAMIC=0"])
+@pytest.mark.parametrize("knob", ["LOGQUANT_ATTN_WPB=12", "LOGQUANT_ATTN_WPB=4", "LOGQUANT_ATTN_DYNAMIC=0"])
 def test_parity_cases_with_forced_kernel_variant(knob):
     env = dict(os.environ)
     k, v = knob.split("=")
