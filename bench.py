@@ -514,7 +514,8 @@ def stored_counters(workload_name):
     """Instruction-issue roofs of the attention kernel from the stored rocprofv3 --pmc summary
     (profiles/decode_attn_<workload>_instruction_counters.txt): the time the vector and the
     matrix instructions of one launch take if nothing else limits them (256 compute units x
-    4 SIMDs, 2.4 GHz, 4 cycles per vector instruction), beside the HBM roofs above."""
+    4 SIMDs, 2.4 GHz, 4 cycles per vector instruction; SQ_INSTS_VALU counts the matrix
+    instructions too, so they are taken off), beside the HBM roofs above."""
     path = os.path.join(ROOT, "profiles", "decode_attn_%s_instruction_counters.txt" % workload_name)
     vals = {}
     try:
@@ -528,7 +529,7 @@ def stored_counters(workload_name):
         return None
     simds, hz = 1024.0, 2.4e9
     out = {"source": "stored: profiles/decode_attn_%s_instruction_counters.txt" % workload_name,
-           "valu_issue_us": vals["SQ_INSTS_VALU"] * 4.0 / simds / hz * 1e6}
+           "valu_issue_us": (vals["SQ_INSTS_VALU"] - vals.get("SQ_INSTS_MFMA", 0.0)) * 4.0 / simds / hz * 1e6}
     if "SQ_VALU_MFMA_BUSY_CYCLES" in vals:
         out["mfma_busy_us"] = vals["SQ_VALU_MFMA_BUSY_CYCLES"] / simds / hz * 1e6
     return out
