@@ -56,6 +56,34 @@ struct Encoder {
   }
 };
 
+// Minimum and maximum over the lanes that differ in the bits CPW .. 32 of the lane index
+// (CPW = 8 or 16), by wavefront shuffles: a rotation by 8 inside the row of 16 lanes, then the
+// swap instructions, which trade rows (halves) between two registers - swapping a register
+// with a copy of itself leaves one holding the even rows (lower half) twice and the other the
+// odd rows (upper half) twice, so the minimum of the two is the minimum over both.
+template <int CPW>
+__device__ __forceinline__ void reduce_over_parts(float* mn, float* mx) {
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    if constexpr (CPW <= 8) {
+      mn[k] = fminf(mn[k], __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(mn[k]), 0x128, 0xF, 0xF, false)));   // row_ror:8
+      mx[k] = fmaxf(mx[k], __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(mx[k]), 0x128, 0xF, 0xF, false)));
+    }
+    {
+      const auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(mn[k]), __float_as_uint(mn[k]), false, false);
+      const auto b = __builtin_amdgcn_permlane16_swap(__float_as_uint(mx[k]), __float_as_uint(mx[k]), false, false);
+      mn[k] = fminf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+      mx[k] = fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+    }
+    {
+      const auto a = __builtin_amdgcn_permlane32_swap(__float_as_uint(mn[k]), __float_as_uint(mn[k]), false, false);
+      const auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx[k]), __float_as_uint(mx[k]), false, false);
+      mn[k] = fminf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+      mx[k] = fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+    }
+  }
+}
+
 // Eight codes (one byte each, in x: elements 0..3, y: elements 4..7) -> the operand
 // order of the packed layouts: element i at bit BITS*(i>>1) + 16*(i&1).
 template <int BITS>
@@ -185,66 +213,77 @@ struct PromptSource {
 // Slots past a short group (the last group of an event when G does not divide W) get
 // zero codes, zero value scales and zero-points and position -1; the key statistics
 // run over the ng rows only.  The staged rows past ng are zeros.
-// 256 threads.  LDS: sm = G * (d + 4) uint16 (the staged rows), cb = QG_CODE_BYTES
+// 256 threads.  LDS: sm = staged_bytes(d, G) (the staged rows), cb = QG_CODE_BYTES
 // bytes (the codes, one byte each: keys [token][d + 4], values transposed
 // [channel][G + 4], so that the eight codes of a packed operand are two aligned
-// 32-bit reads), red = 8 * 128 floats.
+// 32-bit reads).
+// Row pitch (in elements) of the staged KEY rows: the key statistics read one 32-bit word per
+// lane with lane = part * CPW + pair and part's rows per * pitch / 2 words apart; the pitch is
+// the one of d + 4, d + 6, .. that spreads a wavefront's 64 reads most evenly over the 32 LDS banks.
+constexpr int key_pitch(int d, int G) {
+  const int parts = d == 96 ? 4 : 512 / d, per = G / parts, cpw = 64 / parts;
+  int best = d + 4, best_worst = 1 << 30;
+  for (int pitch = d + 4; pitch <= d + 36; pitch += 2) {
+    int hits[32] = {};
+    for (int part = 0; part < parts; ++part)
+      for (int cl = 0; cl < cpw; ++cl) ++hits[(part * per * (pitch / 2) + cl) % 32];
+    int worst = 0;
+    for (int b = 0; b < 32; ++b) worst = hits[b] > worst ? hits[b] : worst;
+    if (worst < best_worst) { best_worst = worst; best = pitch; }
+  }
+  return best;
+}
+// LDS bytes of the staged rows: key pitch or value pitch (d + 4), whichever is larger
+constexpr int staged_bytes(int d, int G) { return G * (key_pitch(d, G) > d + 4 ? key_pitch(d, G) : d + 4) * 2; }
+
 template <int d, int G>
 constexpr int QG_CODE_BYTES = (G * (d + 4) > d * (G + 4) ? G * (d + 4) : d * (G + 4));
 
 template <bool BF16, int d, int G, int BITS, bool FULL, class Src>
 __device__ __forceinline__ void quantize_group_t(
-    uint16_t* sm, uint8_t* cb, float* red, const Src& src, int ng_in, int bh, int q0, uint32_t* __restrict__ k_codes,
+    uint16_t* sm, uint8_t* cb, const Src& src, int ng_in, int bh, int q0, uint32_t* __restrict__ k_codes,
     uint32_t* __restrict__ v_codes, uint16_t* __restrict__ k_scale, uint16_t* __restrict__ k_zero,
     uint16_t* __restrict__ v_scale, uint16_t* __restrict__ v_zero, int32_t* __restrict__ pos_q,
     int qcap, int Hkv) {
   const int tid = threadIdx.x;
   const int ng = FULL ? G : ng_in;        // a compile-time constant for whole groups
-  constexpr int nkc = d >> 5, ngc = (d + G - 1) / G, ld = d + 4;
+  constexpr int nkc = d >> 5, ngc = (d + G - 1) / G, ld = d + 4, ldk = key_pitch(d, G);
   constexpr int WPL = nkc * (BITS / 2);   // code words per lane and 32-slot block
   constexpr int KP = d + 4, VP = G + 4;   // byte pitches of the code arrays
   const int64_t code_base = ((int64_t)bh * (qcap >> 5) + (q0 >> 5)) * 64 * WPL;
   const uint32_t* cw = reinterpret_cast<const uint32_t*>(cb);
 
   // ---------------- keys ----------------
-  src.template stage_keys<FULL>(sm, ld);
+  src.template stage_keys<FULL>(sm, ldk);
   const typename Src::ValueRegs vregs = src.template load_values<FULL>();   // in flight during the key phase
   __syncthreads();
-  // per pair of neighbouring channels: `parts` threads each scan a share of the G tokens
-  // (one 32-bit LDS read per token, kept in registers), exchange their partial minima
-  // and maxima, and then encode their own share.  The workgroup is bound by the number
-  // of LDS instructions, hence pairs, one pass over LDS, and two code bytes per write.
+  // Per pair of neighbouring channels, `parts` lanes of ONE wavefront each scan a share of the
+  // G tokens (one 32-bit LDS read per token, kept in registers), combine their minima and
+  // maxima by wavefront shuffles and then encode their own share.  A wavefront owns CPW
+  // channel pairs; lane = part * CPW + pair.  The workgroup is bound by the number of LDS
+  // instructions, hence pairs, one pass over LDS, and two code bytes per write.
   {
     constexpr int PAIRS = d / 2;
-    constexpr int parts = d == 96 ? 4 : 512 / d;      // threads per channel pair (d = 96: 192 threads work); divides G
-    constexpr int per = G / parts;                    // tokens per thread
-    static_assert(G % parts == 0 && parts * PAIRS <= 256 && 2 * parts * d <= 8 * 128, "key statistics split");
-    const int cp = tid % PAIRS, part = tid / PAIRS;
+    constexpr int parts = d == 96 ? 4 : 512 / d;      // lanes per channel pair (d = 96: three wavefronts work); divides G
+    constexpr int per = G / parts;                    // tokens per lane
+    constexpr int CPW = 64 / parts;                   // channel pairs per wavefront
+    static_assert(G % parts == 0 && (PAIRS + CPW - 1) / CPW <= 4 && (CPW == 8 || CPW == 16), "key statistics split");
+    const int lane = tid & 63;
+    const int cp = (tid >> 6) * CPW + lane % CPW, part = lane / CPW;
     const int e0 = part * per;
-    uint32_t xv[per];
-    float mn[2] = {INFINITY, INFINITY}, mx[2] = {-INFINITY, -INFINITY};
-    if (part < parts) {
+    if (cp < PAIRS) {   // (whole wavefronts)
+      uint32_t xv[per];
+      float mn[2] = {INFINITY, INFINITY}, mx[2] = {-INFINITY, -INFINITY};
 #pragma unroll
       for (int i = 0; i < per; ++i) {
-        xv[i] = *reinterpret_cast<const uint32_t*>(sm + (e0 + i) * ld + 2 * cp);
+        xv[i] = *reinterpret_cast<const uint32_t*>(sm + (e0 + i) * ldk + 2 * cp);
         if (FULL || e0 + i < ng) {
           const float x0 = t2f<BF16>((uint16_t)xv[i]), x1 = t2f<BF16>((uint16_t)(xv[i] >> 16));
           mn[0] = fminf(mn[0], x0); mx[0] = fmaxf(mx[0], x0);
           mn[1] = fminf(mn[1], x1); mx[1] = fmaxf(mx[1], x1);
         }
       }
-      *reinterpret_cast<float2*>(red + part * d + 2 * cp) = make_float2(mn[0], mn[1]);
-      *reinterpret_cast<float2*>(red + (parts + part) * d + 2 * cp) = make_float2(mx[0], mx[1]);
-    }
-    __syncthreads();
-    if (part < parts) {
-#pragma unroll
-      for (int pp = 0; pp < parts; ++pp) {
-        const float2 a = *reinterpret_cast<const float2*>(red + pp * d + 2 * cp);
-        const float2 b = *reinterpret_cast<const float2*>(red + (parts + pp) * d + 2 * cp);
-        mn[0] = fminf(mn[0], a.x); mn[1] = fminf(mn[1], a.y);
-        mx[0] = fmaxf(mx[0], b.x); mx[1] = fmaxf(mx[1], b.y);
-      }
+      reduce_over_parts<CPW>(mn, mx);
       float z0, s0, z1, s1;
       uint16_t zt0, st0, zt1, st1;
       group_params<BF16, BITS>(mn[0], mx[0], &z0, &s0, &zt0, &st0);
@@ -368,15 +407,15 @@ __device__ __forceinline__ void quantize_group_t(
 
 template <bool BF16, int d, int G, int BITS, class Src>
 __device__ __forceinline__ void quantize_group(
-    uint16_t* sm, uint8_t* cb, float* red, const Src& src, int ng, int bh, int q0, uint32_t* __restrict__ k_codes,
+    uint16_t* sm, uint8_t* cb, const Src& src, int ng, int bh, int q0, uint32_t* __restrict__ k_codes,
     uint32_t* __restrict__ v_codes, uint16_t* __restrict__ k_scale, uint16_t* __restrict__ k_zero,
     uint16_t* __restrict__ v_scale, uint16_t* __restrict__ v_zero, int32_t* __restrict__ pos_q,
     int qcap, int Hkv) {
   if (ng == G)
-    quantize_group_t<BF16, d, G, BITS, true>(sm, cb, red, src, ng, bh, q0, k_codes, v_codes, k_scale, k_zero, v_scale,
+    quantize_group_t<BF16, d, G, BITS, true>(sm, cb, src, ng, bh, q0, k_codes, v_codes, k_scale, k_zero, v_scale,
                                              v_zero, pos_q, qcap, Hkv);
   else
-    quantize_group_t<BF16, d, G, BITS, false>(sm, cb, red, src, ng, bh, q0, k_codes, v_codes, k_scale, k_zero, v_scale,
+    quantize_group_t<BF16, d, G, BITS, false>(sm, cb, src, ng, bh, q0, k_codes, v_codes, k_scale, k_zero, v_scale,
                                               v_zero, pos_q, qcap, Hkv);
 }
 
@@ -432,11 +471,10 @@ struct CompressParams {
 // One launch does both halves of the filtering branch; they read the same buffer and
 // write disjoint ones.  grid (ceil(W/G) + ceil(2W/32), B*Hkv), block 256: workgroups
 // x < ceil(W/G) quantize one key group each, the others move 32 kept rows each.
-// Dynamic LDS: G * (d + 4) uint16.
+// Dynamic LDS: staged_bytes(d, G).
 template <bool BF16, int D, int G, int BITS>
 __global__ void __launch_bounds__(256) compress_kernel(const CompressParams P, const SeqInline S) {
   extern __shared__ __attribute__((aligned(16))) uint16_t sm[];  // [G][d + 4]: the staged rows
-  __shared__ float red[8 * 128];    // partial minima [4][d] and maxima [4][d] of the key channels
   __shared__ __attribute__((aligned(16))) uint8_t cb[QG_CODE_BYTES<D, G>];
   const int nq = (P.W + G - 1) / G;
   int bh = blockIdx.y, cur = P.cur, n_q = P.n_q;
@@ -459,7 +497,7 @@ __global__ void __launch_bounds__(256) compress_kernel(const CompressParams P, c
     const int ng = min(G, P.W - j * G);
     const int64_t fp_slice = (int64_t)bh * P.cap * D;
     const FpSource<D, G> src{k_old + fp_slice, v_old + fp_slice, pos_old + (bh / P.Hkv) * P.cap, j, ng, P.cap};
-    quantize_group<BF16, D, G, BITS>(sm, cb, red, src, ng, bh, n_q + j * G, P.k_codes, P.v_codes, P.k_scale, P.k_zero,
+    quantize_group<BF16, D, G, BITS>(sm, cb, src, ng, bh, n_q + j * G, P.k_codes, P.v_codes, P.k_scale, P.k_zero,
                                P.v_scale, P.v_zero, P.pos_q, P.qcap, P.Hkv);
   } else {
     compact_rows(blockIdx.x - nq, bh, k_old, v_old, pos_old, cur ? P.k_buf[0] : P.k_buf[1],
@@ -489,7 +527,6 @@ struct PrefillParams {
 template <bool BF16, int D, int G, int BITS>
 __global__ void __launch_bounds__(256) prefill_kernel(const PrefillParams P, const SeqInline S) {
   extern __shared__ __attribute__((aligned(16))) uint16_t sm[];
-  __shared__ float red[8 * 128];
   __shared__ __attribute__((aligned(16))) uint8_t cb[QG_CODE_BYTES<D, G>];
   __shared__ int posl[128];
   const int tid = threadIdx.x, bh = blockIdx.y;
@@ -509,7 +546,7 @@ __global__ void __launch_bounds__(256) prefill_kernel(const PrefillParams P, con
     if (tid < G) posl[tid] = tid < ng ? evicted_position(ev, j * G + tid, P.W) : -1;
     __syncthreads();
     const PromptSource<D, G> src{P.k + prompt, P.v + prompt, posl};
-    quantize_group<BF16, D, G, BITS>(sm, cb, red, src, ng, bh, (ev - 1) * per_event * G + j * G, P.k_codes, P.v_codes, P.k_scale,
+    quantize_group<BF16, D, G, BITS>(sm, cb, src, ng, bh, (ev - 1) * per_event * G + j * G, P.k_codes, P.v_codes, P.k_scale,
                                P.k_zero, P.v_scale, P.v_zero, P.pos_q, P.qcap, P.Hkv);
     return;
   }
@@ -602,7 +639,7 @@ hipError_t launch_compress(const Shape& s, const lq_cache& c, hipStream_t st, co
   P.v_scale = (uint16_t*)c.v_scale; P.v_zero = (uint16_t*)c.v_zero;
   P.pos_q = c.pos_q;
   P.d = s.d; P.G = s.G; P.W = s.W; P.cap = s.cap; P.qcap = s.qcap; P.n_q = c.n_q; P.Hkv = s.Hkv;
-  const size_t lds = (size_t)s.G * (s.d + 4) * sizeof(uint16_t);
+  const size_t lds = (size_t)staged_bytes(s.d, s.G);
   dim3 grid(s.Wq / s.G + (2 * s.W + 31) / 32, (seq ? n_items : s.B) * s.Hkv);
   dispatch_dg<CompressLaunch>(s, grid, lds, st, P, S);
   return launch_status(__func__);
@@ -626,7 +663,7 @@ hipError_t launch_prefill(const Shape& s, const lq_cache& c, const void* k, cons
   P.pos_q = c.pos_q;
   P.d = s.d; P.G = s.G; P.W = s.W; P.cap = s.cap; P.qcap = s.qcap; P.Hkv = s.Hkv;
   P.L = L; P.E = E; P.n_fp = n_fp;
-  const size_t lds = (size_t)s.G * (s.d + 4) * sizeof(uint16_t);
+  const size_t lds = (size_t)staged_bytes(s.d, s.G);
   dim3 grid(E * (s.Wq / s.G) + (n_fp + 31) / 32, s.B * s.Hkv);
   dispatch_dg<PrefillLaunch>(s, grid, lds, st, P, S);
   return launch_status(__func__);
