@@ -9,8 +9,11 @@
 namespace lq {
 
 // One group of values: zero z = min, scale s = T((max - min) / STEPS) with the
-// difference and the quotient correctly rounded to fp32 (the fp64 quotient
-// rounded once more to fp32 equals the IEEE fp32 quotient, 53 >= 2*24 + 2).
+// difference and the quotient correctly rounded to fp32.  The quotient takes three
+// operations: with y = fp32(1/STEPS), q0 = fp32(a y), the remainder r = a - STEPS q0 (exact
+// in one fused multiply-add), and fp32(q0 + r y) is the correctly rounded a / STEPS; for
+// STEPS = 3 and 15 this was checked against the fp64 quotient rounded to fp32 (which equals
+// the IEEE fp32 quotient, 53 >= 2*24 + 2) for every finite non-negative fp32 a.
 // z and s (values of T) are what the codes are formed with; zt and st are what is
 // stored: the same two values as fp16 (bit-identical for an fp16 cache; for a bf16
 // cache exact whenever the value is in fp16's normal range).
@@ -19,8 +22,12 @@ __device__ __forceinline__ void group_params(float mn, float mx, float* z, float
                                              uint16_t* st) {
   if (mn == 0.f) mn = 0.f;  // -0 -> +0 (min/max do not order signed zeros)
   if (mx == 0.f) mx = 0.f;
+  constexpr float STEPS = (float)((1 << BITS) - 1), y = 1.0f / STEPS;
   const float diff = mx - mn;
-  const float quo = (float)((double)diff / (double)((1 << BITS) - 1));
+  const float q0 = diff * y;
+  float quo = __fmaf_rn(__fmaf_rn(-STEPS, q0, diff), y, q0);
+  asm("" : "+v"(quo));      // the fp32 quotient is rounded before the conversion to T: keeps the compiler from
+                            // merging the last operation and the conversion into one that rounds once, to fp16
   *s = t2f<BF16>(f2t<BF16>(quo));
   *z = mn;                  // an element of T
   *st = f2t<false>(*s);
@@ -29,32 +36,83 @@ __device__ __forceinline__ void group_params(float mn, float mx, float* z, float
 
 // Encoder of one group: round-half-up of (x - z)/s clamped to 0..2^BITS-1, by
 // threshold compares on the exact (fp64) difference; (k + 0.5) * s is exact in fp64.
-// The thresholds grow with k, so the number of them that x - z reaches is found by
-// bisection (BITS compares instead of 2^BITS - 1); with 2 bits the three thresholds
-// are formed once per group.
+// The thresholds grow with k, so with 4 bits the number of them that x - z reaches is found
+// by bisection (BITS compares instead of 2^BITS - 1).
 template <int BITS>
 struct Encoder {
-  double z, sd, t0, t1, t2;
+  double z, sd;
   bool flat;
   __device__ __forceinline__ Encoder(float zf, float s) {
     z = (double)zf; sd = (double)s; flat = s == 0.f;
-    t0 = 0.5 * sd; t1 = 1.5 * sd; t2 = 2.5 * sd;
   }
   __device__ __forceinline__ uint32_t operator()(float x) const {
     const double dl = (double)x - z;
-    uint32_t c;
-    if constexpr (BITS == 2) {
-      const uint32_t hi = dl >= t1;
-      c = 2 * hi + (uint32_t)(dl >= (hi ? t2 : t0));
-    } else {
-      c = 0;
+    uint32_t c = 0;
 #pragma unroll
-      for (int step = 1 << (BITS - 1); step >= 1; step >>= 1)
-        if (dl >= ((double)(c + step) - 0.5) * sd) c += step;
-    }
+    for (int step = 1 << (BITS - 1); step >= 1; step >>= 1)
+      if (dl >= ((double)(c + step) - 0.5) * sd) c += step;
     return flat ? 0u : c;
   }
 };
+// ---- 2-bit groups: statistics and codes on order-preserving 16-bit keys, two values per
+// instruction.  The bits of a T value (sign, then magnitude) map to an unsigned key that
+// orders like the value: negative values have every bit flipped, the others the sign bit
+// set (-0 -> 0x7FFF sits just below +0 -> 0x8000).  Minima and maxima are then unsigned
+// packed min/max.  For the codes, x - z >= (k + 1/2) s  <=>  x >= z + (k + 1/2) s, that sum
+// is exact in fp64 (s comes from a group that holds z, so it is at least a third of the
+// spacing of T at |z|: the two addends lie within 13 binary places of each other, with at
+// most 11 and 14 significant bits), and since x is a value of T it reaches the sum exactly
+// when it reaches the smallest value of T at or above it.  The three thresholds are turned
+// into keys once per group - each by one of the lanes that share the group, handed round by
+// lane shuffles - and per pair of values the code is then three packed saturating
+// subtractions, three packed minima and two packed adds.
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+typedef short i16x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ u16x2 keys_of(uint32_t w) {   // two T values -> two keys
+  const i16x2 x = __builtin_bit_cast(i16x2, w);
+  const i16x2 flip = (x >> 15) | (i16x2)((short)0x8000);   // 0xFFFF for a negative value, 0x8000 otherwise
+  return __builtin_bit_cast(u16x2, x ^ flip);
+}
+__device__ __forceinline__ uint32_t key_of(uint16_t bits) { return (bits & 0x8000u) ? (~(uint32_t)bits & 0xFFFFu) : (bits | 0x8000u); }
+__device__ __forceinline__ uint16_t bits_of_key(uint32_t key) { return (uint16_t)((key & 0x8000u) ? (key ^ 0x8000u) : (~key & 0xFFFFu)); }
+
+// key(smallest value of T that is >= t) - 1: a key above it belongs to a value that reaches t.
+// f = fp32(t) and "up" = [f < t] locate t between neighbouring fp32 numbers; h = T(f) is a
+// neighbour of f in T.  The smallest value of T at or above t is h, or the next one upwards
+// (the next key: keys step with the values whatever the sign) when h < f, or when h == f
+// and t lies above f.  A threshold of zero (either sign) is taken as -0, which both zeros
+// reach.  In a flat group (s == 0) every code is 0: 0xFFFF, which no key exceeds.
+template <bool BF16>
+__device__ __forceinline__ uint32_t threshold_key(float zf, float s, float k_plus_half) {
+  const double t = (double)zf + (double)k_plus_half * (double)s;   // exact
+  const float f = (float)t;
+  const bool up = (double)f < t;
+  const uint16_t h = f2t<BF16>(f);
+  const float hb = t2f<BF16>(h);
+  uint32_t key = key_of(h) + ((hb < f || (hb == f && up)) ? 1u : 0u);
+  if (key == 0x8000u) key = 0x7FFFu;
+  return s == 0.f ? 0xFFFFu : key - 1u;
+}
+
+// codes of two keys; tk[k]: the two values' k-th thresholds (low half: first value).
+// [key > t] per half is min(key -sat t, 1); written as instructions because the compiler
+// turns that expression into 16-bit compares and selects, one value at a time.
+__device__ __forceinline__ u16x2 codes_of(u16x2 key, const u16x2* tk) {
+  uint32_t c, a, b;
+  asm("v_pk_sub_u16 %0, %3, %4 clamp\n\t"
+      "v_pk_sub_u16 %1, %3, %5 clamp\n\t"
+      "v_pk_sub_u16 %2, %3, %6 clamp\n\t"
+      "v_pk_min_u16 %0, %0, %7\n\t"
+      "v_pk_min_u16 %1, %1, %7\n\t"
+      "v_pk_min_u16 %2, %2, %7\n\t"
+      "v_pk_add_u16 %0, %0, %1\n\t"
+      "v_pk_add_u16 %0, %0, %2"
+      : "=&v"(c), "=&v"(a), "=&v"(b)
+      : "v"(__builtin_bit_cast(uint32_t, key)), "v"(__builtin_bit_cast(uint32_t, tk[0])),
+        "v"(__builtin_bit_cast(uint32_t, tk[1])), "v"(__builtin_bit_cast(uint32_t, tk[2])), "v"(0x00010001u));
+  return __builtin_bit_cast(u16x2, c);
+}
 
 // Minimum and maximum over the lanes that differ in the bits CPW .. 32 of the lane index
 // (CPW = 8 or 16), by wavefront shuffles: a rotation by 8 inside the row of 16 lanes, then the
@@ -82,6 +140,29 @@ __device__ __forceinline__ void reduce_over_parts(float* mn, float* mx) {
       mx[k] = fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
     }
   }
+}
+
+// The same reduction for packed keys (two channels per register).
+template <int CPW>
+__device__ __forceinline__ void reduce_keys_over_parts(u16x2& mn, u16x2& mx) {
+  uint32_t a = __builtin_bit_cast(uint32_t, mn), b = __builtin_bit_cast(uint32_t, mx);
+  auto lo = [](uint32_t x, uint32_t y) { return __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(u16x2, x), __builtin_bit_cast(u16x2, y))); };
+  auto hi = [](uint32_t x, uint32_t y) { return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(u16x2, x), __builtin_bit_cast(u16x2, y))); };
+  if constexpr (CPW <= 8) {
+    a = lo(a, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)a, 0x128, 0xF, 0xF, false));   // row_ror:8
+    b = hi(b, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)b, 0x128, 0xF, 0xF, false));
+  }
+  {
+    const auto p = __builtin_amdgcn_permlane16_swap(a, a, false, false);
+    const auto q = __builtin_amdgcn_permlane16_swap(b, b, false, false);
+    a = lo(p[0], p[1]); b = hi(q[0], q[1]);
+  }
+  {
+    const auto p = __builtin_amdgcn_permlane32_swap(a, a, false, false);
+    const auto q = __builtin_amdgcn_permlane32_swap(b, b, false, false);
+    a = lo(p[0], p[1]); b = hi(q[0], q[1]);
+  }
+  mn = __builtin_bit_cast(u16x2, a); mx = __builtin_bit_cast(u16x2, b);
 }
 
 // Eight codes (one byte each, in x: elements 0..3, y: elements 4..7) -> the operand
@@ -272,6 +353,47 @@ __device__ __forceinline__ void quantize_group_t(
     const int cp = (tid >> 6) * CPW + lane % CPW, part = lane / CPW;
     const int e0 = part * per;
     if (cp < PAIRS) {   // (whole wavefronts)
+      if constexpr (BITS == 2) {
+        u16x2 kv[per];
+        u16x2 mn = (u16x2)((unsigned short)0xFFFF), mx = (u16x2)((unsigned short)0);
+#pragma unroll
+        for (int i = 0; i < per; ++i) {
+          kv[i] = keys_of(*reinterpret_cast<const uint32_t*>(sm + (e0 + i) * ldk + 2 * cp));
+          if (FULL || e0 + i < ng) {
+            mn = __builtin_elementwise_min(mn, kv[i]);
+            mx = __builtin_elementwise_max(mx, kv[i]);
+          }
+        }
+        reduce_keys_over_parts<CPW>(mn, mx);
+        float z0, s0, z1, s1;
+        uint16_t zt0, st0, zt1, st1;
+        group_params<BF16, BITS>(t2f<BF16>(bits_of_key(mn.x)), t2f<BF16>(bits_of_key(mx.x)), &z0, &s0, &zt0, &st0);
+        group_params<BF16, BITS>(t2f<BF16>(bits_of_key(mn.y)), t2f<BF16>(bits_of_key(mx.y)), &z1, &s1, &zt1, &st1);
+        if (part == 0) {
+          const int64_t mi = ((int64_t)bh * (qcap / G) + q0 / G) * d + 2 * cp;
+          *reinterpret_cast<uint32_t*>(k_scale + mi) = (uint32_t)st0 | ((uint32_t)st1 << 16);
+          *reinterpret_cast<uint32_t*>(k_zero + mi) = (uint32_t)zt0 | ((uint32_t)zt1 << 16);
+        }
+        // threshold k of both channels by the lanes of row k (16 lanes: parts 16k/CPW ..), then
+        // every row's word to all four rows by the swap instructions
+        u16x2 tk[3];
+        {
+          const float kh = (float)(lane >> 4) + 0.5f;
+          const uint32_t x = threshold_key<BF16>(z0, s0, kh) | (threshold_key<BF16>(z1, s1, kh) << 16);
+          const auto eo = __builtin_amdgcn_permlane16_swap(x, x, false, false);       // rows 0 0 2 2 | 1 1 3 3
+          const auto e = __builtin_amdgcn_permlane32_swap(eo[0], eo[0], false, false);  // rows 0 0 0 0 | 2 2 2 2
+          const auto o = __builtin_amdgcn_permlane32_swap(eo[1], eo[1], false, false);  // rows 1 1 1 1 | 3 3 3 3
+          tk[0] = __builtin_bit_cast(u16x2, (uint32_t)e[0]);
+          tk[1] = __builtin_bit_cast(u16x2, (uint32_t)o[0]);
+          tk[2] = __builtin_bit_cast(u16x2, (uint32_t)e[1]);
+        }
+#pragma unroll
+        for (int i = 0; i < per; ++i) {
+          const uint32_t c = __builtin_bit_cast(uint32_t, codes_of(kv[i], tk));
+          *reinterpret_cast<uint16_t*>(cb + (e0 + i) * KP + 2 * cp) =
+              (FULL || e0 + i < ng) ? (uint16_t)(c | (c >> 8)) : (uint16_t)0;
+        }
+      } else {
       uint32_t xv[per];
       float mn[2] = {INFINITY, INFINITY}, mx[2] = {-INFINITY, -INFINITY};
 #pragma unroll
@@ -299,6 +421,7 @@ __device__ __forceinline__ void quantize_group_t(
         const uint32_t c0 = enc0(t2f<BF16>((uint16_t)xv[i])), c1 = enc1(t2f<BF16>((uint16_t)(xv[i] >> 16)));
         *reinterpret_cast<uint16_t*>(cb + (e0 + i) * KP + 2 * cp) =
             (FULL || e0 + i < ng) ? (uint16_t)(c0 | (c1 << 8)) : (uint16_t)0;
+      }
       }
     }
   }
@@ -343,6 +466,57 @@ __device__ __forceinline__ void quantize_group_t(
       const uint16_t* row = sm + e * ld + c0;               // 8-byte aligned: ld and c0 are multiples of 4
       uint8_t* col = cb + c0 * VP + e;
       // one pass over LDS, four channels per read; the values stay in registers for the encode
+      if constexpr (BITS == 2) {
+        u16x2 ka[PER / 4], kb[PER / 4];
+        u16x2 mn2 = (u16x2)((unsigned short)0xFFFF), mx2 = (u16x2)((unsigned short)0);
+#pragma unroll
+        for (int k = 0; k < PER / 4; ++k) {
+          const uint2 x = *reinterpret_cast<const uint2*>(row + (4 * k < n ? 4 * k : 0));
+          ka[k] = keys_of(x.x); kb[k] = keys_of(x.y);
+          if (4 * k < n) {
+            mn2 = __builtin_elementwise_min(mn2, __builtin_elementwise_min(ka[k], kb[k]));
+            mx2 = __builtin_elementwise_max(mx2, __builtin_elementwise_max(ka[k], kb[k]));
+          }
+        }
+        uint32_t mn = min((uint32_t)mn2.x, (uint32_t)mn2.y), mx = max((uint32_t)mx2.x, (uint32_t)mx2.y);
+        for (int o = 1; o < vp; o <<= 1) {
+          mn = min(mn, (uint32_t)__shfl_xor((int)mn, o));
+          mx = max(mx, (uint32_t)__shfl_xor((int)mx, o));
+        }
+        float z, sc;
+        uint16_t zt, st;
+        group_params<BF16, BITS>(t2f<BF16>(bits_of_key(mn)), t2f<BF16>(bits_of_key(mx)), &z, &sc, &zt, &st);
+        if (part == 0) {
+          const int64_t mi = (int64_t)bh * (qcap >> 5) * ngc * 32 + v_meta_index(q0 + e, gc, ngc);
+          v_scale[mi] = st;
+          v_zero[mi] = zt;
+        }
+        // the lanes of a group share out the thresholds and hand them round inside their quad
+        u16x2 tk[3];
+        if constexpr (vp >= 4) {
+          const uint32_t x = threshold_key<BF16>(z, sc, (float)min(part & 3, 2) + 0.5f) * 0x10001u;
+          tk[0] = __builtin_bit_cast(u16x2, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x00, 0xF, 0xF, false));   // quad_perm:[0,0,0,0]
+          tk[1] = __builtin_bit_cast(u16x2, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x55, 0xF, 0xF, false));   // quad_perm:[1,1,1,1]
+          tk[2] = __builtin_bit_cast(u16x2, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xAA, 0xF, 0xF, false));   // quad_perm:[2,2,2,2]
+        } else if constexpr (vp == 2) {
+          const uint32_t x = threshold_key<BF16>(z, sc, (float)part + 0.5f) * 0x10001u;
+          tk[0] = __builtin_bit_cast(u16x2, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xA0, 0xF, 0xF, false));   // quad_perm:[0,0,2,2]
+          tk[1] = __builtin_bit_cast(u16x2, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xF5, 0xF, 0xF, false));   // quad_perm:[1,1,3,3]
+          tk[2] = __builtin_bit_cast(u16x2, threshold_key<BF16>(z, sc, 2.5f) * 0x10001u);
+        } else {
+#pragma unroll
+          for (int k = 0; k < 3; ++k) tk[k] = __builtin_bit_cast(u16x2, threshold_key<BF16>(z, sc, (float)k + 0.5f) * 0x10001u);
+        }
+#pragma unroll
+        for (int k = 0; k < PER / 4; ++k)
+          if (4 * k < n) {
+            const u16x2 ca = codes_of(ka[k], tk), cc = codes_of(kb[k], tk);
+            col[(4 * k + 0) * VP] = (uint8_t)ca.x;
+            col[(4 * k + 1) * VP] = (uint8_t)ca.y;
+            col[(4 * k + 2) * VP] = (uint8_t)cc.x;
+            col[(4 * k + 3) * VP] = (uint8_t)cc.y;
+          }
+      } else {
       uint2 xv[PER / 4];
       float mn = INFINITY, mx = -INFINITY;
 #pragma unroll
@@ -376,6 +550,7 @@ __device__ __forceinline__ void quantize_group_t(
           col[(4 * k + 2) * VP] = (uint8_t)enc(t2f<BF16>((uint16_t)xv[k].y));
           col[(4 * k + 3) * VP] = (uint8_t)enc(t2f<BF16>((uint16_t)(xv[k].y >> 16)));
         }
+      }
     }
   }
   __syncthreads();
