@@ -165,7 +165,11 @@ lq_status logquant_append(const lq_config *cfg, lq_cache *cache, const void *k_n
  *   - logical rows 0,2,..,2W-2 followed by rows 2W..3W-1 become rows 0..2W-1 of
  *     the other fp buffer, which becomes the live one (cache->cur flips).
  * On success n_fp = 2W, n_q += WQ.  `workspace` is not used at present and may
- * be null. */
+ * be null.
+ * Input contract: the rows being quantized are finite and |x| <= 65504 (always true
+ * of an fp16 cache; a bf16 cache may hold larger values, whose scales and zero-points
+ * would overflow the fp16 they are stored in - the call does not look at the data and
+ * returns LQ_OK, and attention over such a group is then undefined). */
 lq_status logquant_compress(const lq_config *cfg, lq_cache *cache, void *workspace,
                             void *stream);
 
@@ -180,7 +184,8 @@ lq_status logquant_compress(const lq_config *cfg, lq_cache *cache, void *workspa
  * Requires an empty cache (n_fp == n_q == 0, else LQ_ERR_STATE), L >= 1 (else
  * LQ_ERR_SHAPE) and E*WQ <= q_capacity for the E = 0 (L < 3W) or floor((L-3W)/W)+1
  * events (else LQ_ERR_CAPACITY).  On success n_q = E*WQ, n_fp = L - E*W, and the live fp
- * buffer is unchanged (cache->cur). */
+ * buffer is unchanged (cache->cur).
+ * Input contract as for logquant_compress: finite values, |x| <= 65504. */
 lq_status logquant_prefill(const lq_config *cfg, lq_cache *cache, const void *k, const void *v,
                            int32_t L, void *stream);
 
