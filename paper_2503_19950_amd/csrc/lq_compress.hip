@@ -187,6 +187,11 @@ struct FpSource {
   int j;
   int ng;                 // rows of this group (G, fewer in the last group of an event when G does not divide W)
   int cap;                // rows allocated per slice (multiple of 32)
+  // Not null: this workgroup also moves the rows that stay - the even logical slots 2jG .. 2jG + 2G - 2 of
+  // the lines it reads anyway - to slots jG .. jG + G - 1 of the other buffer (slice bases).  Only for
+  // whole groups with d a multiple of 64.
+  uint16_t* k_keep;
+  uint16_t* v_keep;
   // FULL: the group has all G rows (compile-time trip counts, no row checks)
   template <bool FULL>
   __device__ __forceinline__ void stage_keys(uint16_t* sm, int ld) const {
@@ -197,6 +202,9 @@ struct FpSource {
       if (FULL || e < ng) v = *reinterpret_cast<const uint4*>(k_fp + k_fp_index(ts, oct * 8, nkc));
       uint32_t* dst = reinterpret_cast<uint32_t*>(sm + e * ld + oct * 8);
       dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+      if (FULL && k_keep)   // the row before it (same 32 bytes) stays: 16 bytes to its new slot
+        *reinterpret_cast<uint4*>(k_keep + k_fp_index(j * G + e, oct * 8, nkc)) =
+            *reinterpret_cast<const uint4*>(k_fp + k_fp_index(ts - 1, oct * 8, nkc));
     }
   }
   // The value rows are fetched into registers while the keys are being processed (the
@@ -221,6 +229,34 @@ struct FpSource {
   }
   template <bool FULL>
   __device__ __forceinline__ void store_values(const ValueRegs& r, uint16_t* sm, int ld) const {
+    if constexpr (FULL && nnt % 4 == 0) {
+      if (v_keep) {
+        // The rows that stay are the even elements (low halves) of the registers just loaded.  Lane (qq, n)
+        // of old tile sb holds old slots 4qq, 4qq+2, 16+4qq, 16+4qq+2 -> new slots 16 (sb & 1) + 2qq, +1 and
+        // 16 (sb & 1) + 8 + 2qq, +1 of new tile sb >> 1: word 2 (sb & 1) + (qq & 1) of new lane (qq >> 1, n)
+        // and of new lane (2 + (qq >> 1), n).  A thread holds both old tiles of a new one (registers k and
+        // PER_SB + k of the pair); the row swap gives both rows of a pair (qq, qq ^ 1) each other's words,
+        // and then the even row stores the 16 bytes of new lane qq >> 1, the odd row those of 2 + (qq >> 1).
+        constexpr int PER_SB = nnt / 4;   // registers per thread and old tile
+        const int lane = threadIdx.x & 63, qq = lane >> 4, n = lane & 15;
+        const int to = ((qq & 1) ? 2 + (qq >> 1) : (qq >> 1)) * 16 + n;
+#pragma unroll
+        for (int t2 = 0; t2 < G / 32; ++t2)
+#pragma unroll
+          for (int k = 0; k < PER_SB; ++k) {
+            const uint4 a = r.v[(2 * t2) * PER_SB + k], b = r.v[(2 * t2 + 1) * PER_SB + k];
+            const int nt = (threadIdx.x >> 6) + 4 * k;
+            const uint32_t a0 = (a.x & 0xFFFFu) | (a.y << 16), b0 = (a.z & 0xFFFFu) | (a.w << 16);
+            const uint32_t a1 = (b.x & 0xFFFFu) | (b.y << 16), b1 = (b.z & 0xFFFFu) | (b.w << 16);
+            const auto sa0 = __builtin_amdgcn_permlane16_swap(a0, a0, false, false);   // [0]: the even row's word, [1]: the odd row's
+            const auto sb0 = __builtin_amdgcn_permlane16_swap(b0, b0, false, false);
+            const auto sa1 = __builtin_amdgcn_permlane16_swap(a1, a1, false, false);
+            const auto sb1 = __builtin_amdgcn_permlane16_swap(b1, b1, false, false);
+            const uint4 out = (qq & 1) ? make_uint4(sb0[0], sb0[1], sb1[0], sb1[1]) : make_uint4(sa0[0], sa0[1], sa1[0], sa1[1]);
+            *reinterpret_cast<uint4*>(v_keep + (((int64_t)((j * G >> 5) + t2) * nnt + nt) * 64 + to) * 8) = out;
+          }
+      }
+    }
 #pragma unroll
     for (int it = 0; it < VLOADS; ++it) {
       const int idx = threadIdx.x + 256 * it;
@@ -671,6 +707,7 @@ struct CompressParams {
   uint16_t *k_scale, *k_zero, *v_scale, *v_zero;
   int32_t* pos_q;
   int d, G, W, cap, qcap, n_q, Hkv;
+  int nb0;                         // first 32-row tile left to the moving workgroups (W/32 when the quantizing ones move the thinned rows, else 0)
 };
 
 // One launch does both halves of the filtering branch; they read the same buffer and
@@ -704,11 +741,20 @@ __global__ void __launch_bounds__(256) compress_kernel(const CompressParams P, c
     const int j = bx;
     const int ng = min(G, P.W - j * G);
     const int64_t fp_slice = (int64_t)bh * P.cap * D;
-    const FpSource<D, G> src{k_old + fp_slice, v_old + fp_slice, pos_old + (bh / P.Hkv) * P.cap, j, ng, P.cap};
+    const bool keep = P.nb0 > 0;
+    uint16_t* k_new = cur ? P.k_buf[0] : P.k_buf[1];
+    uint16_t* v_new = cur ? P.v_buf[0] : P.v_buf[1];
+    const FpSource<D, G> src{k_old + fp_slice, v_old + fp_slice, pos_old + (bh / P.Hkv) * P.cap, j, ng, P.cap,
+                             keep ? k_new + fp_slice : nullptr, keep ? v_new + fp_slice : nullptr};
+    if (keep && bh % P.Hkv == 0 && (int)threadIdx.x < G) {
+      int32_t* pos_new = cur ? P.pos_buf[0] : P.pos_buf[1];
+      const int b = bh / P.Hkv, tn = j * G + threadIdx.x;
+      pos_new[b * P.cap + tn] = pos_old[b * P.cap + 2 * tn];
+    }
     quantize_group<BF16, D, G, BITS>(sm, cb, src, ng, bh, n_q + j * G, P.k_codes, P.v_codes, P.k_scale, P.k_zero,
                                P.v_scale, P.v_zero, P.pos_q, P.qcap, P.Hkv);
   } else {
-    compact_rows(bx - nq, bh, k_old, v_old, pos_old, cur ? P.k_buf[0] : P.k_buf[1],
+    compact_rows(bx - nq + P.nb0, bh, k_old, v_old, pos_old, cur ? P.k_buf[0] : P.k_buf[1],
                  cur ? P.v_buf[0] : P.v_buf[1], cur ? P.pos_buf[0] : P.pos_buf[1], P.d, P.W, P.cap, P.Hkv);
   }
 }
@@ -848,7 +894,16 @@ hipError_t launch_compress(const Shape& s, const lq_cache& c, hipStream_t st, co
   P.pos_q = c.pos_q;
   P.d = s.d; P.G = s.G; P.W = s.W; P.cap = s.cap; P.qcap = s.qcap; P.n_q = c.n_q; P.Hkv = s.Hkv;
   const size_t lds = (size_t)staged_bytes(s.d, s.G);
-  dim3 grid(s.Wq / s.G + (2 * s.W + 31) / 32, (seq ? n_items : s.B) * s.Hkv);
+  // With whole key groups (G | W; then 32 | W too) and d a multiple of 64 the quantizing workgroups can also move the
+  // thinned rows - they read those lines anyway - and the moving ones start at the recent window.
+  // That pays when the launch is bound by memory traffic (every line fetched once instead of twice: 41.8 -> 36.3 us
+  // at 512 slices); a launch of a few hundred workgroups is bound by the time one quantizing workgroup takes, which
+  // the extra stores lengthen (64 slices: 9.9 -> 10.4 .. 11.5 us), so small launches keep the separate workgroups.
+  const int slices = (seq ? n_items : s.B) * s.Hkv;
+  const int tiles = (2 * s.W + 31) / 32;
+  const bool fuse = s.W % s.G == 0 && s.d % 64 == 0 && (int64_t)slices * (s.Wq / s.G + tiles) >= 2048;
+  P.nb0 = fuse ? s.W / 32 : 0;
+  dim3 grid(s.Wq / s.G + tiles - P.nb0, slices);
   dispatch_dg<CompressLaunch>(s, grid, lds, st, P, S);
   return launch_status(__func__);
 }

@@ -112,6 +112,26 @@ def test_workload_4_batch64_128_decode_steps():
         U.check_state(dc, oc, wl, b, h)
 
 
+@pytest.mark.parametrize("name,d,G,dtype", [("d64_g64_bf16", 64, 64, "bf16"), ("d128_g128_f16", 128, 128, "f16")])
+def test_compress_of_many_slices_moves_kept_rows_in_the_quantizing_workgroups(name, d, G, dtype):
+    """From about two thousand workgroups on, logquant_compress lets the workgroup that quantizes a
+    key group also move the rows that stay (it reads their lines anyway).  Workload 4 above takes
+    that route with d = 128, G = 32; here the other register shapes of it, at 240 slices: the state
+    after four filtering events bit for bit on three slices, attention on the same."""
+    wl = U.make_wl(B=30, Hq=8, Hkv=8, d=d, G=G, F=256, dtype=dtype, sinks=2)
+    L = 3 * 128 + 3 * 128 + 41
+    slices = [(0, 0), (29, 7), (13, 3)]
+    print("case", name, "L", L, flush=True)
+    dc = U.build_gpu_sampled(wl, 44, L, slices, q_capacity=U.q_capacity_for(wl, L))
+    ocs = {}
+    for (b, h) in slices:
+        oc = U.build_oracle(wl, 44, L, b, h)
+        U.check_state(dc, oc, wl, b, h)
+        ocs[(b, h)] = oc
+    assert dc.c.n_q == 4 * 128
+    U.check_attention(dc, ocs, wl, inputs.queries(44, 0, wl))
+
+
 def test_workload_5_mha_d96_l32768():
     wl = dict(inputs.WORKLOADS[5])
     slices = [(0, 0), (9, 20), (15, 31)]
