@@ -146,6 +146,29 @@ def test_equal_lengths_give_the_lock_step_result_bit_for_bit():
         assert torch.equal(oa, ob)
 
 
+def test_compress_seq_of_many_full_rows_gives_the_lock_step_state_bit_for_bit():
+    """240 slices whose windows fill at the same step: logquant_compress_seq then launches enough
+    workgroups to let the quantizing ones move the kept rows as well (the route large lock-step
+    batches take); the state must equal the one the lock-step calls reach, buffer by buffer."""
+    wl = U.make_wl(B=30, Hq=8, Hkv=8, d=64, G=64, F=256, dtype="bf16")
+    W = 128
+    L = 4 * W
+    K, V = inputs.batch_kv(780, 0, L, wl)
+    Kd, Vd = U.to_dev(K, "bf16"), U.to_dev(V, "bf16")
+    a = U.new_cache(wl, L)
+    assert a.stream_in(Kd, Vd) == 2
+    b = _new(wl, L)
+    b.prefill_seq(Kd[:, :, :L - 1].contiguous(), Vd[:, :, :L - 1].contiguous(), [L - 1] * wl["B"])
+    assert all(b.n_fp[i] == 3 * W - 1 for i in range(wl["B"]))
+    b.append_seq(Kd[:, :, L - 1:].contiguous(), Vd[:, :, L - 1:].contiguous())
+    b.compress_seq()
+    assert all(b.view(i) == b.view(0) for i in range(wl["B"]))
+    b.c.cur, b.c.n_fp, b.c.n_q = b.view(0)
+    la, lb = U.live_buffers(a, wl), U.live_buffers(b, wl)
+    for key in la:
+        assert np.array_equal(la[key], lb[key]), key
+
+
 def test_error_codes():
     from paper_2503_19950_amd import binding as B
     wl = U.make_wl(B=2, Hq=4, Hkv=2, d=128, G=32, F=64)
