@@ -64,8 +64,8 @@ struct Encoder {
 // most 11 and 14 significant bits), and since x is a value of T it reaches the sum exactly
 // when it reaches the smallest value of T at or above it.  The three thresholds are turned
 // into keys once per group - each by one of the lanes that share the group, handed round by
-// lane shuffles - and per pair of values the code is then three packed saturating
-// subtractions, three packed minima and two packed adds.
+// lane shuffles - and per pair of values the code is then two threshold tests (a packed
+// saturating subtraction and a packed minimum each) and two packed multiply-adds.
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
 typedef short i16x2 __attribute__((ext_vector_type(2)));
 
@@ -95,22 +95,21 @@ __device__ __forceinline__ uint32_t threshold_key(float zf, float s, float k_plu
   return s == 0.f ? 0xFFFFu : key - 1u;
 }
 
-// codes of two keys; tk[k]: the two values' k-th thresholds (low half: first value).
-// [key > t] per half is min(key -sat t, 1); written as instructions because the compiler
-// turns that expression into 16-bit compares and selects, one value at a time.
-__device__ __forceinline__ u16x2 codes_of(u16x2 key, const u16x2* tk) {
-  uint32_t c, a, b;
-  asm("v_pk_sub_u16 %0, %3, %4 clamp\n\t"
-      "v_pk_sub_u16 %1, %3, %5 clamp\n\t"
-      "v_pk_sub_u16 %2, %3, %6 clamp\n\t"
-      "v_pk_min_u16 %0, %0, %7\n\t"
-      "v_pk_min_u16 %1, %1, %7\n\t"
-      "v_pk_min_u16 %2, %2, %7\n\t"
-      "v_pk_add_u16 %0, %0, %1\n\t"
-      "v_pk_add_u16 %0, %0, %2"
-      : "=&v"(c), "=&v"(a), "=&v"(b)
+// codes of two keys; tk[k]: the two values' k-th thresholds (low half: first value).  [key > t] per half is
+// min(key -sat t, 1).  Two such tests: the middle threshold gives the high bit b1, the lower or the upper one -
+// t0 + b1 (t2 - t0), a packed multiply-add - the low bit.  Written as instructions because the compiler turns
+// the expression into 16-bit compares and selects, one value at a time.
+__device__ __forceinline__ u16x2 codes_of(u16x2 key, const u16x2* tk, u16x2 t20) {   // t20 = tk[2] - tk[0]
+  uint32_t c, b;
+  asm("v_pk_sub_u16 %1, %2, %4 clamp\n\t"
+      "v_pk_min_u16 %1, %1, %6\n\t"          // b1
+      "v_pk_mad_u16 %0, %1, %5, %3\n\t"      // the threshold that decides the low bit
+      "v_pk_sub_u16 %0, %2, %0 clamp\n\t"
+      "v_pk_min_u16 %0, %0, %6\n\t"          // b0
+      "v_pk_mad_u16 %0, %1, %7, %0"            // 2 b1 + b0
+      : "=&v"(c), "=&v"(b)
       : "v"(__builtin_bit_cast(uint32_t, key)), "v"(__builtin_bit_cast(uint32_t, tk[0])),
-        "v"(__builtin_bit_cast(uint32_t, tk[1])), "v"(__builtin_bit_cast(uint32_t, tk[2])), "v"(0x00010001u));
+        "v"(__builtin_bit_cast(uint32_t, tk[1])), "v"(__builtin_bit_cast(uint32_t, t20)), "v"(0x00010001u), "v"(0x00020002u));
   return __builtin_bit_cast(u16x2, c);
 }
 
@@ -174,6 +173,16 @@ __device__ __forceinline__ uint32_t pack8(uint32_t x, uint32_t y) {
   w |= ((y & M) << (2 * BITS)) | (((y >> 8) & M) << (16 + 2 * BITS)) | (((y >> 16) & M) << (3 * BITS)) |
        (((y >> 24) & M) << (16 + 3 * BITS));
   return w;
+}
+
+// The same for two operands of 2-bit codes at once (the two byte positions h = 0, 1 of a word), the bytes
+// holding nothing but a code (0..3): t = x | y << 4 has elements j and 4 + j in byte j; t | t >> 14 then has
+// bytes 0 and 2 (elements 0, 2, 4, 6: the low half's byte) interleaved in its byte 0 and bytes 1 and 3 (the
+// high half's) in its byte 1; one byte permute puts the four bytes of the two operands in place.
+__device__ __forceinline__ uint32_t pack16_2bit(uint32_t x0, uint32_t y0, uint32_t x1, uint32_t y1) {
+  const uint32_t t0 = x0 | (y0 << 4), t1 = x1 | (y1 << 4);
+  const uint32_t u0 = t0 | (t0 >> 14), u1 = t1 | (t1 >> 14);
+  return __builtin_amdgcn_perm(u1, u0, 0x05010400u);   // bytes: u0.0, u1.0, u0.1, u1.1
 }
 
 // Where the G rows of one key group come from.
@@ -423,9 +432,10 @@ __device__ __forceinline__ void quantize_group_t(
           tk[1] = __builtin_bit_cast(u16x2, (uint32_t)o[0]);
           tk[2] = __builtin_bit_cast(u16x2, (uint32_t)e[1]);
         }
+        const u16x2 t20 = tk[2] - tk[0];
 #pragma unroll
         for (int i = 0; i < per; ++i) {
-          const uint32_t c = __builtin_bit_cast(uint32_t, codes_of(kv[i], tk));
+          const uint32_t c = __builtin_bit_cast(uint32_t, codes_of(kv[i], tk, t20));
           *reinterpret_cast<uint16_t*>(cb + (e0 + i) * KP + 2 * cp) =
               (FULL || e0 + i < ng) ? (uint16_t)(c | (c >> 8)) : (uint16_t)0;
         }
@@ -469,13 +479,13 @@ __device__ __forceinline__ void quantize_group_t(
     const int r = lane & 15, qq = lane >> 4;
     uint32_t w;
     if constexpr (BITS == 2) {
-      w = 0;
+      int at[2];
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
         const int o = 2 * m + h, uu = o / nkc, kc = o % nkc;
-        const int at = ((blk * 32 + 16 * uu + r) * KP + 32 * kc + 8 * qq) >> 2;
-        w |= pack8<2>(cw[at], cw[at + 1]) << (8 * h);
+        at[h] = ((blk * 32 + 16 * uu + r) * KP + 32 * kc + 8 * qq) >> 2;
       }
+      w = pack16_2bit(cw[at[0]], cw[at[0] + 1], cw[at[1]], cw[at[1] + 1]);
     } else {
       const int uu = m / nkc, kc = m % nkc;
       const int at = ((blk * 32 + 16 * uu + r) * KP + 32 * kc + 8 * qq) >> 2;
@@ -543,10 +553,11 @@ __device__ __forceinline__ void quantize_group_t(
 #pragma unroll
           for (int k = 0; k < 3; ++k) tk[k] = __builtin_bit_cast(u16x2, threshold_key<BF16>(z, sc, (float)k + 0.5f) * 0x10001u);
         }
+        const u16x2 t20 = tk[2] - tk[0];
 #pragma unroll
         for (int k = 0; k < PER / 4; ++k)
           if (4 * k < n) {
-            const u16x2 ca = codes_of(ka[k], tk), cc = codes_of(kb[k], tk);
+            const u16x2 ca = codes_of(ka[k], tk, t20), cc = codes_of(kb[k], tk, t20);
             col[(4 * k + 0) * VP] = (uint8_t)ca.x;
             col[(4 * k + 1) * VP] = (uint8_t)ca.y;
             col[(4 * k + 2) * VP] = (uint8_t)cc.x;
@@ -597,12 +608,8 @@ __device__ __forceinline__ void quantize_group_t(
     const int n = lane & 15, qq = lane >> 4;
     uint32_t w;
     if constexpr (BITS == 2) {
-      w = 0;
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const int at = ((16 * (2 * m + h) + n) * VP + blk * 32 + 4 * qq) >> 2;
-        w |= pack8<2>(cw[at], cw[at + 4]) << (8 * h);
-      }
+      const int a0 = ((16 * (2 * m) + n) * VP + blk * 32 + 4 * qq) >> 2, a1 = ((16 * (2 * m + 1) + n) * VP + blk * 32 + 4 * qq) >> 2;
+      w = pack16_2bit(cw[a0], cw[a0 + 4], cw[a1], cw[a1 + 4]);
     } else {
       const int at = ((16 * m + n) * VP + blk * 32 + 4 * qq) >> 2;
       w = pack8<4>(cw[at], cw[at + 4]);
