@@ -696,9 +696,15 @@ attn_mfma_kernel(const AttnParams P, const SeqArgs<GENERAL> S) {
       // ---- hand the probabilities (fp16) to the lanes that feed the output step
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        const _Float16 ph16 = (_Float16)p[u];
+        _Float16 ph16 = (_Float16)p[u];
+        // Two pieces and no carried product residual (bf16 caches): the head piece keeps only the three
+        // leading significant bits of p, so that its product with a value scale - a bf16 number, 8
+        // significant bits - is exact in fp16; the rounding of the product then hits the second piece
+        // only, which is at most a quarter of p.
+        if constexpr (VPIECES == 2 && !PROD_LO)
+          ph16 = __builtin_bit_cast(_Float16, (uint16_t)(__builtin_bit_cast(uint16_t, ph16) & 0xFF00u));
         p_wr[(u >> 1) * (9 * 32) + 16 * (u & 1)] = __builtin_bit_cast(uint16_t, ph16);
-        if constexpr (VPIECES == 2)   // what the rounding to fp16 dropped, for the residual rows
+        if constexpr (VPIECES == 2)   // what the head piece leaves out, for the residual rows
           p_wr[(u >> 1) * (9 * 32) + 16 * (u & 1) + 5 * 32] = __builtin_bit_cast(uint16_t, (_Float16)(p[u] - (float)ph16));
       }
       wave_lds_sync();

@@ -56,7 +56,10 @@ def _cases(seed=20250319):
 # plus one case of another seed with large logits and few tokens sharing the weight, which exceeded the
 # fp16 tolerance while q*s entered the matrix unit as two 11-bit pieces
 # (its name keeps its own number: the data seed is derived from it)
-CASES = _cases() + [_cases(112)[2]]
+# and one bf16 case of another seed in which one token carries the weight and outputs lie in [2, 4), where
+# half an ulp of bf16 is 7.8e-3 of the 1e-2: it exceeded the tolerance (1.008e-2) while the head piece of the
+# probabilities had all 11 bits and its product with the value scale was rounded to fp16
+CASES = _cases() + [_cases(112)[2], _cases(17)[27]]
 
 
 @pytest.mark.parametrize("name,wl,L,steps", CASES, ids=[c[0] for c in CASES])

@@ -49,7 +49,10 @@ def _cases(seed=20250321):
 # magnitude: Laplace keys, outlier channels, sink rows) with two or three tokens sharing the weight:
 # they exceeded the fp16 tolerance while q*s entered the matrix unit as two 11-bit pieces
 # (their names keep their own number: the data seed is derived from it)
-CASES = _cases() + [_cases(105)[10], _cases(131)[10]]
+# and three bf16 cases of other seeds with a dominant token and outputs in [2, 4) (half an ulp of bf16 is
+# 7.8e-3 of the 1e-2 there), which exceeded the tolerance by up to 8 % before the head piece of the
+# probabilities was cut to three bits (its product with a bf16 value scale is then exact in fp16)
+CASES = _cases() + [_cases(105)[10], _cases(131)[10], _cases(11)[4], _cases(18)[2], _cases(21)[10]]
 
 
 @pytest.mark.parametrize("name,wl,lengths,steps", CASES, ids=[c[0] for c in CASES])
