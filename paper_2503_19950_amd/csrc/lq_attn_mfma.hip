@@ -438,8 +438,9 @@ attn_mfma_kernel(const AttnParams P, const SeqArgs<GENERAL> S) {
     const char* vzb = (const char*)(P.v_zero + (int64_t)bh * (P.qcap >> 5) * NGC * 32);
     // Rows of the probability operand of the output step: row 4*up + g.  With at most
     // two channel groups there are rows to spare, and the probabilities enter in two
-    // pieces: p rounded to fp16, and the residual of that rounding (rows up = piece *
-    // NGC + channel group), so that only the rounding of the product p * vs remains.
+    // pieces: a head piece (p rounded to fp16; for bf16 caches cut to three significant
+    // bits, see where it is written) and what that leaves out (rows up = piece * NGC +
+    // channel group), so that only the rounding of the product p * vs remains.
     // With three or four groups there is one piece (up = channel group); the softmax
     // denominator then sums the rounded probabilities, so that the rounding does not
     // bias the normalised weights.
